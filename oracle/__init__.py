@@ -1,0 +1,38 @@
+"""CPU oracle for the measurement-and-recovery path (test infrastructure only).
+
+Plain NumPy, fp64, one function per operation, written from the paper's
+definitions (Secs. 3, 6, 7, 8, 9).  It shares no code with the HIP library and
+must never be imported by the product path: only the test-suite, the smoke
+check and the benchmark's CPU-baseline leg call it.
+
+Pin status of each function (what ties it to something other than itself):
+
+* philox4x32_10      -- published known-answer vectors of the generator.
+* phi_entries        -- statistical tests (moments, unit column norms, nested
+                        rows); the (seed, stream, row, col) -> counter mapping
+                        is this project's own convention: parity unpinned by
+                        any external vector beyond the generator itself.
+* sketch             -- equals an explicit dense matrix-vector product;
+                        linearity; norm preservation in expectation.
+* block_omp          -- brute force over all supports, closed forms for
+                        orthonormal dictionaries, the incoherence guarantee of
+                        Prop. 1, exactness in the noiseless case (Thm. 1),
+                        sample-complexity shape of Thm. 2, library lstsq.
+* block_ffn          -- dense SwiGLU via an independent formulation, masked
+                        dense identity (Sec. 3), additivity over supports.
+* head_attn          -- full softmax attention, L=1, uniform-key closed forms.
+* top_k / joint      -- full sort, permutation invariance, k=n.
+"""
+from .philox import philox4x32_10
+from .operator import phi_entries, phi_matrix, GAUSS, RADEMACHER
+from .sketch import sketch
+from .recover import effective_matrix, block_omp
+from .ffn import block_ffn
+from .attn import head_attn
+from .joint import top_k_indices, token_proxy, joint_select
+
+__all__ = [
+    "philox4x32_10", "phi_entries", "phi_matrix", "GAUSS", "RADEMACHER",
+    "sketch", "effective_matrix", "block_omp", "block_ffn", "head_attn",
+    "top_k_indices", "token_proxy", "joint_select",
+]

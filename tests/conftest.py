@@ -1,0 +1,23 @@
+import os
+import sys
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session")
+def cs():
+    """The ctypes binding over the HIP library, with a context on cuda:0."""
+    import torch
+    from paper_2604_14156_amd import binding
+    if not torch.cuda.is_available():
+        pytest.fail("GPU test collected on a machine without a GPU")
+    ctx = binding.Context(device=0)
+    yield ctx
+    ctx.close()
