@@ -1,0 +1,183 @@
+/*
+ * cs.h -- C ABI of the measurement-and-recovery library (MI355X / gfx950).
+ *
+ * The library implements the online phase of compressed-sensing-guided sparse
+ * execution (paper Sec. 12, "online phase"): sketch the latent usage vector
+ * with a random operator, recover the active structured units by block
+ * orthogonal matching pursuit, and execute only those units (block-sparse
+ * gated FFN, head-pruned attention), plus joint token/unit selection (Sec. 6).
+ *
+ * Conventions common to every call
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    never frees or keeps it beyond the stream order of the call.
+ *  - Work is enqueued on the context's HIP stream; no call synchronises the
+ *    device.  Results are valid once the caller has synchronised that stream.
+ *  - Device pointers must be 16-byte aligned (CS_EALIGN otherwise).
+ *  - Errors are reported by return code, never by exception; arguments are
+ *    checked on the host before anything is launched.  cs_last_error() gives
+ *    a message for the last failing call on the context.
+ *  - The context owns a scratch buffer (sized at cs_create) and a cache of
+ *    per-operator plans.  The five hot calls allocate nothing once the plan
+ *    they need exists (see cs_plan).
+ */
+#ifndef CS_H_
+#define CS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cs_ctx cs_ctx;
+
+typedef enum {
+    CS_OK = 0,
+    CS_EINVAL = -1,     /* bad argument (range, shape, null pointer, unsupported combination) */
+    CS_EALIGN = -2,     /* a device pointer is not 16-byte aligned */
+    CS_EILLPOSED = -3,  /* recovery with k*rb >= m: the refit would be under-determined */
+    CS_ENOMEM = -4,     /* scratch buffer too small, or a device allocation failed */
+    CS_EHIP = -5        /* a HIP runtime call failed; text in cs_last_error */
+} cs_status;
+
+typedef enum { CS_GAUSS = 0, CS_RADEMACHER = 1 } cs_ensemble;
+typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
+
+/*
+ * Measurement operator Phi (the paper's A_t, Sec. 3 and Sec. 8): an m x n random
+ * matrix from a subgaussian ensemble.  It is never stored: entry (row, col) is a
+ * pure function of (seed, stream_id, row, col) through the Philox4x32-10 counter
+ * generator:
+ *   key = (seed & 0xffffffff, seed >> 32), counter = (col / cpc, row, stream_id, ens)
+ *   Rademacher: cpc = 128; column c reads bit (c % 32) of output word ((c % 128) / 32);
+ *               bit 0 -> +1, bit 1 -> -1.
+ *   Gaussian:   cpc = 4; p = (c % 4) / 2; u1 = (w[2p]+1)/2^32, u2 = (w[2p+1]+1)/2^32;
+ *               even columns sqrt(-2 ln u1) cos(2 pi u2), odd columns ... sin(2 pi u2).
+ *   Phi[row][col] = entry / sqrt(m).
+ * Rows do not depend on m, so a change of the measurement budget (Sec. 8.1) only
+ * adds or removes rows and rescales.
+ */
+typedef struct {
+    int32_t  ens;        /* cs_ensemble */
+    uint64_t seed;
+    uint32_t stream_id;  /* selects one operator of a bank (layer, kind) */
+    int32_t  m;          /* rows = number of measurements */
+    int32_t  n;          /* columns = length of the usage vector */
+} cs_op;
+
+/*
+ * Structured dictionary Psi (Sec. 3): block diagonal, unit g maps rb coefficients
+ * onto its b contiguous channels.  psi is a device array float[G][b][rb] whose
+ * columns within a unit are linearly independent, or NULL for the identity
+ * dictionary (then rb must equal b).  The effective sensing matrix is
+ * M = Phi Psi (Sec. 9), unit g owning columns g*rb .. g*rb+rb-1.
+ */
+typedef struct {
+    const float* psi;
+    int32_t G, b, rb;
+} cs_dict;
+
+/* Create a context bound to `device` and to `hip_stream` (a hipStream_t, may be
+ * NULL for the default stream).  scratch_bytes of device memory are allocated
+ * once and reused by every call (0 selects 64 MiB).  Calls on one context must
+ * not overlap in time.  Returns CS_EHIP / CS_ENOMEM on failure. */
+cs_status cs_create(cs_ctx** out, int device, void* hip_stream, size_t scratch_bytes);
+void cs_destroy(cs_ctx* ctx);
+const char* cs_last_error(const cs_ctx* ctx);
+/* Rebind the context to another stream (no synchronisation is performed). */
+cs_status cs_set_stream(cs_ctx* ctx, void* hip_stream);
+
+/*
+ * Build and cache the plan of (op, dict): the effective matrix M = Phi Psi, its
+ * column Gram matrix and the per-unit score weights (Sec. 9: M_t = A_t Psi, and
+ * the normalised columns used in the coherence definition).  Allocates device
+ * memory the context keeps until cs_destroy.  cs_recover_support and
+ * cs_joint_select call it implicitly on first use of an (op, dict) pair; calling
+ * it beforehand keeps allocation out of the hot loop.  The content of dict->psi
+ * is read at plan time only.
+ */
+cs_status cs_plan(cs_ctx* ctx, const cs_op* op, const cs_dict* dict);
+
+/*
+ * y = Phi z (measurement equation, Sec. 3 / Sec. 8).
+ *   z: float[B][n] in,  y: float[B][m] out.  B >= 0 (B == 0 is a no-op).
+ */
+cs_status cs_sketch(cs_ctx* ctx, const cs_op* op, const float* z, int B, float* y);
+
+/*
+ * Structured sparse recovery by block orthogonal matching pursuit over the
+ * dictionary's units (Sec. 8, "orthogonal matching pursuit over a constrained
+ * support dictionary"; support projection of Sec. 3 and Sec. 7 with the
+ * admissible family "exactly k units").  For each of the B sketches:
+ *   k rounds of { score every unselected unit; take the best (ties -> smaller
+ *   index); least-squares refit of all selected coefficients; new residual }.
+ * Score of unit g: with a dictionary, the energy of the residual in the unit's
+ * column space (for rb == 1 the squared normalised correlation of Sec. 9);
+ * with the identity dictionary, the raw block energy ||M_g^T r||^2.
+ *   y:          float[B][m] in
+ *   support:    int32[B][k] out, ascending unit indices
+ *   coef:       float[B][k*rb] out or NULL, coefficients in ascending-unit order
+ *   resid_norm: float[B] out or NULL, ||y - M_S coef||_2
+ *   margin:     float[B] out or NULL, min over rounds of (best - runner_up)/best;
+ *               a small margin means another support was nearly as good
+ * Requires 1 <= k <= G, op->n == G*b, k*rb < m (else CS_EILLPOSED).
+ * A non-finite sketch or a rank-deficient selection does not abort the call:
+ * that problem reports resid_norm = NaN and margin = 0 (the hook for reverting
+ * to a denser support, Sec. 12), and its support is still k distinct units.
+ */
+cs_status cs_recover_support(cs_ctx* ctx, const cs_op* op, const cs_dict* dict, int k,
+                             const float* y, int B,
+                             int32_t* support, float* coef, float* resid_norm, float* margin);
+
+/*
+ * Block-sparse gated (SwiGLU) feed-forward layer restricted to the support
+ * (masked execution of Sec. 3; block sparsity of Sec. 7):
+ *   out[t] = sum_{g in S_t} Wd_g ( silu(Wg_g x_t) * (Wu_g x_t) ),  silu(u) = u/(1+exp(-u)).
+ *   Wg, Wu: [G][b][d]  (unit g, channel c: one contiguous row of d inputs)
+ *   Wd:     [G][d][b]  (unit g, output row j: the b channel weights, contiguous)
+ *   x:      [T][d] in, out: [T][d] out, both of type `dtype` (float or bf16 bits)
+ *   support: int32[k] if shared != 0 (one support for all T rows: task-conditioned
+ *            prefill, Sec. 4), else int32[T][k] (token-adaptive decode, Sec. 5);
+ *            entries distinct within a row and in [0, G).  Order is irrelevant.
+ * Accumulation is in fp32; bf16 results are rounded once at the end.
+ * Requires d % 8 == 0 and b % 8 == 0.  An out-of-range support entry makes that
+ * unit contribute nothing (it is never dereferenced).
+ */
+cs_status cs_block_ffn(cs_ctx* ctx, int dtype, const void* Wg, const void* Wu, const void* Wd,
+                       int d, int G, int b, const void* x, int T,
+                       const int32_t* support, int k, int shared, void* out);
+
+/*
+ * Head-pruned single-query (decode) attention over a key/value cache: heads are
+ * the structured units (Sec. 3, Sec. 7).  For every kept head h of sequence i:
+ *   out[i][h] = softmax(q[i][h] . K[i][h][:]^T / sqrt(dh)) V[i][h][:]
+ * over all L cached positions (no mask, no positional transform); pruned heads
+ * output zeros.
+ *   q: [B][H][dh], K, V: [B][H][L][dh], out: [B][H][dh], all of type `dtype`
+ *   heads: int32[B][kh], distinct, in [0, H).
+ * Requires dh in {64, 128, 256}, L >= 1.
+ */
+cs_status cs_head_attn(cs_ctx* ctx, int dtype, const void* q, const void* K, const void* V,
+                       int B, int H, int L, int dh, const int32_t* heads, int kh, void* out);
+
+/*
+ * Joint prompt-token and unit selection (Sec. 6): from a sketch of per-token
+ * saliency and a sketch of channel usage, return the retained tokens and the
+ * channel support in one call.
+ *   tokens  = indices of the k_tok largest entries of the back-projection
+ *             p = Phi_tok^T y_tok (signed; ties -> smaller index), ascending;
+ *   support = cs_recover_support(ch_op, ch_dict, k_ch) applied to y_ch.
+ *   y_tok: float[tok_op->m], y_ch: float[ch_op->m]
+ *   tokens: int32[k_tok] out, support: int32[k_ch] out
+ *   resid_norm, margin: float[1] out or NULL (of the channel recovery)
+ * Requires 1 <= k_tok <= tok_op->n.
+ */
+cs_status cs_joint_select(cs_ctx* ctx, const cs_op* tok_op, const float* y_tok, int k_tok,
+                          const cs_op* ch_op, const cs_dict* ch_dict, const float* y_ch, int k_ch,
+                          int32_t* tokens, int32_t* support, float* resid_norm, float* margin);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CS_H_ */

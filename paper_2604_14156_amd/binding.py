@@ -1,0 +1,164 @@
+"""ctypes binding over the C ABI (include/cs.h).
+
+Argument marshalling only: every step of the path runs in the library's kernels.
+PyTorch is used for device memory (tensors own the buffers) and for the stream.
+The module raises at load time if the shared library is missing: there is no
+fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+from .buildlib import LIB_PATH
+
+CS_OK, CS_EINVAL, CS_EALIGN, CS_EILLPOSED, CS_ENOMEM, CS_EHIP = 0, -1, -2, -3, -4, -5
+CS_GAUSS, CS_RADEMACHER = 0, 1
+CS_F32, CS_BF16 = 0, 1
+
+EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
+           "cs_recover_support", "cs_block_ffn", "cs_head_attn", "cs_joint_select")
+
+
+class CsOp(ctypes.Structure):
+    _fields_ = [("ens", ctypes.c_int32), ("seed", ctypes.c_uint64), ("stream_id", ctypes.c_uint32),
+                ("m", ctypes.c_int32), ("n", ctypes.c_int32)]
+
+
+class CsDict(ctypes.Structure):
+    _fields_ = [("psi", ctypes.c_void_p), ("G", ctypes.c_int32), ("b", ctypes.c_int32), ("rb", ctypes.c_int32)]
+
+
+class CsError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("cs status %d: %s" % (status, message))
+        self.status = status
+
+
+def load_library(path=LIB_PATH):
+    if not os.path.exists(path):
+        raise ImportError("%s is missing: build it with `python -m paper_2604_14156_amd.buildlib`" % path)
+    lib = ctypes.CDLL(path)
+    vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.cs_create.argtypes = [ctypes.POINTER(vp), i32, vp, u64]
+    lib.cs_destroy.argtypes = [vp]
+    lib.cs_destroy.restype = None
+    lib.cs_last_error.argtypes = [vp]
+    lib.cs_last_error.restype = ctypes.c_char_p
+    lib.cs_set_stream.argtypes = [vp, vp]
+    lib.cs_plan.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict)]
+    lib.cs_sketch.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, vp]
+    lib.cs_recover_support.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
+    lib.cs_block_ffn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, i32, vp, i32, i32, vp]
+    lib.cs_head_attn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
+    lib.cs_joint_select.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
+                                    vp, i32, vp, vp, vp, vp]
+    for name in EXPORTS:
+        if name not in ("cs_destroy", "cs_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return CS_F32
+    if t.dtype == torch.bfloat16:
+        return CS_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def make_op(ens, seed, stream_id, m, n):
+    return CsOp(int(ens), int(seed), int(stream_id), int(m), int(n))
+
+
+def make_dict(psi, G, b, rb):
+    return CsDict(None if psi is None else psi.data_ptr(), int(G), int(b), int(rb))
+
+
+class Context:
+    """A library context on one device, bound to a torch stream."""
+
+    def __init__(self, device=0, stream=None, scratch_bytes=0):
+        self.lib = load_library()
+        self.device = torch.device("cuda", device)
+        self._h = ctypes.c_void_p()
+        sptr = None if stream is None else ctypes.c_void_p(stream.cuda_stream)
+        st = self.lib.cs_create(ctypes.byref(self._h), device, sptr, scratch_bytes)
+        if st != CS_OK:
+            raise CsError(st, "cs_create failed")
+        self._keep = []        # dictionaries referenced by cached plans stay alive
+
+    def close(self):
+        if self._h:
+            self.lib.cs_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def _check(self, st):
+        if st != CS_OK:
+            raise CsError(st, self.lib.cs_last_error(self._h).decode())
+
+    def set_stream(self, stream):
+        self._check(self.lib.cs_set_stream(self._h, None if stream is None else ctypes.c_void_p(stream.cuda_stream)))
+
+    # -- the calls of the C ABI, same names ---------------------------------
+    def cs_plan(self, op, dct, psi=None):
+        if psi is not None:
+            self._keep.append(psi)
+        self._check(self.lib.cs_plan(self._h, ctypes.byref(op), ctypes.byref(dct)))
+
+    def cs_sketch(self, op, z, y=None):
+        B = z.shape[0]
+        if y is None:
+            y = torch.empty((B, op.m), dtype=torch.float32, device=z.device)
+        self._check(self.lib.cs_sketch(self._h, ctypes.byref(op), _ptr(z), B, _ptr(y)))
+        return y
+
+    def cs_recover_support(self, op, dct, k, y, support=None, coef=None, resid=None, margin=None,
+                           want_coef=True):
+        B = y.shape[0]
+        dev = y.device
+        if support is None:
+            support = torch.empty((B, k), dtype=torch.int32, device=dev)
+        if coef is None and want_coef:
+            coef = torch.empty((B, k * dct.rb), dtype=torch.float32, device=dev)
+        if resid is None:
+            resid = torch.empty((B,), dtype=torch.float32, device=dev)
+        if margin is None:
+            margin = torch.empty((B,), dtype=torch.float32, device=dev)
+        self._check(self.lib.cs_recover_support(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
+                                                _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
+        return support, coef, resid, margin
+
+    def cs_block_ffn(self, Wg, Wu, Wd, x, support, shared, out=None):
+        G, b, d = Wg.shape
+        T = x.shape[0]
+        k = support.shape[-1]
+        if out is None:
+            out = torch.empty_like(x)
+        self._check(self.lib.cs_block_ffn(self._h, _dtype_code(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), d, G, b,
+                                          _ptr(x), T, _ptr(support), k, 1 if shared else 0, _ptr(out)))
+        return out
+
+    def cs_head_attn(self, q, K, V, heads, out=None):
+        B, H, L, dh = K.shape
+        kh = heads.shape[-1]
+        if out is None:
+            out = torch.empty_like(q)
+        self._check(self.lib.cs_head_attn(self._h, _dtype_code(q), _ptr(q), _ptr(K), _ptr(V), B, H, L, dh,
+                                          _ptr(heads), kh, _ptr(out)))
+        return out
+
+    def cs_joint_select(self, tok_op, y_tok, k_tok, ch_op, ch_dict, y_ch, k_ch):
+        dev = y_tok.device
+        tokens = torch.empty((k_tok,), dtype=torch.int32, device=dev)
+        support = torch.empty((k_ch,), dtype=torch.int32, device=dev)
+        resid = torch.empty((1,), dtype=torch.float32, device=dev)
+        margin = torch.empty((1,), dtype=torch.float32, device=dev)
+        self._check(self.lib.cs_joint_select(self._h, ctypes.byref(tok_op), _ptr(y_tok), k_tok,
+                                             ctypes.byref(ch_op), ctypes.byref(ch_dict), _ptr(y_ch), k_ch,
+                                             _ptr(tokens), _ptr(support), _ptr(resid), _ptr(margin)))
+        return tokens, support, resid, margin

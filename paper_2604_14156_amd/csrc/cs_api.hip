@@ -1,0 +1,332 @@
+// C ABI of the library: argument checking, plan cache, scratch management and
+// dispatch to the kernels.  No exception crosses this boundary.
+#include "../../include/cs.h"
+#include "kernels.hpp"
+#include <cmath>
+#include <cstdarg>
+#include <new>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace csk;
+
+struct PlanEntry {
+    cs_op op;
+    const float* psi;
+    int G, b, rb;
+    Plan plan;
+};
+
+struct cs_ctx {
+    int device;
+    hipStream_t stream;
+    void* scratch;
+    size_t scratch_bytes;
+    int lds_limit;
+    std::vector<PlanEntry> plans;
+    std::string err;
+};
+
+namespace {
+
+constexpr size_t kDefaultScratch = 64ull << 20;
+constexpr int kMaxWeightedRb = 16;
+
+cs_status fail(cs_ctx* c, cs_status st, const char* fmt, ...) {
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return st;
+}
+
+cs_status hip_fail(cs_ctx* c, hipError_t e, const char* what) {
+    return fail(c, CS_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+OpDesc make_desc(const cs_op& op) {
+    OpDesc d;
+    d.k0 = (uint32_t)(op.seed & 0xFFFFFFFFull);
+    d.k1 = (uint32_t)(op.seed >> 32);
+    d.stream = op.stream_id;
+    d.ens = op.ens;
+    d.m = op.m;
+    d.n = op.n;
+    d.scale = (float)(1.0 / std::sqrt((double)op.m));
+    return d;
+}
+
+cs_status check_op(cs_ctx* c, const cs_op* op, const char* who) {
+    if (!op) return fail(c, CS_EINVAL, "%s: operator is NULL", who);
+    if (op->ens != CS_GAUSS && op->ens != CS_RADEMACHER) return fail(c, CS_EINVAL, "%s: unknown ensemble %d", who, op->ens);
+    if (op->m < 1 || op->n < 1) return fail(c, CS_EINVAL, "%s: operator needs m >= 1 and n >= 1 (m=%d n=%d)", who, op->m, op->n);
+    return CS_OK;
+}
+
+cs_status check_dict(cs_ctx* c, const cs_op* op, const cs_dict* dict, const char* who) {
+    if (!dict) return fail(c, CS_EINVAL, "%s: dictionary is NULL", who);
+    if (dict->G < 1 || dict->b < 1 || dict->rb < 1) return fail(c, CS_EINVAL, "%s: dictionary needs G, b, rb >= 1", who);
+    if ((long long)dict->G * dict->b != op->n) return fail(c, CS_EINVAL, "%s: n (%d) != G*b (%d*%d)", who, op->n, dict->G, dict->b);
+    if (!dict->psi && dict->rb != dict->b) return fail(c, CS_EINVAL, "%s: identity dictionary needs rb == b", who);
+    if (dict->psi && dict->rb > dict->b) return fail(c, CS_EINVAL, "%s: rb > b", who);
+    if (dict->psi && dict->rb > kMaxWeightedRb) return fail(c, CS_EINVAL, "%s: rb > %d with a dictionary is not supported", who, kMaxWeightedRb);
+    if (dict->psi && !aligned16(dict->psi)) return fail(c, CS_EALIGN, "%s: psi is not 16-byte aligned", who);
+    return CS_OK;
+}
+
+cs_status bind_device(cs_ctx* c) {
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    return CS_OK;
+}
+
+cs_status find_or_build_plan(cs_ctx* c, const cs_op* op, const cs_dict* dict, const Plan** out) {
+    for (const PlanEntry& pe : c->plans) {
+        if (pe.op.ens == op->ens && pe.op.seed == op->seed && pe.op.stream_id == op->stream_id &&
+            pe.op.m == op->m && pe.op.n == op->n && pe.psi == dict->psi && pe.G == dict->G &&
+            pe.b == dict->b && pe.rb == dict->rb) {
+            *out = &pe.plan;
+            return CS_OK;
+        }
+    }
+    PlanEntry pe;
+    pe.op = *op; pe.psi = dict->psi; pe.G = dict->G; pe.b = dict->b; pe.rb = dict->rb;
+    Plan& p = pe.plan;
+    p.op = make_desc(*op);
+    p.G = dict->G; p.b = dict->b; p.rb = dict->rb;
+    p.N = dict->G * dict->rb;
+    p.weighted = dict->psi ? 1 : 0;
+    p.Mt = nullptr; p.gram = nullptr; p.W = nullptr;
+    hipError_t e;
+    if ((e = hipMalloc(&p.Mt, (size_t)p.N * op->m * sizeof(float))) != hipSuccess ||
+        (e = hipMalloc(&p.gram, (size_t)p.N * p.N * sizeof(float))) != hipSuccess ||
+        (p.weighted && (e = hipMalloc(&p.W, (size_t)p.G * p.rb * p.rb * sizeof(float))) != hipSuccess)) {
+        if (p.Mt) (void)hipFree(p.Mt);
+        if (p.gram) (void)hipFree(p.gram);
+        if (p.W) (void)hipFree(p.W);
+        (void)hipGetLastError();
+        return fail(c, CS_ENOMEM, "cs_plan: device allocation failed: %s", hipGetErrorString(e));
+    }
+    e = launch_plan_build(p, dict->psi, c->stream);
+    if (e != hipSuccess) {
+        (void)hipFree(p.Mt); (void)hipFree(p.gram);
+        if (p.W) (void)hipFree(p.W);
+        return hip_fail(c, e, "cs_plan: kernel launch");
+    }
+    c->plans.push_back(pe);
+    *out = &c->plans.back().plan;
+    return CS_OK;
+}
+
+cs_status check_recover_args(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k, const char* who) {
+    cs_status st;
+    if ((st = check_op(c, op, who)) != CS_OK) return st;
+    if ((st = check_dict(c, op, dict, who)) != CS_OK) return st;
+    if (k < 1 || k > dict->G) return fail(c, CS_EINVAL, "%s: k=%d out of range [1, G=%d]", who, k, dict->G);
+    if ((long long)k * dict->rb >= op->m)
+        return fail(c, CS_EILLPOSED, "%s: k*rb = %lld >= m = %d, the refit is under-determined", who,
+                    (long long)k * dict->rb, op->m);
+    return CS_OK;
+}
+
+cs_status run_recover(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k, const float* y, int B,
+                      int32_t* support, float* coef, float* resid, float* margin, size_t scratch_off,
+                      const char* who) {
+    const Plan* plan = nullptr;
+    cs_status st = find_or_build_plan(c, op, dict, &plan);
+    if (st != CS_OK) return st;
+    RecoverArgs a;
+    a.y = y; a.B = B; a.k = k; a.support = support; a.coef = coef; a.resid = resid; a.margin = margin;
+    a.spill_stride = recover_spill_floats(*plan, k, c->lds_limit);
+    a.spill = nullptr;
+    if (a.spill_stride) {
+        const size_t need = scratch_off + a.spill_stride * sizeof(float) * (size_t)B;
+        if (need > c->scratch_bytes)
+            return fail(c, CS_ENOMEM, "%s: needs %zu bytes of scratch, context has %zu", who, need, c->scratch_bytes);
+        a.spill = reinterpret_cast<float*>(static_cast<char*>(c->scratch) + scratch_off);
+    }
+    hipError_t e = launch_recover(*plan, a, c->lds_limit, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, who);
+    return CS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+cs_status cs_create(cs_ctx** out, int device, void* hip_stream, size_t scratch_bytes) {
+    if (!out) return CS_EINVAL;
+    *out = nullptr;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || device < 0 || device >= ndev) { (void)hipGetLastError(); return CS_EHIP; }
+    if ((e = hipSetDevice(device)) != hipSuccess) return CS_EHIP;
+    cs_ctx* c = new (std::nothrow) cs_ctx();
+    if (!c) return CS_ENOMEM;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->scratch_bytes = scratch_bytes ? scratch_bytes : kDefaultScratch;
+    c->scratch = nullptr;
+    if (hipMalloc(&c->scratch, c->scratch_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return CS_ENOMEM;
+    }
+    int lds = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess || lds <= 0)
+        lds = 64 * 1024;
+    c->lds_limit = lds;
+    *out = c;
+    return CS_OK;
+}
+
+void cs_destroy(cs_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    for (PlanEntry& pe : c->plans) {
+        if (pe.plan.Mt) (void)hipFree(pe.plan.Mt);
+        if (pe.plan.gram) (void)hipFree(pe.plan.gram);
+        if (pe.plan.W) (void)hipFree(pe.plan.W);
+    }
+    if (c->scratch) (void)hipFree(c->scratch);
+    delete c;
+}
+
+const char* cs_last_error(const cs_ctx* c) { return c ? c->err.c_str() : "no context"; }
+
+cs_status cs_set_stream(cs_ctx* c, void* hip_stream) {
+    if (!c) return CS_EINVAL;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    return CS_OK;
+}
+
+cs_status cs_plan(cs_ctx* c, const cs_op* op, const cs_dict* dict) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_op(c, op, "cs_plan")) != CS_OK) return st;
+    if ((st = check_dict(c, op, dict, "cs_plan")) != CS_OK) return st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    const Plan* plan = nullptr;
+    return find_or_build_plan(c, op, dict, &plan);
+}
+
+cs_status cs_sketch(cs_ctx* c, const cs_op* op, const float* z, int B, float* y) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_op(c, op, "cs_sketch")) != CS_OK) return st;
+    if (B < 0) return fail(c, CS_EINVAL, "cs_sketch: B < 0");
+    if (B == 0) return CS_OK;
+    if (!z || !y) return fail(c, CS_EINVAL, "cs_sketch: NULL buffer");
+    if (!aligned16(z) || !aligned16(y)) return fail(c, CS_EALIGN, "cs_sketch: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    hipError_t e = launch_sketch(make_desc(*op), z, B, y, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_sketch");
+    return CS_OK;
+}
+
+cs_status cs_recover_support(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k,
+                             const float* y, int B,
+                             int32_t* support, float* coef, float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_recover_args(c, op, dict, k, "cs_recover_support")) != CS_OK) return st;
+    if (B < 0) return fail(c, CS_EINVAL, "cs_recover_support: B < 0");
+    if (B == 0) return CS_OK;
+    if (!y || !support) return fail(c, CS_EINVAL, "cs_recover_support: NULL buffer");
+    if (!aligned16(y) || !aligned16(support) || !aligned16(coef) || !aligned16(resid_norm) || !aligned16(margin))
+        return fail(c, CS_EALIGN, "cs_recover_support: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    return run_recover(c, op, dict, k, y, B, support, coef, resid_norm, margin, 0, "cs_recover_support");
+}
+
+cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
+                       int d, int G, int b, const void* x, int T,
+                       const int32_t* support, int k, int shared, void* out) {
+    if (!c) return CS_EINVAL;
+    if (dtype != CS_F32 && dtype != CS_BF16) return fail(c, CS_EINVAL, "cs_block_ffn: unknown dtype %d", dtype);
+    if (d < 8 || (d % 8) || b < 8 || (b % 8) || G < 1) return fail(c, CS_EINVAL, "cs_block_ffn: need d %% 8 == 0, b %% 8 == 0, G >= 1");
+    if (k < 0 || k > G) return fail(c, CS_EINVAL, "cs_block_ffn: k=%d out of range [0, G=%d]", k, G);
+    if (T < 0 || T > 65535) return fail(c, CS_EINVAL, "cs_block_ffn: T=%d out of range [0, 65535]", T);
+    if (T == 0) return CS_OK;
+    if (!Wg || !Wu || !Wd || !x || !out || (k > 0 && !support)) return fail(c, CS_EINVAL, "cs_block_ffn: NULL buffer");
+    if (!aligned16(Wg) || !aligned16(Wu) || !aligned16(Wd) || !aligned16(x) || !aligned16(out) || !aligned16(support))
+        return fail(c, CS_EALIGN, "cs_block_ffn: buffer not 16-byte aligned");
+    cs_status st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    const size_t esz = dtype == CS_F32 ? 4 : 2;
+    if (k == 0) {
+        hipError_t e = launch_zero_fill(out, (size_t)T * d * esz, c->stream);
+        if (e != hipSuccess) return hip_fail(c, e, "cs_block_ffn");
+        return CS_OK;
+    }
+    FfnArgs a;
+    a.dtype = dtype; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.d = d; a.G = G; a.b = b;
+    a.x = x; a.T = T; a.support = support; a.k = k; a.shared = shared ? 1 : 0; a.out = out;
+    a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes;
+    const size_t need = ffn_scratch_bytes(a);
+    if (need > c->scratch_bytes)
+        return fail(c, CS_ENOMEM, "cs_block_ffn: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);
+    hipError_t e = launch_block_ffn(a, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_block_ffn");
+    return CS_OK;
+}
+
+cs_status cs_head_attn(cs_ctx* c, int dtype, const void* q, const void* K, const void* V,
+                       int B, int H, int L, int dh, const int32_t* heads, int kh, void* out) {
+    if (!c) return CS_EINVAL;
+    if (dtype != CS_F32 && dtype != CS_BF16) return fail(c, CS_EINVAL, "cs_head_attn: unknown dtype %d", dtype);
+    if (dh != 64 && dh != 128 && dh != 256) return fail(c, CS_EINVAL, "cs_head_attn: dh must be 64, 128 or 256");
+    if (H < 1 || L < 1) return fail(c, CS_EINVAL, "cs_head_attn: need H >= 1 and L >= 1");
+    if (kh < 0 || kh > H) return fail(c, CS_EINVAL, "cs_head_attn: kh=%d out of range [0, H=%d]", kh, H);
+    if (B < 0 || B > 65535 || H > 65535) return fail(c, CS_EINVAL, "cs_head_attn: B or H out of range");
+    if (B == 0) return CS_OK;
+    if (!q || !K || !V || !out || (kh > 0 && !heads)) return fail(c, CS_EINVAL, "cs_head_attn: NULL buffer");
+    if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || !aligned16(heads))
+        return fail(c, CS_EALIGN, "cs_head_attn: buffer not 16-byte aligned");
+    cs_status st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    AttnArgs a;
+    a.dtype = dtype; a.q = q; a.K = K; a.V = V; a.B = B; a.H = H; a.L = L; a.dh = dh;
+    a.heads = heads; a.kh = kh; a.out = out; a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes;
+    const size_t need = attn_scratch_bytes(a);
+    if (need > c->scratch_bytes)
+        return fail(c, CS_ENOMEM, "cs_head_attn: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);
+    hipError_t e = launch_head_attn(a, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_head_attn");
+    return CS_OK;
+}
+
+cs_status cs_joint_select(cs_ctx* c, const cs_op* tok_op, const float* y_tok, int k_tok,
+                          const cs_op* ch_op, const cs_dict* ch_dict, const float* y_ch, int k_ch,
+                          int32_t* tokens, int32_t* support, float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_op(c, tok_op, "cs_joint_select(tokens)")) != CS_OK) return st;
+    if (k_tok < 1 || k_tok > tok_op->n) return fail(c, CS_EINVAL, "cs_joint_select: k_tok=%d out of range [1, n=%d]", k_tok, tok_op->n);
+    if ((st = check_recover_args(c, ch_op, ch_dict, k_ch, "cs_joint_select(channels)")) != CS_OK) return st;
+    if (!y_tok || !y_ch || !tokens || !support) return fail(c, CS_EINVAL, "cs_joint_select: NULL buffer");
+    if (!aligned16(y_tok) || !aligned16(y_ch) || !aligned16(tokens) || !aligned16(support) ||
+        !aligned16(resid_norm) || !aligned16(margin))
+        return fail(c, CS_EALIGN, "cs_joint_select: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    const size_t proxy_bytes = (((size_t)tok_op->n * sizeof(float)) + 255) & ~(size_t)255;
+    if (proxy_bytes > c->scratch_bytes)
+        return fail(c, CS_ENOMEM, "cs_joint_select: needs %zu bytes of scratch, context has %zu", proxy_bytes, c->scratch_bytes);
+    float* proxy = reinterpret_cast<float*>(c->scratch);
+    hipError_t e = launch_backproject(make_desc(*tok_op), y_tok, proxy, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select: back-projection");
+    e = launch_topk(proxy, tok_op->n, k_tok, tokens, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select: top-k");
+    return run_recover(c, ch_op, ch_dict, k_ch, y_ch, 1, support, nullptr, resid_norm, margin, proxy_bytes,
+                       "cs_joint_select: recovery");
+}
+
+}  // extern "C"

@@ -1,0 +1,60 @@
+// Host-callable launchers of the HIP kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "common.hpp"
+
+namespace csk {
+
+// y[B][m] = Phi z[B][n]
+hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s);
+
+// Plan of an (operator, dictionary) pair, all device memory owned by the context.
+struct Plan {
+    OpDesc op;
+    int G, b, rb;
+    int N;                // number of atoms = G*rb
+    int weighted;         // 1: per-unit triangular weights (dictionary given), 0: raw energy
+    float* Mt;            // [N][m]  atoms, contiguous per atom
+    float* gram;          // [N][N]
+    float* W;             // [G][rb][rb] lower-triangular score weights (weighted only)
+};
+hipError_t launch_plan_build(const Plan& p, const float* psi, hipStream_t s);
+
+struct RecoverArgs {
+    const float* y; int B; int k;
+    int32_t* support; float* coef; float* resid; float* margin;
+    float* spill;         // global workspace for the running factor if it does not fit in LDS
+    size_t spill_stride;  // floats per problem
+};
+// bytes of global spill workspace needed per problem (0 if everything fits in LDS)
+size_t recover_spill_floats(const Plan& p, int k, int lds_limit);
+hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hipStream_t s);
+
+// p[n] = Phi^T y (back-projection), then top-k.
+hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s);
+hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s);
+
+// zero `bytes` bytes (a multiple of 4) with a kernel, so that the call can be captured in a graph
+hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s);
+
+struct FfnArgs {
+    int dtype;            // 0 f32, 1 bf16
+    const void *Wg, *Wu, *Wd; int d, G, b;
+    const void* x; int T; const int32_t* support; int k; int shared;
+    void* out;
+    void* scratch; size_t scratch_bytes;
+};
+size_t ffn_scratch_bytes(const FfnArgs& a);
+hipError_t launch_block_ffn(const FfnArgs& a, hipStream_t s);
+
+struct AttnArgs {
+    int dtype;
+    const void *q, *K, *V; int B, H, L, dh;
+    const int32_t* heads; int kh; void* out;
+    void* scratch; size_t scratch_bytes;
+};
+size_t attn_scratch_bytes(const AttnArgs& a);
+hipError_t launch_head_attn(const AttnArgs& a, hipStream_t s);
+
+}  // namespace csk

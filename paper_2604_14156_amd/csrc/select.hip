@@ -1,0 +1,128 @@
+// Token side of the joint selection (paper Sec. 6): back-projection of the token
+// sketch, p = Phi^T y, and selection of the k largest entries (ties -> smaller
+// index) returned in ascending index order.
+#include "kernels.hpp"
+
+namespace csk {
+
+// One thread per column (Rademacher) or per group of four columns (Gaussian);
+// rows are visited in ascending order.
+__global__ void backproject_kernel(OpDesc op, const float* __restrict__ y, float* __restrict__ p) {
+    extern __shared__ float ys[];
+    for (int i = threadIdx.x; i < op.m; i += blockDim.x) ys[i] = y[i];
+    __syncthreads();
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (op.ens == 1) {
+        if (t >= op.n) return;
+        const uint32_t cg = (uint32_t)t >> 7, word = ((uint32_t)t & 127u) >> 5, bit = (uint32_t)t & 31u;
+        float acc = 0.f;
+        for (int i = 0; i < op.m; ++i) {
+            const u32x4 b = rademacher_bits(op, (uint32_t)i, cg);
+            const uint32_t sgn = ((b.w[word] >> bit) & 1u) << 31;
+            acc += __uint_as_float(__float_as_uint(ys[i]) ^ sgn);
+        }
+        p[t] = acc * op.scale;
+    } else {
+        const int c0 = t * 4;
+        if (c0 >= op.n) return;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < op.m; ++i) {
+            float e[4];
+            gauss4(op, (uint32_t)i, (uint32_t)t, e);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] += e[j] * ys[i];
+        }
+        for (int j = 0; j < 4 && c0 + j < op.n; ++j) p[c0 + j] = acc[j] * op.scale;
+    }
+}
+
+hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s) {
+    const int items = op.ens == 1 ? op.n : (op.n + 3) / 4;
+    const int block = 64;                    // many small workgroups: the row loop is long
+    hipLaunchKernelGGL(backproject_kernel, dim3((items + block - 1) / block), dim3(block),
+                       (size_t)op.m * sizeof(float), s, op, y, p);
+    return hipGetLastError();
+}
+
+// order-preserving map float -> uint32 (larger float <=> larger key)
+__device__ __forceinline__ uint32_t float_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0u;            // -0 and +0 compare equal
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int TK_THREADS = 1024;
+
+// Radix select of the k-th largest key (four 8-bit passes), then an order-keeping
+// compaction: everything above the threshold, plus the first `need` entries equal
+// to it.  One workgroup; the scores are re-read from L2 in every pass.
+__global__ __launch_bounds__(TK_THREADS)
+void topk_kernel(const float* __restrict__ scores, int n, int k, int32_t* __restrict__ out) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh_prefix, sh_need;
+    __shared__ uint32_t wsum_gt[TK_THREADS / 64], wsum_eq[TK_THREADS / 64];
+    __shared__ uint32_t base_gt, base_eq;
+    const int tid = threadIdx.x;
+
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += TK_THREADS) {
+            const uint32_t key = float_key(scores[i]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t left = need;
+            int bin = 255;
+            for (; bin > 0; --bin) {
+                if (hist[bin] >= left) break;
+                left -= hist[bin];
+            }
+            sh_prefix = prefix | ((uint32_t)bin << shift);
+            sh_need = left;                 // how many are still wanted inside this bin
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    const uint32_t thr = prefix;            // key of the k-th largest; `need` equal keys are kept
+
+    if (tid == 0) { base_gt = 0; base_eq = 0; }
+    __syncthreads();
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int i0 = 0; i0 < n; i0 += TK_THREADS) {
+        const int i = i0 + tid;
+        uint32_t key = 0;
+        bool gt = false, eq = false;
+        if (i < n) { key = float_key(scores[i]); gt = key > thr; eq = key == thr; }
+        const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        const uint32_t lgt = __popcll(bgt & below), leq = __popcll(beq & below);
+        if (lane == 0) { wsum_gt[wave] = __popcll(bgt); wsum_eq[wave] = __popcll(beq); }
+        __syncthreads();
+        uint32_t ogt = base_gt, oeq = base_eq;
+        for (int w = 0; w < wave; ++w) { ogt += wsum_gt[w]; oeq += wsum_eq[w]; }
+        const uint32_t gt_before = ogt + lgt, eq_before = oeq + leq;
+        if (gt) out[gt_before + min(eq_before, need)] = i;
+        else if (eq && eq_before < need) out[gt_before + eq_before] = i;
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t a = 0, b = 0;
+            for (int w = 0; w < TK_THREADS / 64; ++w) { a += wsum_gt[w]; b += wsum_eq[w]; }
+            base_gt += a; base_eq += b;
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s) {
+    hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(TK_THREADS), 0, s, scores, n, k, out);
+    return hipGetLastError();
+}
+
+}  // namespace csk

@@ -1,0 +1,138 @@
+"""GPU parity: block-sparse FFN and head-pruned attention against the CPU oracle,
+through the C ABI.  Tolerances: fp32 layers 1e-5, bf16 layers 2e-2 (relative L2
+error of each output row against the unrounded fp64 oracle)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_14156_amd import binding, workloads as wl
+from gpu_util import dev_w, dev_bf16, dev_i32, host, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _ffn_case(cs, seed, G, b, d, k, T, dtype, shared, std):
+    rng = wl.rng_for(seed)
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, G, b, d, std, dtype)
+    x = wl.make_tokens(rng, T, d, dtype)
+    sup = wl.random_supports(rng, G, k, 1)[0] if shared else wl.random_supports(rng, G, k, T)
+    for t in range(0 if shared else T):            # supports need not be sorted
+        rng.shuffle(sup[t])
+    out = host(cs.cs_block_ffn(dev_w(Wg, dtype), dev_w(Wu, dtype), dev_w(Wd, dtype), dev_w(x, dtype),
+                               dev_i32(sup), shared))
+    want = oracle.block_ffn(Wg, Wu, Wd, x, sup)
+    for t in range(T):
+        assert rel_err(out[t], want[t]) <= TOL[dtype], (t, rel_err(out[t], want[t]))
+
+
+def test_ffn_tiny_planted_config(cs):
+    c = wl.CFG1
+    _ffn_case(cs, 1000, c.G, c.b, c.d, c.k, 1, "f32", False, c.wstd)
+
+
+@pytest.mark.parametrize("T,shared", [(1, False), (5, False), (8, False), (16, False), (19, False), (7, True), (1, True)])
+def test_ffn_bf16_small_shapes(cs, T, shared):
+    _ffn_case(cs, 1100 + T, 10, 64, 512, 3, T, "bf16", shared, 0.05)
+
+
+@pytest.mark.parametrize("T", [1, 3])
+def test_ffn_f32_ragged_shapes(cs, T):
+    _ffn_case(cs, 1200 + T, 7, 24, 136, 7, T, "f32", False, 0.1)     # k == G: the dense layer
+
+
+def test_ffn_bf16_block_of_32_channels(cs):
+    _ffn_case(cs, 1300, 12, 32, 256, 5, 4, "bf16", False, 0.05)
+
+
+def test_ffn_empty_cases(cs):
+    rng = wl.rng_for(1400)
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, 4, 64, 128, 0.05, "bf16")
+    x = wl.make_tokens(rng, 3, 128, "bf16")
+    dW = [dev_bf16(w) for w in (Wg, Wu, Wd)]
+    out = cs.cs_block_ffn(*dW, dev_bf16(x), torch.empty((3, 0), dtype=torch.int32, device="cuda:0"), False)
+    assert float(out.float().abs().max()) == 0.0                       # empty support: zeros
+    out = cs.cs_block_ffn(*dW, dev_bf16(x[:0]), dev_i32(np.zeros((0, 2))), False)
+    assert out.shape == (0, 128)
+    # an out-of-range unit contributes nothing
+    sup = np.array([[1, 99], [2, -1], [0, 3]], dtype=np.int32)
+    got = host(cs.cs_block_ffn(*dW, dev_bf16(x), dev_i32(sup), False))
+    want = np.stack([oracle.block_ffn(Wg, Wu, Wd, x[t:t + 1], [g for g in sup[t] if 0 <= g < 4])[0] for t in range(3)])
+    for t in range(3):
+        assert rel_err(got[t], want[t]) <= 2e-2
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_block_ffn(*dW, dev_bf16(x), dev_i32(np.zeros((3, 5))), False)    # k > G
+    assert e.value.status == binding.CS_EINVAL
+
+
+def _full_size_ffn(cs, B, seed):
+    """Decode shape at full size: weights drawn on the device, oracle on sampled tokens."""
+    c = wl.CFG2
+    gen = torch.Generator(device="cuda:0").manual_seed(seed)
+    Wg, Wu = (torch.randn((c.G, c.b, c.d), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16) for _ in range(2))
+    Wd = torch.randn((c.G, c.d, c.b), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16)
+    x = torch.randn((B, c.d), generator=gen, device="cuda:0").to(torch.bfloat16)
+    sup = wl.random_supports(wl.rng_for(seed), c.G, c.k, B)
+    out = host(cs.cs_block_ffn(Wg, Wu, Wd, x, dev_i32(sup), False))
+    hWg, hWu, hWd, hx = host(Wg), host(Wu), host(Wd), host(x)
+    for t in sorted(set([0, B // 2, B - 1])):
+        want = oracle.block_ffn(hWg, hWu, hWd, hx[t:t + 1], sup[t])[0]
+        assert rel_err(out[t], want) <= 2e-2, (t, rel_err(out[t], want))
+
+
+@pytest.mark.parametrize("B", [1, 8, 16, 64])
+def test_ffn_decode_shape_full_size(cs, B):
+    _full_size_ffn(cs, B, 2000 + B)
+
+
+def _attn_case(cs, seed, B, H, L, dh, kh):
+    rng = wl.rng_for(seed)
+    q, K, V = wl.make_kv(rng, B, H, L, dh)
+    heads = wl.random_supports(rng, H, kh, B)
+    out = host(cs.cs_head_attn(dev_bf16(q), dev_bf16(K), dev_bf16(V), dev_i32(heads)))
+    want = oracle.head_attn(q, K, V, heads)
+    for b in range(B):
+        kept = set(heads[b].tolist())
+        for h in range(H):
+            if h in kept:
+                assert rel_err(out[b, h], want[b, h]) <= 2e-2, (b, h)
+            else:
+                assert np.all(out[b, h] == 0.0)
+
+
+@pytest.mark.parametrize("B,H,L,dh,kh", [(2, 4, 300, 128, 2), (1, 3, 1, 128, 3), (3, 8, 1000, 64, 3),
+                                         (2, 2, 77, 256, 1), (1, 32, 4096, 128, 12), (2, 4, 130, 128, 0)])
+def test_attention_small_and_ragged(cs, B, H, L, dh, kh):
+    _attn_case(cs, 3000 + L + dh, B, H, L, dh, kh)
+
+
+def test_attention_decode_shape_full_size(cs):
+    hs = wl.CFG3_HEADS
+    B = 16
+    gen = torch.Generator(device="cuda:0").manual_seed(31)
+    q = torch.randn((B, hs.H, hs.dh), generator=gen, device="cuda:0").to(torch.bfloat16)
+    K = torch.randn((B, hs.H, hs.L, hs.dh), generator=gen, device="cuda:0").to(torch.bfloat16)
+    V = torch.randn((B, hs.H, hs.L, hs.dh), generator=gen, device="cuda:0").to(torch.bfloat16)
+    heads = wl.random_supports(wl.rng_for(31), hs.H, hs.kh, B)
+    out = host(cs.cs_head_attn(q, K, V, dev_i32(heads)))
+    hq = host(q)
+    for b in (0, 7, 15):
+        for h in (int(heads[b][0]), int(heads[b][-1])):
+            want = oracle.head_attn(hq[b:b + 1, h:h + 1], host(K[b:b + 1, h:h + 1]), host(V[b:b + 1, h:h + 1]),
+                                    np.array([[0]]))[0, 0]
+            assert rel_err(out[b, h], want) <= 2e-2
+        pruned = sorted(set(range(hs.H)) - set(heads[b].tolist()))
+        assert np.all(out[b, pruned] == 0.0)
+
+
+def test_attention_sharp_scores_do_not_overflow(cs):
+    rng = wl.rng_for(3500)
+    q, K, V = wl.make_kv(rng, 1, 2, 200, 128)
+    q = wl.round_bf16(q * 8.0)                    # scores of order +-100
+    heads = np.array([[0, 1]], dtype=np.int32)
+    out = host(cs.cs_head_attn(dev_bf16(q), dev_bf16(K), dev_bf16(V), dev_i32(heads)))
+    want = oracle.head_attn(q, K, V, heads)
+    assert np.all(np.isfinite(out))
+    for h in range(2):
+        assert rel_err(out[0, h], want[0, h]) <= 2e-2

@@ -1,0 +1,291 @@
+"""GPU parity: sketch, recovery and joint selection against the CPU oracle,
+through the C ABI.  Tolerances: supports bit-exact when the oracle's selection
+margin exceeds 1e-3; ||r_gpu - r_oracle|| <= 1e-5 ||y||; sketches within 1e-5."""
+import math
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_14156_amd import binding, workloads as wl
+from gpu_util import dev_f32, dev_i32, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-3
+RES_TOL = 1e-5
+
+
+@pytest.mark.parametrize("ens", [wl.GAUSS, wl.RADEMACHER])
+@pytest.mark.parametrize("m,n,B", [(64, 1024, 1), (256, 11008, 3), (33, 1001, 9), (16, 32, 16), (5, 130, 2)])
+def test_sketch_matches_oracle(cs, ens, m, n, B):
+    rng = wl.rng_for(10 * m + n + B)
+    z = rng.standard_normal((B, n)).astype(np.float32)
+    op = binding.make_op(ens, 0xABCDEF0123456789, 7, m, n)
+    y = host(cs.cs_sketch(op, dev_f32(z)))
+    want = oracle.sketch(ens, 0xABCDEF0123456789, 7, m, z)
+    assert y.shape == (B, m)
+    for t in range(B):
+        assert rel_err(y[t], want[t]) <= 1e-5
+
+
+def test_sketch_full_size_prefill_operator(cs):
+    c = wl.CFG4
+    rng = wl.rng_for(4000)
+    z = rng.standard_normal((1, c.n)).astype(np.float32)
+    op = binding.make_op(c.ens, 4000, 0, c.m, c.n)
+    y = host(cs.cs_sketch(op, dev_f32(z)))
+    assert rel_err(y[0], oracle.sketch(c.ens, 4000, 0, c.m, z[0])) <= 1e-5
+
+
+def test_sketch_empty_batch_and_errors(cs):
+    op = binding.make_op(wl.GAUSS, 1, 0, 8, 64)
+    z = torch.empty((0, 64), dtype=torch.float32, device="cuda:0")
+    assert cs.cs_sketch(op, z).shape == (0, 8)
+    bad = binding.make_op(5, 1, 0, 8, 64)
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_sketch(bad, dev_f32(np.zeros((1, 64))))
+    assert e.value.status == binding.CS_EINVAL
+    zz = dev_f32(np.zeros((1, 68)))
+    with pytest.raises(binding.CsError) as e:                 # misaligned view
+        cs.cs_sketch(op, zz[:, 1:65])
+    assert e.value.status == binding.CS_EALIGN
+
+
+def _check_recovery(cs, op, dct, psi_dev, M, Y, G, rb, k, normalised):
+    """Y: [B, m] fp32 values fed to both sides."""
+    B = Y.shape[0]
+    if psi_dev is not None:
+        cs.cs_plan(op, dct, psi_dev)
+    sup, coef, resid, margin = cs.cs_recover_support(op, dct, k, dev_f32(Y))
+    sup, coef, resid, margin = host(sup), host(coef), host(resid), host(margin)
+    exact = 0
+    for t in range(B):
+        y = Y[t].astype(np.float64)
+        rec = oracle.block_omp(M, y, G, rb, k, normalised)
+        s = sup[t]
+        assert len(set(s.tolist())) == k and np.all(np.diff(s) > 0) and s.min() >= 0 and s.max() < G
+        ynorm = np.linalg.norm(y)
+        cols = np.concatenate([np.arange(g * rb, (g + 1) * rb) for g in s])
+        ls, *_ = np.linalg.lstsq(M[:, cols], y, rcond=None)
+        own = np.linalg.norm(y - M[:, cols] @ ls)
+        # whatever was selected, the reported residual and coefficients are its least-squares fit
+        assert abs(resid[t] - own) <= RES_TOL * ynorm
+        assert np.linalg.norm(coef[t] - ls) <= 1e-4 * max(np.linalg.norm(ls), 1e-30)
+        if rec["margin"] > MARGIN:
+            assert list(s) == list(rec["support"]), (t, rec["margin"])
+            assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm
+            assert abs(margin[t] - rec["margin"]) <= 1e-3
+            exact += 1
+    return exact
+
+
+@pytest.mark.parametrize("seed", [1000, 1001, 1002, 1003])
+def test_tiny_planted_instance_end_to_end(cs, seed):
+    c = wl.CFG1
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 1, c.amp, c.bg)
+    noise = (c.noise * rng.standard_normal((1, c.m))).astype(np.float32)
+    op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    y_gpu = cs.cs_sketch(op, dev_f32(z)) + dev_f32(noise)
+    sup, coef, resid, margin = cs.cs_recover_support(op, dct, c.k, y_gpu)
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    y_or = oracle.sketch(c.ens, seed, 0, c.m, z[0]) + noise[0]
+    rec = oracle.block_omp(M, y_or, c.G, 1, c.k, True)
+    assert rec["margin"] > MARGIN
+    assert list(host(sup)[0]) == list(rec["support"]) == list(S[0])
+    assert abs(host(resid)[0] - rec["resid_norm"]) <= RES_TOL * np.linalg.norm(y_or)
+    assert np.allclose(host(coef)[0], rec["coef"], rtol=1e-4)
+
+
+def test_decode_shape_batch(cs):
+    c = wl.CFG2
+    seed = 2000
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 6, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 4, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 4, c.m, c.n, c.G, c.b, 1, psi)
+    Y = oracle.sketch(c.ens, seed, 4, c.m, z).astype(np.float32)
+    exact = _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True)
+    assert exact >= 3          # most instances clear the margin filter
+    # end to end: the GPU's own sketch leads to the same supports where the margin allows
+    y_gpu = cs.cs_sketch(op, dev_f32(z))
+    sup = host(cs.cs_recover_support(op, dct, c.k, y_gpu)[0])
+    for t in range(6):
+        rec = oracle.block_omp(M, Y[t].astype(np.float64), c.G, 1, c.k, True)
+        if rec["margin"] > MARGIN:
+            assert list(sup[t]) == list(rec["support"])
+
+
+def test_literal_entrywise_usage_still_matches_oracle(cs):
+    c = wl.CFG2
+    seed = 2100
+    rng = wl.rng_for(seed)
+    _, psi = wl.make_profiles(rng, c.G, c.b)
+    z, _ = wl.plant_usage_literal(rng, c.G, c.b, c.k, 3, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    Y = oracle.sketch(c.ens, seed, 0, c.m, z).astype(np.float32)
+    _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True)
+
+
+def test_head_selection_shape(cs):
+    hs = wl.CFG3_HEADS
+    seed = 3000
+    rng = wl.rng_for(seed)
+    u, S = wl.plant_head_usage(rng, hs, 16)
+    op = binding.make_op(hs.ens, seed, 3, hs.m, hs.H)
+    dct = binding.make_dict(None, hs.H, 1, 1)
+    M = oracle.effective_matrix(hs.ens, seed, 3, hs.m, hs.H, hs.H, 1, 1, None)
+    Y = oracle.sketch(hs.ens, seed, 3, hs.m, u).astype(np.float32)
+    exact = _check_recovery(cs, op, dct, None, M, Y, hs.H, 1, hs.kh, False)
+    assert exact >= 10
+
+
+def test_prefill_shape_uses_the_spill_path(cs):
+    c = wl.CFG4
+    seed = 4000
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 1, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    Y = oracle.sketch(c.ens, seed, 0, c.m, z).astype(np.float32)
+    _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True)
+
+
+def test_textbook_block_mode_identity_dictionary(cs):
+    G, b, k, m = 32, 4, 3, 48
+    seed = 5000
+    rng = wl.rng_for(seed)
+    op = binding.make_op(wl.GAUSS, seed, 1, m, G * b)
+    dct = binding.make_dict(None, G, b, b)
+    M = oracle.effective_matrix(wl.GAUSS, seed, 1, m, G * b, G, b, b, None)
+    Y = []
+    for _ in range(5):
+        S = np.sort(rng.choice(G, size=k, replace=False))
+        z = np.zeros(G * b)
+        for g in S:
+            z[g * b:(g + 1) * b] = rng.standard_normal(b) + 3.0
+        Y.append(M @ z + 1e-3 * rng.standard_normal(m))
+    Y = np.array(Y, dtype=np.float32)
+    assert _check_recovery(cs, op, dct, None, M, Y, G, b, k, False) >= 4
+
+
+def test_rank_two_units_with_dictionary(cs):
+    G, b, rb, k, m = 20, 8, 2, 4, 40
+    seed = 5100
+    rng = wl.rng_for(seed)
+    psi = np.linalg.qr(rng.standard_normal((G, b, rb)))[0].astype(np.float32)
+    # skew the two atoms of each unit so that raw and projected energies differ
+    psi[:, :, 1] = 0.3 * psi[:, :, 1] + 0.9 * psi[:, :, 0]
+    op = binding.make_op(wl.RADEMACHER, seed, 2, m, G * b)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, G, b, rb)
+    M = oracle.effective_matrix(wl.RADEMACHER, seed, 2, m, G * b, G, b, rb, psi)
+    Y = []
+    for _ in range(5):
+        alpha = np.zeros(G * rb)
+        for g in rng.choice(G, size=k, replace=False):
+            alpha[g * rb:(g + 1) * rb] = rng.standard_normal(rb) * 3.0
+        Y.append(M @ alpha + 1e-2 * rng.standard_normal(m))
+    Y = np.array(Y, dtype=np.float32)
+    assert _check_recovery(cs, op, dct, psi_dev, M, Y, G, rb, k, True) >= 3
+
+
+def test_recovery_degenerate_and_error_paths(cs):
+    c = wl.CFG1
+    op = binding.make_op(c.ens, 77, 0, c.m, c.n)
+    rng = wl.rng_for(77)
+    _, psi = wl.make_profiles(rng, c.G, c.b)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    # all-zero sketch: every score ties at zero -> lowest indices, margin 0, residual 0
+    sup, coef, resid, margin = cs.cs_recover_support(op, dct, c.k, dev_f32(np.zeros((1, c.m))))
+    assert list(host(sup)[0]) == [0, 1, 2, 3] and host(margin)[0] == 0.0 and host(resid)[0] == 0.0
+    # non-finite sketch: flagged, support still a valid k-set
+    bad = np.zeros((2, c.m), dtype=np.float32)
+    bad[0, 3] = np.nan
+    bad[1] = rng.standard_normal(c.m)
+    sup, coef, resid, margin = cs.cs_recover_support(op, dct, c.k, dev_f32(bad))
+    s0 = host(sup)[0]
+    assert len(set(s0.tolist())) == c.k and math.isnan(host(resid)[0]) and host(margin)[0] == 0.0
+    assert not math.isnan(host(resid)[1])
+    # k = G: everything is selected
+    small = binding.make_op(wl.GAUSS, 5, 0, 40, 8)
+    d8 = binding.make_dict(None, 8, 1, 1)
+    sup = host(cs.cs_recover_support(small, d8, 8, dev_f32(rng.standard_normal((1, 40))))[0])
+    assert list(sup[0]) == list(range(8))
+    # argument errors
+    for k, status in ((0, binding.CS_EINVAL), (c.G + 1, binding.CS_EINVAL)):
+        with pytest.raises(binding.CsError) as e:
+            cs.cs_recover_support(op, dct, k, dev_f32(np.zeros((1, c.m))))
+        assert e.value.status == status
+    tight = binding.make_op(c.ens, 77, 0, 4, c.n)
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support(tight, dct, 4, dev_f32(np.zeros((1, 4))))
+    assert e.value.status == binding.CS_EILLPOSED
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support(op, binding.make_dict(psi_dev, c.G + 1, c.b, 1), 2, dev_f32(np.zeros((1, c.m))))
+    assert e.value.status == binding.CS_EINVAL
+
+
+def test_joint_selection_prompt_shape(cs):
+    t = wl.CFG5_TOK
+    c = wl.CFG2
+    seed = 5200
+    rng = wl.rng_for(seed)
+    sal, mask = wl.plant_saliency(rng, t["n_tok"], t["p_active"])
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 1, c.amp, c.bg)
+    tok_op = binding.make_op(t["ens"], seed, 9, t["m_tok"], t["n_tok"])
+    ch_op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    y_tok = cs.cs_sketch(tok_op, dev_f32(sal[None, :]))
+    y_ch = cs.cs_sketch(ch_op, dev_f32(z))
+    tokens, support, resid, margin = cs.cs_joint_select(tok_op, y_tok[0], t["k_tok"], ch_op, dct, y_ch[0], c.k)
+    tokens, support = host(tokens), host(support)
+    # oracle on the same (GPU-produced, fp32) sketches
+    yt, yc = host(y_tok)[0], host(y_ch)[0]
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    otok, rec, p = oracle.joint_select((t["ens"], seed, 9, t["m_tok"], t["n_tok"]), yt, t["k_tok"],
+                                       M, yc, c.G, 1, c.k, True)
+    assert tokens.shape == (t["k_tok"],) and np.all(np.diff(tokens) > 0)
+    # tokens: identical except for scores within rounding distance of the cut
+    srt = np.sort(p)[::-1]
+    cut = 0.5 * (srt[t["k_tok"] - 1] + srt[t["k_tok"]])
+    tol = 1e-5 * np.linalg.norm(yt)
+    sure_in = set(np.nonzero(p > cut + tol)[0].tolist())
+    sure_out = set(np.nonzero(p < cut - tol)[0].tolist())
+    got = set(tokens.tolist())
+    assert sure_in <= got and not (got & sure_out)
+    if srt[t["k_tok"] - 1] - srt[t["k_tok"]] > 2 * tol:
+        assert list(tokens) == list(otok)
+    if rec["margin"] > MARGIN:
+        assert list(support) == list(rec["support"])
+        assert abs(host(resid)[0] - rec["resid_norm"]) <= RES_TOL * np.linalg.norm(yc)
+
+
+def test_top_k_ties_and_small_cases(cs):
+    # Rademacher back-projection of a one-hot sketch gives +-c: massive ties, lower index wins
+    n, m = 300, 8
+    op = binding.make_op(wl.RADEMACHER, 3, 0, m, n)
+    y = np.zeros(m, dtype=np.float32); y[2] = 1.0
+    ch_op = binding.make_op(wl.GAUSS, 5, 0, 40, 8)
+    d8 = binding.make_dict(None, 8, 1, 1)
+    y_ch = dev_f32(wl.rng_for(1).standard_normal(40))
+    for k_tok in (1, 7, 150, 300):
+        tokens = host(cs.cs_joint_select(op, dev_f32(y), k_tok, ch_op, d8, y_ch, 2)[0])
+        p = oracle.token_proxy(wl.RADEMACHER, 3, 0, m, n, y)
+        assert list(tokens) == list(oracle.top_k_indices(p, k_tok))
