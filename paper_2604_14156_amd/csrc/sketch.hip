@@ -50,7 +50,8 @@ void sketch_rademacher_kernel(OpDesc op, const float* __restrict__ z, int B, flo
                     }
                 }
             } else {
-                for (int c = cw; c < op.n; ++c) {
+                const int cend = min(cw + 32, op.n);
+                for (int c = cw; c < cend; ++c) {
                     const uint32_t bit = (word >> (c - cw)) & 1u;
                     for (int t = 0; t < nt; ++t) {
                         const float v = z[(size_t)(t0 + t) * op.n + c];
