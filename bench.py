@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the measurement-and-recovery decode step on one MI355X.
+
+A step is one pass of the whole path over one batch: for each of the 32 layers of
+a 7B-shaped decoder, sketch the head-usage and channel-usage vectors, recover the
+head and channel-block supports, run head-pruned attention over the KV cache and
+the block-sparse SwiGLU FFN on the recovered supports.  All inputs are synthetic
+and seeded, resident in HBM before the timed region.
+
+Prints one JSON line (see --help for the knobs).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--batch", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the single-layer side measurements")
+    return ap.parse_args()
+
+
+class DecodeState:
+    """Weights, caches, dictionaries and per-step planted inputs of the decode workload."""
+
+    def __init__(self, ctx, wl, binding, layers, B, nsteps, seed=3000):
+        dev = "cuda:0"
+        c, hs = wl.CFG2, wl.CFG3_HEADS
+        self.c, self.hs, self.B, self.layers = c, hs, B, layers
+        gen = torch.Generator(device=dev).manual_seed(seed)
+        bf = torch.bfloat16
+
+        def randn(shape, std=1.0, dtype=bf):
+            t = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32 if dtype != bf else bf)
+            return t.mul_(std) if std != 1.0 else t
+
+        self.Wg = [randn((c.G, c.b, c.d), c.wstd) for _ in range(layers)]
+        self.Wu = [randn((c.G, c.b, c.d), c.wstd) for _ in range(layers)]
+        self.Wd = [randn((c.G, c.d, c.b), c.wstd) for _ in range(layers)]
+        self.K = [randn((B, hs.H, hs.L, hs.dh)) for _ in range(layers)]
+        self.V = [randn((B, hs.H, hs.L, hs.dh)) for _ in range(layers)]
+        # dictionaries: one unit-norm profile per channel block and layer
+        self.pi = torch.randn((layers, c.G, c.b), generator=gen, device=dev)
+        self.psi = [(self.pi[l] / self.pi[l].norm(dim=1, keepdim=True)).reshape(c.G, c.b, 1).contiguous()
+                    for l in range(layers)]
+        self.ffn_op = [binding.make_op(c.ens, seed, 2 * l, c.m, c.n) for l in range(layers)]
+        self.head_op = [binding.make_op(hs.ens, seed, 2 * l + 1, hs.m, hs.H) for l in range(layers)]
+        self.ffn_dict = [binding.make_dict(self.psi[l], c.G, c.b, 1) for l in range(layers)]
+        self.head_dict = binding.make_dict(None, hs.H, 1, 1)
+        for l in range(layers):
+            ctx.cs_plan(self.ffn_op[l], self.ffn_dict[l], self.psi[l])
+            ctx.cs_plan(self.head_op[l], self.head_dict)
+        # per-step planted inputs (fresh every step)
+        self.z, self.u, self.x, self.q, self.S_true = [], [], [], [], []
+        for _ in range(nsteps):
+            zs, us = [], []
+            for l in range(layers):
+                # k active blocks per token with Laplace magnitudes, plus dense background
+                perm = torch.rand((B, c.G), generator=gen, device=dev).argsort(dim=1)[:, :c.k]
+                amp = torch.zeros((B, c.G), device=dev)
+                e = -torch.log(torch.rand((B, c.k), generator=gen, device=dev).clamp_min(1e-12))
+                sgn = torch.where(torch.rand((B, c.k), generator=gen, device=dev) < 0.5, -1.0, 1.0)
+                amp.scatter_(1, perm, e * sgn)
+                z = (amp[:, :, None] * self.pi[l][None]).reshape(B, c.n)
+                z += c.bg * torch.randn((B, c.n), generator=gen, device=dev)
+                zs.append(z.contiguous())
+                hperm = torch.rand((B, hs.H), generator=gen, device=dev).argsort(dim=1)[:, :hs.kh]
+                u = hs.bg * torch.randn((B, hs.H), generator=gen, device=dev)
+                u.scatter_add_(1, hperm, torch.randn((B, hs.kh), generator=gen, device=dev))
+                us.append(u.contiguous())
+            self.z.append(zs)
+            self.u.append(us)
+            self.x.append(randn((layers, B, c.d)))
+            self.q.append(randn((layers, B, hs.H, hs.dh)))
+        # outputs and intermediates, allocated once
+        self.y = torch.empty((B, c.m), device=dev)
+        self.yh = torch.empty((B, hs.m), device=dev)
+        self.S = torch.empty((B, c.k), dtype=torch.int32, device=dev)
+        self.heads = torch.empty((B, hs.kh), dtype=torch.int32, device=dev)
+        self.resid = torch.empty((B,), device=dev)
+        self.margin = torch.empty((B,), device=dev)
+        self.residh = torch.empty((B,), device=dev)
+        self.marginh = torch.empty((B,), device=dev)
+        self.o = torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf)
+        self.out = torch.empty((B, c.d), device=dev, dtype=bf)
+
+
+def decode_step(ctx, st, i, ev=None):
+    """One decode step over all layers.  ev: optional dict of event lists for per-call timing."""
+    c, hs = st.c, st.hs
+    for l in range(st.layers):
+        def timed(name, fn):
+            if ev is None:
+                return fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ev[name].append((a, b))
+        timed("sketch", lambda: ctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh))
+        timed("recover", lambda: ctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh, st.heads,
+                                                        None, st.residh, st.marginh, want_coef=False))
+        timed("attn", lambda: ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads, st.o))
+        timed("sketch", lambda: ctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y))
+        timed("recover", lambda: ctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y, st.S,
+                                                        None, st.resid, st.margin, want_coef=False))
+        timed("ffn", lambda: ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S, False, st.out))
+
+
+def union_blocks(S, G):
+    return int(torch.unique(S).numel())
+
+
+def cpu_baseline(wl, layers_sample=2, B=16, seed=3000):
+    """The CPU oracle on a bounded sample of the same workload: `layers_sample` layers of one step."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    c, hs = wl.CFG2, wl.CFG3_HEADS
+    rng = wl.rng_for(seed)
+    # inputs and plan-time products (not timed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, c.G, c.b, c.d, c.wstd, "bf16")
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    Mh = oracle.effective_matrix(hs.ens, seed, 1, hs.m, hs.H, hs.H, 1, 1, None)
+    # the cache is materialised for kh heads only: the oracle touches kept heads alone, so the
+    # recovered head set is relabelled 0..kh-1 (same arithmetic, 12/32 of the host memory)
+    q, K, V = wl.make_kv(rng, B, hs.kh, hs.L, hs.dh)
+    compact = np.tile(np.arange(hs.kh), (B, 1))
+    t_total = 0.0
+    for _ in range(layers_sample):
+        z, _ = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
+        u, _ = wl.plant_head_usage(rng, hs, B)
+        x = wl.make_tokens(rng, B, c.d, "bf16")
+        t0 = time.perf_counter()
+        yh = oracle.sketch(hs.ens, seed, 1, hs.m, u)
+        heads = np.stack([oracle.block_omp(Mh, yh[t], hs.H, 1, hs.kh, False)["support"] for t in range(B)])
+        assert heads.shape == compact.shape
+        oracle.head_attn(q, K, V, compact)
+        y = oracle.sketch(c.ens, seed, 0, c.m, z)
+        S = np.stack([oracle.block_omp(M, y[t], c.G, 1, c.k, True)["support"] for t in range(B)])
+        oracle.block_ffn(Wg, Wu, Wd, x, S)
+        t_total += time.perf_counter() - t0
+    per_layer = t_total / layers_sample
+    return {"value": B / (per_layer * 32), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d of 32 layers of one decode step at batch %d (%.1f s), scaled to 32 layers"
+                      % (layers_sample, B, t_total)}
+
+
+def time_loop(fn, iters, stream):
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for i in range(iters):
+        fn(i)
+    b.record(stream)
+    b.synchronize()
+    return a.elapsed_time(b) / iters          # ms per iteration
+
+
+def extra_measurements(ctx, st, wl, stream):
+    """Single-layer side figures: FFN at batch 1/8/64 on rotating layers, recovery and sketch per call."""
+    c, hs = st.c, st.hs
+    dev = "cuda:0"
+    res = {}
+    nl = st.layers
+    gen = torch.Generator(device=dev).manual_seed(77)
+    for B in (1, 8, 64):
+        sup = [torch.rand((B, c.G), generator=gen, device=dev).argsort(dim=1)[:, :c.k].to(torch.int32).contiguous()
+               for _ in range(nl)]
+        x = torch.randn((B, c.d), generator=gen, device=dev).to(torch.bfloat16)
+        out = torch.empty_like(x)
+        fn = lambda i: ctx.cs_block_ffn(st.Wg[i % nl], st.Wu[i % nl], st.Wd[i % nl], x, sup[i % nl], False, out)
+        time_loop(fn, nl, stream)
+        ms = time_loop(fn, 2 * nl, stream)
+        blocks = float(np.mean([union_blocks(s, c.G) for s in sup]))
+        bytes_active = blocks * 3 * c.b * c.d * 2
+        res["ffn_B%d" % B] = {"us": ms * 1e3, "active_MB": bytes_active / 1e6,
+                              "GBs": bytes_active / (ms * 1e-3) / 1e9,
+                              "hbm_frac": bytes_active / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "tokens_per_s_layer": B / (ms * 1e-3)}
+    B = st.B
+    fn = lambda i: ctx.cs_recover_support(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, st.S, None,
+                                          st.resid, st.margin, want_coef=False)
+    ctx.cs_sketch(st.ffn_op[0], st.z[0][0], st.y)
+    time_loop(fn, nl, stream)
+    res["recover_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
+    fn = lambda i: ctx.cs_recover_support(st.head_op[i % nl], st.head_dict, hs.kh, st.yh, st.heads, None,
+                                          st.residh, st.marginh, want_coef=False)
+    ctx.cs_sketch(st.head_op[0], st.u[0][0], st.yh)
+    time_loop(fn, nl, stream)
+    res["recover_heads_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
+    fn = lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y)
+    time_loop(fn, nl, stream)
+    res["sketch_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
+    return res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    from paper_2604_14156_amd import binding, workloads as wl
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU and the HIP library; there is no CPU fallback")
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    ctx = binding.Context(device=0, stream=stream)
+    nsteps = args.steps + args.warmup
+    with torch.cuda.stream(stream):
+        st = DecodeState(ctx, wl, binding, args.layers, args.batch, nsteps)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            decode_step(ctx, st, i)
+        torch.cuda.synchronize()
+        # --- timed region: exactly `steps` steps, no per-call events
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            decode_step(ctx, st, args.warmup + i)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        # --- the same steps again with HIP events around every call (per-call durations)
+        ev = {"sketch": [], "recover": [], "attn": [], "ffn": []}
+        unions = []
+        for i in range(args.steps):
+            decode_step(ctx, st, args.warmup + i, ev)
+        torch.cuda.synchronize()
+        per = {k: sum(a.elapsed_time(b) for a, b in v) / max(len(v), 1) for k, v in ev.items()}   # ms per call
+        # active bytes per call
+        c, hs = st.c, st.hs
+        attn_bytes = args.batch * hs.kh * 2 * hs.L * hs.dh * 2
+        # union of the supports of the last call stands for all (same distribution)
+        ctx.cs_sketch(st.ffn_op[0], st.z[0][0], st.y)
+        ctx.cs_recover_support(st.ffn_op[0], st.ffn_dict[0], c.k, st.y, st.S, None, st.resid, st.margin, want_coef=False)
+        torch.cuda.synchronize()
+        margin_pass = float((st.margin > 1e-3).float().mean())
+        ffn_bytes = union_blocks(st.S, c.G) * 3 * c.b * c.d * 2
+        extra = None if args.no_extra else extra_measurements(ctx, st, wl, stream)
+        torch.cuda.synchronize()
+
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = args.batch / (wall / args.steps)
+    calls_per_step = {"sketch": 2 * args.layers, "recover": 2 * args.layers, "attn": args.layers, "ffn": args.layers}
+    step_share = {k: per[k] * calls_per_step[k] for k in per}
+    kernels = {
+        "attn": {"us_per_call": per["attn"] * 1e3, "active_MB": attn_bytes / 1e6,
+                 "GBs": attn_bytes / (per["attn"] * 1e-3) / 1e9},
+        "ffn": {"us_per_call": per["ffn"] * 1e3, "active_MB": ffn_bytes / 1e6,
+                "GBs": ffn_bytes / (per["ffn"] * 1e-3) / 1e9},
+        "recover": {"us_per_call": per["recover"] * 1e3},
+        "sketch": {"us_per_call": per["sketch"] * 1e3},
+    }
+    dom = "attn" if step_share["attn"] >= step_share["ffn"] else "ffn"
+    achieved = kernels[dom]["GBs"]
+    rec_frac = step_share["recover"] / sum(step_share.values())
+    result = {
+        "metric": "decode tokens/s + HBM GB/s on active blocks; recovery us/token (7B-shaped)",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 3: full 7B-shaped decode step, %d layers, batch %d, KV length %d, "
+                               "supports re-recovered every token" % (args.layers, args.batch, hs.L),
+                   "global_batch": args.batch, "layers": args.layers, "kv_len": hs.L,
+                   "ffn_blocks_kept": "%d/%d" % (c.k, c.G), "heads_kept": "%d/%d" % (hs.kh, hs.H)},
+        "roofline": {"bound": "hbm", "kernel": "cs_head_attn" if dom == "attn" else "cs_block_ffn",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+        "kernels": kernels,
+        "recovery": {"us_per_token": step_share["recover"] * 1e3 / args.batch,
+                     "frac_of_step_serial": rec_frac, "margin_pass_rate": margin_pass},
+        "step_breakdown_ms": step_share,
+    }
+    if extra is not None:
+        result["single_layer"] = extra
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, B=args.batch)
+    ctx.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -30,8 +30,9 @@ RADEMACHER = 1
 # ----------------------------------------------------------------------------
 def to_bf16_bits(a):
     """float array -> uint16 bf16 bit patterns, round-to-nearest-even."""
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    rounded = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    # finite inputs only: the 32-bit add cannot wrap below the largest finite float
+    rounded = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
     return rounded.astype(np.uint16)
 
 
@@ -159,20 +160,20 @@ def plant_saliency(rng, n_tok, p_active):
 def make_ffn_weights(rng, G, b, d, std, dtype):
     """Wg, Wu as [G, b, d]; Wd as [G, d, b]; values representable in `dtype`."""
     def draw(shape):
-        w = (std * rng.standard_normal(shape)).astype(np.float32)
+        w = rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
         return round_bf16(w) if dtype == "bf16" else w
     return draw((G, b, d)), draw((G, b, d)), draw((G, d, b))
 
 
 def make_tokens(rng, T, d, dtype):
-    x = rng.standard_normal((T, d)).astype(np.float32)
+    x = rng.standard_normal((T, d), dtype=np.float32)
     return round_bf16(x) if dtype == "bf16" else x
 
 
 def make_kv(rng, B, H, L, dh):
-    q = round_bf16(rng.standard_normal((B, H, dh)))
-    K = round_bf16(rng.standard_normal((B, H, L, dh)))
-    V = round_bf16(rng.standard_normal((B, H, L, dh)))
+    q = round_bf16(rng.standard_normal((B, H, dh), dtype=np.float32))
+    K = round_bf16(rng.standard_normal((B, H, L, dh), dtype=np.float32))
+    V = round_bf16(rng.standard_normal((B, H, L, dh), dtype=np.float32))
     return q, K, V
 
 
