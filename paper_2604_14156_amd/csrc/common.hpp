@@ -99,24 +99,43 @@ __device__ __forceinline__ float load1(const float* p) { return *p; }
 __device__ __forceinline__ float load1(const uint16_t* p) { return bf16_to_f32(*p); }
 
 // ---------------------------------------------------------------------------
-// wavefront reductions (64 lanes)
+// wavefront reductions (64 lanes) on the data-parallel-primitive lane crossbar:
+// each step is one VALU instruction that reads a permuted copy of a register.
+// A row is 16 lanes.  Steps: swap within pairs, swap pairs within quads, mirror
+// within half rows, mirror within rows; afterwards every lane of a row holds the
+// row's result, and the four rows are combined through scalar lane reads.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+#define CS_DPP_QUAD_SWAP1 0xB1      /* quad_perm [1,0,3,2] */
+#define CS_DPP_QUAD_SWAP2 0x4E      /* quad_perm [2,3,0,1] */
+#define CS_DPP_HALF_MIRROR 0x141
+#define CS_DPP_ROW_MIRROR 0x140
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+__device__ __forceinline__ float readlane_f32(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
-// sum over aligned groups of `width` lanes (width a power of two <= 64)
+
+// sum over aligned groups of WIDTH lanes (WIDTH in {2,4,8,16,32,64}); every lane gets the result
 template <int WIDTH>
 __device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-    for (int off = WIDTH / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (WIDTH >= 2) v += dpp_f32<CS_DPP_QUAD_SWAP1>(v);
+    if (WIDTH >= 4) v += dpp_f32<CS_DPP_QUAD_SWAP2>(v);
+    if (WIDTH >= 8) v += dpp_f32<CS_DPP_HALF_MIRROR>(v);
+    if (WIDTH >= 16) v += dpp_f32<CS_DPP_ROW_MIRROR>(v);
+    if (WIDTH == 32) v += __shfl_xor(v, 16, 64);
+    if (WIDTH == 64) v = (readlane_f32(v, 0) + readlane_f32(v, 16)) + (readlane_f32(v, 32) + readlane_f32(v, 48));
     return v;
+}
+__device__ __forceinline__ float wave_sum(float v) { return group_sum<64>(v); }
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_f32<CS_DPP_QUAD_SWAP1>(v));
+    v = fmaxf(v, dpp_f32<CS_DPP_QUAD_SWAP2>(v));
+    v = fmaxf(v, dpp_f32<CS_DPP_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_f32<CS_DPP_ROW_MIRROR>(v));
+    return fmaxf(fmaxf(readlane_f32(v, 0), readlane_f32(v, 16)), fmaxf(readlane_f32(v, 32), readlane_f32(v, 48)));
 }
 
 }  // namespace csk

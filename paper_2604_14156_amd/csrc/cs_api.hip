@@ -104,12 +104,14 @@ cs_status find_or_build_plan(cs_ctx* c, const cs_op* op, const cs_dict* dict, co
     p.G = dict->G; p.b = dict->b; p.rb = dict->rb;
     p.N = dict->G * dict->rb;
     p.weighted = dict->psi ? 1 : 0;
-    p.Mt = nullptr; p.gram = nullptr; p.W = nullptr;
+    p.Mt = nullptr; p.Mr = nullptr; p.gram = nullptr; p.W = nullptr;
     hipError_t e;
     if ((e = hipMalloc(&p.Mt, (size_t)p.N * op->m * sizeof(float))) != hipSuccess ||
+        (e = hipMalloc(&p.Mr, (size_t)p.N * op->m * sizeof(float))) != hipSuccess ||
         (e = hipMalloc(&p.gram, (size_t)p.N * p.N * sizeof(float))) != hipSuccess ||
         (p.weighted && (e = hipMalloc(&p.W, (size_t)p.G * p.rb * p.rb * sizeof(float))) != hipSuccess)) {
         if (p.Mt) (void)hipFree(p.Mt);
+        if (p.Mr) (void)hipFree(p.Mr);
         if (p.gram) (void)hipFree(p.gram);
         if (p.W) (void)hipFree(p.W);
         (void)hipGetLastError();
@@ -117,7 +119,7 @@ cs_status find_or_build_plan(cs_ctx* c, const cs_op* op, const cs_dict* dict, co
     }
     e = launch_plan_build(p, dict->psi, c->stream);
     if (e != hipSuccess) {
-        (void)hipFree(p.Mt); (void)hipFree(p.gram);
+        (void)hipFree(p.Mt); (void)hipFree(p.Mr); (void)hipFree(p.gram);
         if (p.W) (void)hipFree(p.W);
         return hip_fail(c, e, "cs_plan: kernel launch");
     }
@@ -193,6 +195,7 @@ void cs_destroy(cs_ctx* c) {
     (void)hipSetDevice(c->device);
     for (PlanEntry& pe : c->plans) {
         if (pe.plan.Mt) (void)hipFree(pe.plan.Mt);
+        if (pe.plan.Mr) (void)hipFree(pe.plan.Mr);
         if (pe.plan.gram) (void)hipFree(pe.plan.gram);
         if (pe.plan.W) (void)hipFree(pe.plan.W);
     }

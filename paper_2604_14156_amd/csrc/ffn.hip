@@ -84,6 +84,213 @@ static hipError_t run_generic(const FfnArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Decode path, bf16, up to 16 tokens per launch (token-adaptive supports, Sec. 5).
+//
+// The layer is bandwidth bound: every active weight block must be read once, and
+// the arithmetic per byte is tiny.  The matrix cores are used only because they
+// consume a 16-byte weight fragment per lane without any unpacking, which keeps
+// the vector ALUs out of the way of the loads; the 16-token operand is padded with
+// zero rows.
+//
+// gate/up kernel: a workgroup of 16 waves walks over (active block, 8-channel
+//   chunk) items.  Wave w owns the input columns of k-steps w, w+16, ... (32
+//   columns each) and keeps that slice of all 16 token rows in registers for the
+//   whole kernel; per item it streams the matching slice of 8 gate rows and 8 up
+//   rows (one 16x16 tile), and the 16 partial tiles are summed through LDS.
+//   The loads of the next item are issued before the current tile is reduced.
+// down kernel: a workgroup owns 16 output columns; its waves split the active
+//   blocks, each multiplying the block's [16 x b] slice of Wd (one contiguous
+//   run of 16 rows) with the block's hidden values, then the waves are summed.
+// Hidden values travel between the two kernels as bf16 in [G][16][b] order,
+// already masked by "token t uses block g".
+// ---------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+constexpr int FD_WAVES = 16;
+constexpr int FD_THREADS = FD_WAVES * 64;
+constexpr int FD_MAXG = 1024;
+
+__device__ __forceinline__ bf16x8_t load_frag(const uint16_t* p) {
+    return *reinterpret_cast<const bf16x8_t*>(p);
+}
+__device__ __forceinline__ bf16x8_t zero_frag() {
+    const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+    return *reinterpret_cast<const bf16x8_t*>(&z);
+}
+
+// Token masks per block and the compacted list of blocks used by at least one token.
+// mask[g] bit t = token t lists block g.  Returns the number of listed blocks.
+__device__ __forceinline__ int build_block_list(const int32_t* __restrict__ support, int T, int k, int shared, int G,
+                                                uint32_t* mask, uint16_t* ulist, int* wcount) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int g = tid; g < G; g += FD_THREADS) mask[g] = 0u;
+    __syncthreads();
+    const int total = shared ? k : T * k;
+    const uint32_t allbits = T >= 32 ? 0xFFFFFFFFu : ((1u << T) - 1u);
+    for (int i = tid; i < total; i += FD_THREADS) {
+        const int g = support[i];
+        if (g >= 0 && g < G) atomicOr(&mask[g], shared ? allbits : (1u << (i / k)));
+    }
+    __syncthreads();
+    // ordered compaction, 64 blocks per wave
+    const int g = wave * 64 + lane;
+    const bool used = g < G && mask[g] != 0u;
+    const unsigned long long bal = __ballot(used);
+    if (lane == 0) wcount[wave] = __popcll(bal);
+    __syncthreads();
+    int off = 0, tot = 0;
+    for (int w = 0; w < FD_WAVES; ++w) { const int c = wcount[w]; if (w < wave) off += c; tot += c; }
+    if (used) ulist[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)g;
+    __syncthreads();
+    return tot;
+}
+
+template <int NS>
+__global__ __launch_bounds__(FD_THREADS)
+void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
+                     const uint16_t* __restrict__ x, int T, const int32_t* __restrict__ support, int k, int shared,
+                     uint16_t* __restrict__ hbuf) {
+    __shared__ uint32_t mask[FD_MAXG];
+    __shared__ uint16_t ulist[FD_MAXG];
+    __shared__ int wcount[FD_WAVES];
+    __shared__ float red[2][FD_WAVES][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblocks = build_block_list(support, T, k, shared, G, mask, ulist, wcount);
+    const int cpb = b >> 3;                           // 8-channel chunks per block
+    const int nitems = nblocks * cpb;
+    const int ln = lane & 15, kg = lane >> 4;         // tile column / row index, k-group
+
+    // this wave's slice of the token rows, kept in registers
+    bf16x8_t xa[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int kk = (wave + FD_WAVES * s) * 32;
+        xa[s] = (kk < d && ln < T) ? load_frag(x + (size_t)ln * d + kk + kg * 8) : zero_frag();
+    }
+    auto row_ptr = [&](int item) -> const uint16_t* {
+        const int g = ulist[item / cpb], cc = item % cpb;
+        const uint16_t* base = ln < 8 ? Wg : Wu;
+        return base + ((size_t)g * b + cc * 8 + (ln & 7)) * d + kg * 8;
+    };
+    bf16x8_t wb[NS], wn[NS];
+    int item = blockIdx.x;
+    if (item < nitems) {
+        const uint16_t* rp = row_ptr(item);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int kk = (wave + FD_WAVES * s) * 32;
+            wb[s] = kk < d ? load_frag(rp + kk) : zero_frag();
+        }
+    }
+    int buf = 0;
+    for (; item < nitems; item += gridDim.x) {
+        const int next = item + gridDim.x;
+        if (next < nitems) {
+            const uint16_t* rp = row_ptr(next);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int kk = (wave + FD_WAVES * s) * 32;
+                wn[s] = kk < d ? load_frag(rp + kk) : zero_frag();
+            }
+        }
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[s], wb[s], acc, 0, 0, 0);
+        *reinterpret_cast<f32x4_t*>(&red[buf][wave][lane * 4]) = acc;
+        __syncthreads();
+        // element e = lane*4 + i of a tile is (token 4*(lane/16)+i, column lane%16);
+        // columns 0-7 are gate channels, 8-15 the matching up channels (32 elements further)
+        if (tid < 256) {
+            const int col = (tid >> 2) & 15;
+            if (col < 8) {
+                float sg = 0.f, su = 0.f;
+#pragma unroll
+                for (int w = 0; w < FD_WAVES; ++w) { sg += red[buf][w][tid]; su += red[buf][w][tid + 32]; }
+                const int tok = 4 * (tid >> 6) + (tid & 3);
+                const int g = ulist[item / cpb], cc = item % cpb;
+                const float hv = ((mask[g] >> tok) & 1u) ? sg / (1.0f + __expf(-sg)) * su : 0.f;
+                hbuf[((size_t)g * 16 + tok) * b + cc * 8 + col] = f32_to_bf16(hv);
+            }
+        }
+        buf ^= 1;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) wb[s] = wn[s];
+    }
+}
+
+__global__ __launch_bounds__(FD_THREADS)
+void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
+                   int T, const int32_t* __restrict__ support, int k, int shared, uint16_t* __restrict__ out) {
+    __shared__ uint32_t mask[FD_MAXG];
+    __shared__ uint16_t ulist[FD_MAXG];
+    __shared__ int wcount[FD_WAVES];
+    __shared__ float red[FD_WAVES][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblocks = build_block_list(support, T, k, shared, G, mask, ulist, wcount);
+    const int ln = lane & 15, kg = lane >> 4;
+    const int col0 = blockIdx.x * 16;
+    const bool row_ok = col0 + ln < d;
+    const int ksteps = b >> 5;                        // 32 channels per matrix instruction
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int UB = 4;                             // blocks in flight per wave
+    for (int u0 = wave; u0 < nblocks; u0 += FD_WAVES * UB) {
+        for (int ks = 0; ks < ksteps; ks += 2) {
+            bf16x8_t wa[UB][2], hb[UB][2];
+#pragma unroll
+            for (int q = 0; q < UB; ++q) {
+                const int u = u0 + q * FD_WAVES;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const bool ok = u < nblocks && ks + e < ksteps;
+                    const int g = ok ? ulist[u] : 0;
+                    const int ch = (ks + e) * 32 + kg * 8;
+                    wa[q][e] = (ok && row_ok) ? load_frag(Wd + ((size_t)g * d + col0 + ln) * b + ch) : zero_frag();
+                    hb[q][e] = ok ? load_frag(hbuf + ((size_t)g * 16 + ln) * b + ch) : zero_frag();
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < UB; ++q)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[q][e], hb[q][e], acc, 0, 0, 0);
+        }
+    }
+    *reinterpret_cast<f32x4_t*>(&red[wave][lane * 4]) = acc;
+    __syncthreads();
+    // element e = lane*4 + i is (output column 4*(lane/16)+i, token lane%16)
+    if (tid < 256) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < FD_WAVES; ++w) s += red[w][tid];
+        const int col = col0 + 4 * (tid >> 6) + (tid & 3), tok = (tid >> 2) & 15;
+        if (tok < T && col < d) out[(size_t)tok * d + col] = f32_to_bf16(s);
+    }
+}
+
+static bool mfma_decode_ok(const FfnArgs& a) {
+    return a.dtype == 1 && a.T <= 16 && a.G <= FD_MAXG && (a.d % 32) == 0 && (a.b % 32) == 0 &&
+           (a.d / 32 + FD_WAVES - 1) / FD_WAVES <= 16;
+}
+
+static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
+    uint16_t* hbuf = reinterpret_cast<uint16_t*>(a.scratch);
+    const int ns = (a.d / 32 + FD_WAVES - 1) / FD_WAVES;
+    const int cpb = a.b / 8;
+    const int union_max = a.shared ? a.k : (a.T * a.k < a.G ? a.T * a.k : a.G);
+    int grid = union_max * cpb;
+    if (grid > 256) grid = 256;                       // one workgroup of 16 waves per compute unit
+    if (grid < 1) grid = 1;
+#define CS_GU(NSV) hipLaunchKernelGGL((ffn_gateup_mfma<NSV>), dim3(grid), dim3(FD_THREADS), 0, s, \
+        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf)
+    if (ns <= 1) CS_GU(1); else if (ns <= 2) CS_GU(2); else if (ns <= 4) CS_GU(4); else if (ns <= 8) CS_GU(8); else CS_GU(16);
+#undef CS_GU
+    hipLaunchKernelGGL(ffn_down_mfma, dim3((a.d + 15) / 16), dim3(FD_THREADS), 0, s,
+                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, a.support, a.k, a.shared, (uint16_t*)a.out);
+    return hipGetLastError();
+}
+
 __global__ void zero_fill_kernel(uint32_t* dst, size_t words) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) dst[i] = 0u;
@@ -98,11 +305,13 @@ hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s) {
 }
 
 size_t ffn_scratch_bytes(const FfnArgs& a) {
+    if (mfma_decode_ok(a)) return (size_t)a.G * 16 * a.b * sizeof(uint16_t);
     return (size_t)a.T * a.k * a.b * sizeof(float);
 }
 
 hipError_t launch_block_ffn(const FfnArgs& a, hipStream_t s) {
     if (a.T <= 0) return hipSuccess;
+    if (mfma_decode_ok(a)) return run_mfma_decode(a, s);
     if (a.dtype == 0) return run_generic<float>(a, s);
     return run_generic<uint16_t>(a, s);
 }

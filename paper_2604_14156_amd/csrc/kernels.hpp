@@ -16,6 +16,7 @@ struct Plan {
     int N;                // number of atoms = G*rb
     int weighted;         // 1: per-unit triangular weights (dictionary given), 0: raw energy
     float* Mt;            // [N][m]  atoms, contiguous per atom
+    float* Mr;            // [m][N]  the same matrix, contiguous per measurement row
     float* gram;          // [N][N]
     float* W;             // [G][rb][rb] lower-triangular score weights (weighted only)
 };

@@ -43,6 +43,16 @@ __global__ void build_atoms_kernel(Plan p, const float* __restrict__ psi) {
     }
 }
 
+// Mr[i][c] = Mt[c][i]
+__global__ void transpose_atoms_kernel(Plan p) {
+    __shared__ float tile[16][17];
+    const int c0 = blockIdx.x * 16, i0 = blockIdx.y * 16;
+    const int ty = threadIdx.y, tx = threadIdx.x;
+    if (c0 + ty < p.N && i0 + tx < p.op.m) tile[ty][tx] = p.Mt[(size_t)(c0 + ty) * p.op.m + i0 + tx];
+    __syncthreads();
+    if (i0 + ty < p.op.m && c0 + tx < p.N) p.Mr[(size_t)(i0 + ty) * p.N + c0 + tx] = tile[tx][ty];
+}
+
 // gram[a][c] = <Mt[a], Mt[c]>
 __global__ void gram_kernel(Plan p) {
     __shared__ float ta[16][17], tc[16][17];
@@ -91,6 +101,10 @@ hipError_t launch_plan_build(const Plan& p, const float* psi, hipStream_t s) {
     {
         dim3 block(128), grid((p.op.m + 127) / 128, p.G);
         hipLaunchKernelGGL(build_atoms_kernel, grid, block, 0, s, p, psi);
+    }
+    {
+        dim3 block(16, 16), grid((p.N + 15) / 16, (p.op.m + 15) / 16);
+        hipLaunchKernelGGL(transpose_atoms_kernel, grid, block, 0, s, p);
     }
     {
         dim3 block(16, 16), grid((p.N + 15) / 16, (p.N + 15) / 16);

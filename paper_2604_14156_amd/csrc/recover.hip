@@ -48,6 +48,8 @@ static RecoverLayout make_layout(const Plan& p, int k, int lds_limit) {
     return L;
 }
 
+static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, struct FastLayout& L);
+
 size_t recover_spill_floats(const Plan& p, int k, int lds_limit) {
     const RecoverLayout L = make_layout(p, k, lds_limit);
     return L.off_D < 0 ? (size_t)k * p.rb * p.N : 0;
@@ -269,8 +271,375 @@ __global__ void recover_kernel(Plan p, RecoverArgs a, RecoverLayout L) {
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Latency-tuned kernel for one atom per unit (rb == 1) and at most 64 selected
+// units.  Thread c owns atom c: its correlation, weight and selection flag live in
+// registers and its row of the factor (d_j[c], j = 0..) in LDS.  A round costs one
+// workgroup barrier:
+//   every wave finds its best and second-best score with lane-crossbar reductions
+//   and posts (best, index, second, correlation of the best) to LDS; after the
+//   barrier every thread merges the few per-wave candidates itself, so the winner,
+//   the margin and the step length are known everywhere without another exchange;
+//   the new factor entry needs only the winner's row (broadcast reads) and the
+//   thread's own row, and the pivot is recomputed by every thread from the same
+//   broadcast values.
+// The triangular solves of the refit run inside one wavefront with scalar lane
+// broadcasts instead of barriers.
+// ---------------------------------------------------------------------------
+struct FastLayout {
+    int off_y, off_r, off_cand, off_beta, off_alpha, off_gv, off_red, off_selcol, off_Dt, off_gram;
+    int KS;               // padded row length of the factor (floats)
+    int rows;             // rows of the factor = atoms rounded up to a wavefront
+    int total_floats;
+};
+
+constexpr int RF_MAXK = 64;        // selected atoms handled by the single-wavefront solves
+constexpr int RF_THREADS = 512;
+
+static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, FastLayout& L) {
+    const int N = p.N, m = p.op.m;
+    int KS = (k + 3) & ~3;
+    if (((KS >> 2) & 1) == 0) KS += 4;        // odd number of 16-byte groups per row: conflict-free b128 reads
+    L.KS = KS;
+    L.rows = (N + 63) & ~63;
+    int o = 0;
+    L.off_y = o; o += (m + 3) & ~3;
+    L.off_r = o; o += (m + 3) & ~3;
+    L.off_cand = o; o += 2 * 16 * 4;
+    L.off_beta = o; o += RF_MAXK;
+    L.off_alpha = o; o += RF_MAXK;
+    L.off_gv = o; o += 16 * RF_MAXK;
+    L.off_red = o; o += 16;
+    L.off_selcol = o; o += RF_MAXK;
+    // the factor's storage doubles as the staging area of the initial correlation partial sums
+    int dt = L.rows * KS;
+    const int stage = nthreads * 4;
+    if (dt < stage) dt = stage;
+    L.off_Dt = o; o += dt;
+    L.off_gram = -1;
+    const long limit = lds_limit / 4 - 16;
+    if (o > limit) return false;
+    if ((long)o + (long)N * N <= limit) { L.off_gram = o; o += N * N; }
+    L.total_floats = o;
+    return true;
+}
+
+template <bool GRAM_LDS>
+__global__ __launch_bounds__(RF_THREADS)
+void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, NT = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = NT >> 6;
+    const int prob = blockIdx.x;
+    const int N = p.N, m = p.op.m, k = a.k, KS = L.KS;
+    const bool active = tid < N;
+    const int round_waves = (N + 63) >> 6;     // waves that own atoms
+
+    float* yv = lds + L.off_y;
+    float* rv = lds + L.off_r;
+    float* cand = lds + L.off_cand;            // [2][16][4]
+    float* beta = lds + L.off_beta;
+    float* alpha = lds + L.off_alpha;
+    float* gv = lds + L.off_gv;                // [16][RF_MAXK]
+    float* red = lds + L.off_red;
+    int* selcol = reinterpret_cast<int*>(lds + L.off_selcol);
+    float* Dt = lds + L.off_Dt;                // [rows][KS], row c = factor entries of atom c
+    float* gl = lds + L.off_gram;
+
+    // ---- bulk loads, many in flight per thread: the Gram matrix into LDS, the sketch
+    if (GRAM_LDS) {
+        const int n4 = (N * N) >> 2;
+        const float4* src = reinterpret_cast<const float4*>(p.gram);
+        float4* dst = reinterpret_cast<float4*>(gl);
+        constexpr int U = 8;
+        for (int base = 0; base < n4; base += NT * U) {
+            float4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * NT + tid;
+                if (idx < n4) r[u] = src[idx];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * NT + tid;
+                if (idx < n4) dst[idx] = r[u];
+            }
+        }
+        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gl[i] = p.gram[i];
+    }
+    const float* y = a.y + (size_t)prob * m;
+    int bad = 0;
+    for (int i = tid; i < m; i += NT) {
+        const float v = y[i];
+        yv[i] = v;
+        if (!isfinite(v)) bad = 1;
+    }
+    bad = __syncthreads_or(bad);
+
+    // ---- c = M^T y from the row-major copy of M.  A thread takes a group of four
+    // adjacent atoms and a slice of the measurement rows; slices are summed through LDS.
+    float corr = 0.f;
+    {
+        float* stage = Dt;                              // [parts][N]
+        if ((N & 3) == 0) {
+            const int ncg = N >> 2;
+            const int parts = NT / ncg > 0 ? NT / ncg : 1;
+            const int cg = tid % ncg, part = tid / ncg;
+            const int rows_per = (m + parts - 1) / parts;
+            if (part < parts) {
+                const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                const float4* mr = reinterpret_cast<const float4*>(p.Mr) + cg;
+                constexpr int U = 8;
+                for (int ib = i0; ib < i1; ib += U) {
+                    float4 r[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (ib + u < i1) r[u] = mr[(size_t)(ib + u) * ncg];
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (ib + u < i1) {
+                            const float yy = yv[ib + u];
+                            acc.x += r[u].x * yy; acc.y += r[u].y * yy; acc.z += r[u].z * yy; acc.w += r[u].w * yy;
+                        }
+                }
+                reinterpret_cast<float4*>(stage)[part * ncg + cg] = acc;
+            }
+            __syncthreads();
+            if (active) for (int q = 0; q < parts; ++q) corr += stage[q * N + tid];
+        } else {
+            const int parts = NT / N > 0 ? NT / N : 1;
+            const int c = tid % N, part = tid / N;
+            const int rows_per = (m + parts - 1) / parts;
+            if (part < parts) {
+                const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
+                float acc = 0.f;
+#pragma unroll 8
+                for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + c] * yv[i];
+                stage[part * N + c] = acc;
+            }
+            __syncthreads();
+            if (active) for (int q = 0; q < parts; ++q) corr += stage[q * N + tid];
+        }
+        __syncthreads();                                // the staging area becomes the factor
+    }
+    const float w = (active && p.weighted) ? p.W[tid] : 1.f;
+    bool selected = false;
+    float margin = 1.f;
+    float* myrow = Dt + (size_t)(tid < L.rows ? tid : 0) * KS;
+
+    for (int J = 0; J < k; ++J) {
+        if (wave < round_waves) {
+            float score = -1.f;
+            if (active && !selected) {
+                const float t = w * corr;
+                score = t * t;
+                if (!(score >= 0.f)) score = 0.f;        // NaN scores tie at zero
+            }
+            const float m1 = wave_max(score);
+            const unsigned long long hit = __ballot(score == m1);
+            const int l1 = __ffsll((long long)hit) - 1;
+            const float c1 = readlane_f32(corr, l1);
+            const float m2 = wave_max(lane == l1 ? -2.f : score);
+            float* cd = cand + ((J & 1) * 16 + wave) * 4;
+            if (lane == 0) { cd[0] = m1; cd[1] = __int_as_float(wave * 64 + l1); cd[2] = m2; cd[3] = c1; }
+        }
+        __syncthreads();
+        if (wave < round_waves) {
+            const float* cb = cand + (J & 1) * 16 * 4;
+            float s1 = cb[0], s2 = cb[2], ccol = cb[3];
+            int gstar = __float_as_int(cb[1]);
+            for (int wv = 1; wv < round_waves; ++wv) {
+                const float o1 = cb[wv * 4];
+                if (o1 > s1) {                            // ties keep the lower wave = lower index
+                    s2 = fmaxf(fmaxf(s2, s1), cb[wv * 4 + 2]);
+                    s1 = o1; gstar = __float_as_int(cb[wv * 4 + 1]); ccol = cb[wv * 4 + 3];
+                } else {
+                    s2 = fmaxf(s2, o1);
+                }
+            }
+            margin = fminf(margin, s1 > 0.f ? (s1 - fmaxf(s2, 0.f)) / s1 : 0.f);
+            if (tid == gstar) selected = true;
+
+            const float* grow = (GRAM_LDS ? gl : p.gram) + (size_t)gstar * N;
+            const float gdiag = grow[gstar];
+            const float gmine = active ? grow[tid] : 0.f;
+            const float* prow = Dt + (size_t)gstar * KS;
+            float dot = 0.f, piv = 0.f;
+            const int J4 = J & ~3;
+            for (int j = 0; j < J4; j += 4) {
+                const float4 u = *reinterpret_cast<const float4*>(myrow + j);
+                const float4 v = *reinterpret_cast<const float4*>(prow + j);
+                dot += u.x * v.x + u.y * v.y + u.z * v.z + u.w * v.w;
+                piv += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            }
+            for (int j = J4; j < J; ++j) {
+                const float v = prow[j];
+                dot += myrow[j] * v;
+                piv += v * v;
+            }
+            const float nrm2 = gdiag - piv;
+            float inv = 0.f;
+            if (nrm2 > 1e-10f * gdiag && nrm2 > 0.f) inv = 1.0f / sqrtf(nrm2);
+            else bad = 1;
+            const float dv = (gmine - dot) * inv;
+            const float bt = ccol * inv;
+            corr -= bt * dv;
+            myrow[J] = dv;
+            if (tid == 0) { beta[J] = bt; selcol[J] = gstar; }
+        }
+    }
+    bad = __syncthreads_or(bad);
+
+    const bool want_fit = a.coef != nullptr || a.resid != nullptr;
+    if (want_fit) {
+        // R[j][i] = Dt[selcol[i]][j] (j <= i).  One wavefront solves the triangular systems;
+        // lane i holds component i and pivots travel by scalar lane reads.
+        auto solve_upper = [&](float rhs) -> float {      // R x = rhs, back substitution
+            float x = 0.f;
+            for (int i = k - 1; i >= 0; --i) {
+                const float* ri = Dt + (size_t)selcol[i] * KS;
+                const float rii = ri[i];
+                const float xi = rii > 0.f ? readlane_f32(rhs, i) / rii : 0.f;
+                if (lane == i) x = xi;
+                if (lane < i) rhs -= ri[lane] * xi;
+            }
+            return x;
+        };
+        auto solve_lower_t = [&](float rhs) -> float {    // R^T x = rhs, forward substitution
+            float x = 0.f;
+            const float* rl = Dt + (size_t)selcol[lane < k ? lane : 0] * KS;
+            for (int i = 0; i < k; ++i) {
+                const float rii = Dt[(size_t)selcol[i] * KS + i];
+                const float xi = rii > 0.f ? readlane_f32(rhs, i) / rii : 0.f;
+                if (lane == i) x = xi;
+                if (lane > i && lane < k) rhs -= rl[i] * xi;
+            }
+            return x;
+        };
+        if (wave == 0) {
+            const float x = solve_upper(lane < k ? beta[lane] : 0.f);
+            if (lane < k) alpha[lane] = x;
+        }
+        __syncthreads();
+        // explicit residual; thread i keeps its row of M_S in registers for the second pass
+        const int mrows = (m + NT - 1) / NT;              // rows per thread (1 unless m > NT)
+        const bool one_row = mrows == 1;
+        float mv[RF_MAXK];
+        float racc = 0.f;
+        if (one_row) {
+            if (tid < m) {
+#pragma unroll
+                for (int j = 0; j < RF_MAXK; ++j) mv[j] = j < k ? p.Mr[(size_t)tid * N + selcol[j]] : 0.f;
+                racc = yv[tid];
+#pragma unroll
+                for (int j = 0; j < RF_MAXK; ++j) if (j < k) racc -= alpha[j] * mv[j];
+                rv[tid] = racc;
+            }
+        } else {
+            for (int i = tid; i < m; i += NT) {
+                float s = yv[i];
+                for (int j = 0; j < k; ++j) s -= alpha[j] * p.Mr[(size_t)i * N + selcol[j]];
+                rv[i] = s;
+            }
+        }
+        __syncthreads();
+        // g = M_S^T r
+        if (one_row) {
+            const int mwaves = (m + 63) >> 6;
+            if (wave < mwaves) {
+#pragma unroll
+                for (int j = 0; j < RF_MAXK; ++j) {
+                    if (j < k) {                           // k is uniform: no divergence
+                        const float s = wave_sum(tid < m ? mv[j] * racc : 0.f);
+                        if (lane == 0) gv[wave * RF_MAXK + j] = s;
+                    }
+                }
+            }
+            __syncthreads();
+            if (wave == 0 && lane < k) {
+                float s = 0.f;
+                for (int q = 0; q < mwaves; ++q) s += gv[q * RF_MAXK + lane];
+                gv[lane] = s;
+            }
+        } else {
+            for (int j = wave; j < k; j += nwaves) {
+                float s = 0.f;
+                for (int i = lane; i < m; i += 64) s += p.Mr[(size_t)i * N + selcol[j]] * rv[i];
+                s = wave_sum(s);
+                if (lane == 0) gv[j] = s;
+            }
+            __syncthreads();
+        }
+        // one refinement step: (R^T R) delta = g
+        if (wave == 0) {
+            const float wv = solve_lower_t(lane < k ? gv[lane] : 0.f);
+            const float dl = solve_upper(wv);
+            if (lane < k) { alpha[lane] += dl; beta[lane] = dl; }
+        }
+        __syncthreads();
+        float ss = 0.f;
+        if (one_row) {
+            if (tid < m) {
+#pragma unroll
+                for (int j = 0; j < RF_MAXK; ++j) if (j < k) racc -= beta[j] * mv[j];
+                ss = racc * racc;
+            }
+        } else {
+            for (int i = tid; i < m; i += NT) {
+                float s = rv[i];
+                for (int j = 0; j < k; ++j) s -= beta[j] * p.Mr[(size_t)i * N + selcol[j]];
+                ss += s * s;
+            }
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+    }
+    for (int qi = tid; qi < k; qi += NT) {
+        const int g = selcol[qi];
+        int rank = 0;
+        for (int o = 0; o < k; ++o) rank += selcol[o] < g;
+        a.support[(size_t)prob * k + rank] = g;
+        if (a.coef) a.coef[(size_t)prob * k + rank] = alpha[qi];
+    }
+    if (tid == 0) {
+        if (a.resid) {
+            float tot = 0.f;
+            for (int wv = 0; wv < nwaves; ++wv) tot += red[wv];
+            a.resid[prob] = bad ? __int_as_float(0x7fc00000) : sqrtf(tot);
+        }
+        if (a.margin) {
+            // every round wave tracked the same margin; wave 0 always owns atoms
+            a.margin[prob] = bad ? 0.f : margin;
+        }
+    }
+}
+
 hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
+    if (p.rb == 1 && a.k <= RF_MAXK && p.N <= RF_THREADS) {
+        // one wavefront for small problems, otherwise a full workgroup so that the bulk loads
+        // (Gram matrix, M) have many requests in flight
+        const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : RF_THREADS;
+        FastLayout FL;
+        if (make_fast_layout(p, a.k, lds_limit, nthreads, FL)) {
+            const size_t bytes = (size_t)FL.total_floats * 4;
+            if (FL.off_gram >= 0) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<true>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(recover_fast_kernel<true>, dim3(a.B), dim3(nthreads), bytes, s, p, a, FL);
+            } else {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<false>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(recover_fast_kernel<false>, dim3(a.B), dim3(nthreads), bytes, s, p, a, FL);
+            }
+            return hipGetLastError();
+        }
+    }
     const RecoverLayout L = make_layout(p, a.k, lds_limit);
     int nt = 256;
     if (p.N > 256) nt = 512;
