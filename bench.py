@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the single-layer side measurements")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     return ap.parse_args()
 
 
@@ -93,18 +94,22 @@ class DecodeState:
         # outputs and intermediates, allocated once
         self.y = torch.empty((B, c.m), device=dev)
         self.yh = torch.empty((B, hs.m), device=dev)
-        self.S = torch.empty((B, c.k), dtype=torch.int32, device=dev)
-        self.heads = torch.empty((B, hs.kh), dtype=torch.int32, device=dev)
+        self.S = [torch.empty((B, c.k), dtype=torch.int32, device=dev) for _ in range(2)]
+        self.heads = [torch.empty((B, hs.kh), dtype=torch.int32, device=dev) for _ in range(2)]
         self.resid = torch.empty((B,), device=dev)
         self.margin = torch.empty((B,), device=dev)
-        self.residh = torch.empty((B,), device=dev)
         self.marginh = torch.empty((B,), device=dev)
+        self.y2 = [torch.empty((B, c.m), device=dev) for _ in range(2)]
+        self.yh2 = [torch.empty((B, hs.m), device=dev) for _ in range(2)]
+        self.margin2 = [torch.empty((B,), device=dev) for _ in range(2)]
+        self.marginh2 = [torch.empty((B,), device=dev) for _ in range(2)]
         self.o = torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf)
         self.out = torch.empty((B, c.d), device=dev, dtype=bf)
 
 
 def decode_step(ctx, st, i, ev=None):
-    """One decode step over all layers.  ev: optional dict of event lists for per-call timing."""
+    """One decode step over all layers, every call in order on one stream.
+    ev: optional dict of event lists for per-call timing."""
     c, hs = st.c, st.hs
     for l in range(st.layers):
         def timed(name, fn):
@@ -116,13 +121,80 @@ def decode_step(ctx, st, i, ev=None):
             b.record()
             ev[name].append((a, b))
         timed("sketch", lambda: ctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh))
-        timed("recover", lambda: ctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh, st.heads,
-                                                        None, st.residh, st.marginh, want_coef=False))
-        timed("attn", lambda: ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads, st.o))
+        timed("recover", lambda: ctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh, st.heads[0],
+                                                        None, None, st.marginh, want_coef=False, want_resid=False))
+        timed("attn", lambda: ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads[0], st.o))
         timed("sketch", lambda: ctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y))
-        timed("recover", lambda: ctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y, st.S,
-                                                        None, st.resid, st.margin, want_coef=False))
-        timed("ffn", lambda: ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S, False, st.out))
+        timed("recover", lambda: ctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y, st.S[0],
+                                                        None, None, st.margin, want_coef=False, want_resid=False))
+        timed("ffn", lambda: ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S[0], False, st.out))
+
+
+def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec):
+    """The same step with measurement and recovery on a second stream, one layer ahead of
+    execution (the recovered support is consumed by the next piece of reduced computation,
+    paper Sec. 5).  Support buffers are double buffered; events order the two streams."""
+    c, hs = st.c, st.hs
+    s_rec.wait_stream(s_exec)
+    done = [None] * st.layers
+    for l in range(st.layers):
+        buf = l & 1
+        with torch.cuda.stream(s_rec):
+            if l >= 2:
+                s_rec.wait_event(done[l - 2])            # layer l-2 has finished reading this buffer
+            rctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh2[buf])
+            rctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh2[buf], st.heads[buf],
+                                    None, None, st.marginh2[buf], want_coef=False, want_resid=False)
+            rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y2[buf])
+            rctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y2[buf], st.S[buf],
+                                    None, None, st.margin2[buf], want_coef=False, want_resid=False)
+            ready = torch.cuda.Event()
+            ready.record(s_rec)
+        with torch.cuda.stream(s_exec):
+            s_exec.wait_event(ready)
+            ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads[buf], st.o)
+            ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S[buf], False, st.out)
+            done[l] = torch.cuda.Event()
+            done[l].record(s_exec)
+    s_exec.wait_stream(s_rec)
+
+
+def call_loops(ctx, st, stream):
+    """ms per call of each call type, measured with HIP events around loops that launch that
+    call for every layer in turn (two passes after one warm pass).  Returns (per, mean union size)."""
+    c, hs = st.c, st.hs
+    nl = st.layers
+    # supports of every layer from one recovery pass on step 0
+    S_all, H_all = [], []
+    for l in range(nl):
+        ctx.cs_sketch(st.ffn_op[l], st.z[0][l], st.y)
+        S_all.append(ctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y, None, None, None, st.margin,
+                                            want_coef=False, want_resid=False)[0])
+        ctx.cs_sketch(st.head_op[l], st.u[0][l], st.yh)
+        H_all.append(ctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh, None, None, None, st.marginh,
+                                            want_coef=False, want_resid=False)[0])
+    torch.cuda.synchronize()
+    union_mean = float(np.mean([union_blocks(S, c.G) for S in S_all]))
+    loops = {
+        "attn": lambda i: ctx.cs_head_attn(st.q[0][i % nl], st.K[i % nl], st.V[i % nl], H_all[i % nl], st.o),
+        "ffn": lambda i: ctx.cs_block_ffn(st.Wg[i % nl], st.Wu[i % nl], st.Wd[i % nl], st.x[0][i % nl], S_all[i % nl],
+                                          False, st.out),
+        "recover_ffn": lambda i: ctx.cs_recover_support(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, st.S[0], None,
+                                                        None, st.margin, want_coef=False, want_resid=False),
+        "recover_heads": lambda i: ctx.cs_recover_support(st.head_op[i % nl], st.head_dict, hs.kh, st.yh, st.heads[0],
+                                                          None, None, st.marginh, want_coef=False, want_resid=False),
+        "sketch_ffn": lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y),
+        "sketch_heads": lambda i: ctx.cs_sketch(st.head_op[i % nl], st.u[0][i % nl], st.yh),
+    }
+    raw = {}
+    for name, fn in loops.items():
+        time_loop(fn, nl, stream)
+        raw[name] = time_loop(fn, 2 * nl, stream)
+    per = {"attn": raw["attn"], "ffn": raw["ffn"],
+           "recover": 0.5 * (raw["recover_ffn"] + raw["recover_heads"]),
+           "sketch": 0.5 * (raw["sketch_ffn"] + raw["sketch_heads"])}
+    per.update({k: raw[k] for k in ("recover_ffn", "recover_heads", "sketch_ffn", "sketch_heads")})
+    return per, union_mean
 
 
 def union_blocks(S, G):
@@ -169,6 +241,7 @@ def cpu_baseline(wl, layers_sample=2, B=16, seed=3000):
 
 
 def time_loop(fn, iters, stream):
+    """ms per iteration between two HIP events recorded on `stream`."""
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record(stream)
     for i in range(iters):
@@ -200,16 +273,19 @@ def extra_measurements(ctx, st, wl, stream):
                               "hbm_frac": bytes_active / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "tokens_per_s_layer": B / (ms * 1e-3)}
     B = st.B
-    fn = lambda i: ctx.cs_recover_support(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, st.S, None,
-                                          st.resid, st.margin, want_coef=False)
     ctx.cs_sketch(st.ffn_op[0], st.z[0][0], st.y)
-    time_loop(fn, nl, stream)
-    res["recover_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
-    fn = lambda i: ctx.cs_recover_support(st.head_op[i % nl], st.head_dict, hs.kh, st.yh, st.heads, None,
-                                          st.residh, st.marginh, want_coef=False)
     ctx.cs_sketch(st.head_op[0], st.u[0][0], st.yh)
-    time_loop(fn, nl, stream)
-    res["recover_heads_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
+    for tag, fit in (("support_margin", False), ("with_refit", True)):
+        coef = torch.empty((B, c.k), device=dev) if fit else None
+        fn = lambda i: ctx.cs_recover_support(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, st.S[0], coef,
+                                              st.resid if fit else None, st.margin, want_coef=False, want_resid=False)
+        time_loop(fn, nl, stream)
+        res["recover_ffn_us_per_call_B%d_%s" % (B, tag)] = time_loop(fn, 2 * nl, stream) * 1e3
+        coefh = torch.empty((B, hs.kh), device=dev) if fit else None
+        fn = lambda i: ctx.cs_recover_support(st.head_op[i % nl], st.head_dict, hs.kh, st.yh, st.heads[0], coefh,
+                                              st.resid if fit else None, st.marginh, want_coef=False, want_resid=False)
+        time_loop(fn, nl, stream)
+        res["recover_heads_us_per_call_B%d_%s" % (B, tag)] = time_loop(fn, 2 * nl, stream) * 1e3
     fn = lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y)
     time_loop(fn, nl, stream)
     res["sketch_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
@@ -226,50 +302,76 @@ def main():
         raise SystemExit("bench.py needs a GPU and the HIP library; there is no CPU fallback")
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
+    rstream = torch.cuda.Stream()
     ctx = binding.Context(device=0, stream=stream)
+    rctx = binding.Context(device=0, stream=rstream)
     nsteps = args.steps + args.warmup
     with torch.cuda.stream(stream):
         st = DecodeState(ctx, wl, binding, args.layers, args.batch, nsteps)
+        for l in range(args.layers):               # the recovery context keeps its own plans
+            rctx.cs_plan(st.ffn_op[l], st.ffn_dict[l], st.psi[l])
+            rctx.cs_plan(st.head_op[l], st.head_dict)
         torch.cuda.synchronize()
+        # one HIP graph per step: the launches of a step (two streams, 8 kernels per layer) are
+        # replayed without host work in between
+        graphs = None
+        if not args.no_graph:
+            try:
+                graphs = []
+                for i in range(nsteps):
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=stream, capture_error_mode="thread_local"):
+                        decode_step_pipelined(ctx, rctx, st, i, stream, rstream)
+                    graphs.append(g)
+            except Exception as exc:                # fall back to plain launches
+                print("graph capture failed (%s); running eager" % exc, file=sys.stderr)
+                graphs = None
+                torch.cuda.synchronize()
+
+        def run(i):
+            if graphs is not None:
+                graphs[i].replay()
+            else:
+                decode_step_pipelined(ctx, rctx, st, i, stream, rstream)
+
         for i in range(args.warmup):
-            decode_step(ctx, st, i)
+            run(i)
         torch.cuda.synchronize()
-        # --- timed region: exactly `steps` steps, no per-call events
+        # --- timed region: exactly `steps` steps
         t0 = time.perf_counter()
         for i in range(args.steps):
-            decode_step(ctx, st, args.warmup + i)
+            run(args.warmup + i)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        # --- the same steps again with HIP events around every call (per-call durations)
-        ev = {"sketch": [], "recover": [], "attn": [], "ffn": []}
-        unions = []
-        for i in range(args.steps):
-            decode_step(ctx, st, args.warmup + i, ev)
-        torch.cuda.synchronize()
-        per = {k: sum(a.elapsed_time(b) for a, b in v) / max(len(v), 1) for k, v in ev.items()}   # ms per call
+        # --- per-call durations: each call type launched back to back over all layers (fresh
+        # weights and supports per layer), HIP events on the launching stream around each loop
+        per, union_mean = call_loops(ctx, st, stream)
         # active bytes per call
         c, hs = st.c, st.hs
         attn_bytes = args.batch * hs.kh * 2 * hs.L * hs.dh * 2
-        # union of the supports of the last call stands for all (same distribution)
+        # union of the supports of one call stands for all (same distribution)
         ctx.cs_sketch(st.ffn_op[0], st.z[0][0], st.y)
-        ctx.cs_recover_support(st.ffn_op[0], st.ffn_dict[0], c.k, st.y, st.S, None, st.resid, st.margin, want_coef=False)
+        ctx.cs_recover_support(st.ffn_op[0], st.ffn_dict[0], c.k, st.y, st.S[0], None, None, st.margin,
+                               want_coef=False, want_resid=False)
         torch.cuda.synchronize()
         margin_pass = float((st.margin > 1e-3).float().mean())
-        ffn_bytes = union_blocks(st.S, c.G) * 3 * c.b * c.d * 2
+        ffn_bytes = union_mean * 3 * c.b * c.d * 2
         extra = None if args.no_extra else extra_measurements(ctx, st, wl, stream)
         torch.cuda.synchronize()
 
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = args.batch / (wall / args.steps)
     calls_per_step = {"sketch": 2 * args.layers, "recover": 2 * args.layers, "attn": args.layers, "ffn": args.layers}
-    step_share = {k: per[k] * calls_per_step[k] for k in per}
+    step_share = {k: per[k] * calls_per_step[k] for k in calls_per_step}
     kernels = {
         "attn": {"us_per_call": per["attn"] * 1e3, "active_MB": attn_bytes / 1e6,
                  "GBs": attn_bytes / (per["attn"] * 1e-3) / 1e9},
         "ffn": {"us_per_call": per["ffn"] * 1e3, "active_MB": ffn_bytes / 1e6,
                 "GBs": ffn_bytes / (per["ffn"] * 1e-3) / 1e9},
-        "recover": {"us_per_call": per["recover"] * 1e3},
-        "sketch": {"us_per_call": per["sketch"] * 1e3},
+        "recover_ffn": {"us_per_call": per["recover_ffn"] * 1e3},
+        "recover_heads": {"us_per_call": per["recover_heads"] * 1e3},
+        "sketch_ffn": {"us_per_call": per["sketch_ffn"] * 1e3},
+        "sketch_heads": {"us_per_call": per["sketch_heads"] * 1e3},
     }
     dom = "attn" if step_share["attn"] >= step_share["ffn"] else "ffn"
     achieved = kernels[dom]["GBs"]
@@ -288,14 +390,18 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None},
         "kernels": kernels,
         "recovery": {"us_per_token": step_share["recover"] * 1e3 / args.batch,
-                     "frac_of_step_serial": rec_frac, "margin_pass_rate": margin_pass},
-        "step_breakdown_ms": step_share,
+                     "frac_of_serial_step": rec_frac, "margin_pass_rate": margin_pass,
+                     "note": "in the timed region recovery runs on a second stream one layer ahead of execution"},
+        "serial_step_breakdown_ms": step_share,
+        "ms_per_step_serial_sum": sum(step_share.values()),
+        "launch_mode": "hip_graph" if graphs is not None else "eager",
     }
     if extra is not None:
         result["single_layer"] = extra
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, B=args.batch)
     ctx.close()
+    rctx.close()
     print(json.dumps(result))
 
 

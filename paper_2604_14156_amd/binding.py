@@ -118,14 +118,14 @@ class Context:
         return y
 
     def cs_recover_support(self, op, dct, k, y, support=None, coef=None, resid=None, margin=None,
-                           want_coef=True):
+                           want_coef=True, want_resid=True):
         B = y.shape[0]
         dev = y.device
         if support is None:
             support = torch.empty((B, k), dtype=torch.int32, device=dev)
         if coef is None and want_coef:
             coef = torch.empty((B, k * dct.rb), dtype=torch.float32, device=dev)
-        if resid is None:
+        if resid is None and want_resid:
             resid = torch.empty((B,), dtype=torch.float32, device=dev)
         if margin is None:
             margin = torch.empty((B,), dtype=torch.float32, device=dev)

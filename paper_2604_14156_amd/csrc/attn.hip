@@ -2,46 +2,90 @@
 // structured units (paper Sec. 3, Sec. 7).  Only the kept heads' K and V are read;
 // pruned heads output zeros.
 //
-// Split-KV streaming: a workgroup takes one (sequence, kept head, position range).
-// A group of dh/8 lanes owns one cached position per step: each lane loads 16 bytes
-// of the key row, the group reduces the dot product, and a running softmax
-// (max, sum, weighted value accumulator) is kept per lane group.  Groups, waves and
-// position ranges are merged with the usual log-sum-exp rescaling.
+// Streaming kernel: a workgroup takes one (sequence, head, position range).  A group
+// of dh/8 lanes owns one cached position per step: each lane loads 16 bytes of the
+// key row and of the value row, the group reduces the dot product on the lane
+// crossbar, and a running softmax (max, sum, weighted value accumulator) is kept
+// per lane group.  Groups and waves are merged through LDS with the usual
+// log-sum-exp rescaling.  The positions of a head are split over several workgroups
+// so that about eight workgroups per compute unit are in flight, and a second small
+// kernel merges the partial results; a short cache is handled by one workgroup per
+// head that writes the result directly.
 #include "kernels.hpp"
 
 namespace csk {
 
-constexpr int AT_WAVES = 4;
-constexpr int AT_UNROLL = 4;
+constexpr int AT_UNROLL = 8;            // key/value row pairs in flight per lane
+constexpr int AT_WAVES = 4;             // waves per workgroup
+constexpr int AT_TARGET_WGS = 2048;     // workgroups wanted in flight (8 per compute unit)
+constexpr int AT_MAX_SPLIT = 32;
 
-template <typename T, int DH>
-__global__ __launch_bounds__(AT_WAVES * 64)
-void attn_partial_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
-                         int H, int L, const int32_t* __restrict__ heads, int kh,
-                         int span, float* __restrict__ part) {
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
+// eight consecutive elements of a row, kept in the form the dot product wants
+template <typename T> struct Frag8;
+template <> struct Frag8<float> {
+    float v[8];
+    __device__ __forceinline__ void load(const float* p) { load8(p, v); }
+    __device__ __forceinline__ float dot(const Frag8<float>& q) const {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += v[i] * q.v[i];
+        return s;
+    }
+    __device__ __forceinline__ float get(int i) const { return v[i]; }
+};
+template <> struct Frag8<uint16_t> {
+    uint4 r;
+    __device__ __forceinline__ void load(const uint16_t* p) { r = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ float dot(const Frag8<uint16_t>& q) const {
+        // packed bf16 dot product with fp32 accumulation: two products per instruction
+        float s = 0.f;
+        s = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&r.x), *reinterpret_cast<const bf16x2_t*>(&q.r.x), s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&r.y), *reinterpret_cast<const bf16x2_t*>(&q.r.y), s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&r.z), *reinterpret_cast<const bf16x2_t*>(&q.r.z), s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&r.w), *reinterpret_cast<const bf16x2_t*>(&q.r.w), s, false);
+        return s;
+    }
+    __device__ __forceinline__ float get(int i) const {
+        const uint32_t w = i < 2 ? r.x : (i < 4 ? r.y : (i < 6 ? r.z : r.w));
+        return (i & 1) ? bf16_hi(w) : bf16_lo(w);
+    }
+};
+
+template <typename T, int DH, int NW, bool FINAL>
+__global__ __launch_bounds__(NW * 64)
+void attn_stream_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
+                        int H, int L, const int32_t* __restrict__ heads, int kh,
+                        int span, float* __restrict__ part, T* __restrict__ out) {
     constexpr int LPP = DH / 8;              // lanes per position
     constexpr int PPW = 64 / LPP;            // positions per wavefront step
-    constexpr int STEP = PPW * AT_WAVES;     // positions per workgroup step
-    __shared__ float sm[AT_WAVES * PPW][DH + 2];
+    constexpr int STEP = PPW * NW;           // positions per workgroup step
+    __shared__ float sm[NW * PPW][DH + 2];
 
-    const int split = blockIdx.x, slot = blockIdx.y, seq = blockIdx.z;
+    const int split = blockIdx.x, h = blockIdx.y, seq = blockIdx.z;
     const int nsplit = gridDim.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPP, grp = lane / LPP;
-    const int h = heads[seq * kh + slot];
-    float* dst = part + (((size_t)seq * kh + slot) * nsplit + split) * (DH + 2);
-    if (h < 0 || h >= H) {                   // invalid head index: contributes an empty partial
-        for (int c = threadIdx.x; c < DH + 2; c += AT_WAVES * 64) dst[c] = (c == 0) ? -INFINITY : 0.f;
+    int slot = -1;
+    for (int j0 = 0; j0 < kh; j0 += 64) {                // one load per lane, match found by ballot
+        const int j = j0 + lane;
+        const int hv = j < kh ? heads[seq * kh + j] : -1;
+        const unsigned long long bal = __ballot(hv == h);
+        if (bal) slot = j0 + __ffsll((long long)bal) - 1;
+    }
+    if (slot < 0) {                          // pruned head: zeros, written once
+        if (split == 0)
+            for (int c = threadIdx.x; c < DH; c += NW * 64) store1(out + ((size_t)seq * H + h) * DH + c, 0.f);
         return;
     }
     const size_t head_off = ((size_t)seq * H + h);
-    const T* Kh = K + head_off * (size_t)L * DH;
-    const T* Vh = V + head_off * (size_t)L * DH;
-    float qf[8];
-    load8(q + head_off * DH + sub * 8, qf);
+    const T* Kh = K + head_off * (size_t)L * DH + sub * 8;
+    const T* Vh = V + head_off * (size_t)L * DH + sub * 8;
+    Frag8<T> qf;
+    qf.load(q + head_off * DH + sub * 8);
     const float sc = 1.4426950408889634f / sqrtf((float)DH);     // log2(e)/sqrt(dh): scores in base 2
-#pragma unroll
-    for (int i = 0; i < 8; ++i) qf[i] *= sc;
 
     const int p_begin = split * span;
     const int p_end = min(L, p_begin + span);
@@ -49,32 +93,25 @@ void attn_partial_kernel(const T* __restrict__ q, const T* __restrict__ K, const
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
-    for (int p0 = p_begin + wave * PPW + grp; p0 < p_end + 0; p0 += STEP * AT_UNROLL) {
-        float kv[AT_UNROLL][8], vv[AT_UNROLL][8];
+    for (int p0 = p_begin + wave * PPW + grp; p0 < p_end; p0 += STEP * AT_UNROLL) {
+        Frag8<T> kv[AT_UNROLL], vv[AT_UNROLL];
 #pragma unroll
         for (int u = 0; u < AT_UNROLL; ++u) {
-            const int p = p0 + u * STEP;
-            if (p < p_end) {
-                load8(Kh + (size_t)p * DH + sub * 8, kv[u]);
-                load8(Vh + (size_t)p * DH + sub * 8, vv[u]);
-            }
+            const int p = min(p0 + u * STEP, p_end - 1);           // clamped: loads stay in range
+            kv[u].load(Kh + (size_t)p * DH);
+            vv[u].load(Vh + (size_t)p * DH);
         }
 #pragma unroll
         for (int u = 0; u < AT_UNROLL; ++u) {
             const int p = p0 + u * STEP;
-            float s = 0.f;
-            if (p < p_end) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) s += kv[u][i] * qf[i];
-            }
-            s = group_sum<LPP>(s);
+            const float s = group_sum<LPP>(kv[u].dot(qf)) * sc;
             if (p < p_end) {
                 const float mnew = fmaxf(mrun, s);
                 const float corr = exp2f(mrun - mnew);           // mrun = -inf gives 0
                 const float w = exp2f(s - mnew);
                 lrun = lrun * corr + w;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + w * vv[u][i];
+                for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + w * vv[u].get(i);
                 mrun = mnew;
             }
         }
@@ -86,67 +123,74 @@ void attn_partial_kernel(const T* __restrict__ q, const T* __restrict__ K, const
     if (sub == 0) { sm[row][DH] = mrun; sm[row][DH + 1] = lrun; }
     __syncthreads();
     float mtot = -INFINITY;
-    for (int r = 0; r < AT_WAVES * PPW; ++r) mtot = fmaxf(mtot, sm[r][DH]);
-    for (int c = threadIdx.x; c < DH + 2; c += AT_WAVES * 64) {
-        float v = 0.f;
-        if (c < DH) {
-            for (int r = 0; r < AT_WAVES * PPW; ++r) {
-                const float mr = sm[r][DH];
-                if (mr > -INFINITY) v += exp2f(mr - mtot) * sm[r][c];
-            }
-        } else if (c == DH) {
-            v = mtot;
-        } else {
-            for (int r = 0; r < AT_WAVES * PPW; ++r) {
-                const float mr = sm[r][DH];
-                if (mr > -INFINITY) v += exp2f(mr - mtot) * sm[r][DH + 1];
-            }
+    for (int r = 0; r < NW * PPW; ++r) mtot = fmaxf(mtot, sm[r][DH]);
+    float den = 0.f;
+    if (FINAL || threadIdx.x == 0)
+        for (int r = 0; r < NW * PPW; ++r) {
+            const float mr = sm[r][DH];
+            if (mr > -INFINITY) den += exp2f(mr - mtot) * sm[r][DH + 1];
         }
-        dst[c == DH ? 0 : (c < DH ? c + 2 : 1)] = v;         // layout: [max, sum, acc[DH]]
+    float* dst = FINAL ? nullptr : part + (((size_t)seq * kh + slot) * nsplit + split) * (DH + 2);
+    for (int c = threadIdx.x; c < DH; c += NW * 64) {
+        float v = 0.f;
+        for (int r = 0; r < NW * PPW; ++r) {
+            const float mr = sm[r][DH];
+            if (mr > -INFINITY) v += exp2f(mr - mtot) * sm[r][c];
+        }
+        if (FINAL) store1(out + head_off * DH + c, den > 0.f ? v / den : 0.f);
+        else dst[2 + c] = v;                                     // layout: [max, sum, acc[DH]]
     }
+    if (!FINAL && threadIdx.x == 0) { dst[0] = mtot; dst[1] = den; }
 }
 
-// One thread per output element: merge the position ranges of a kept head, or
-// write zeros for a pruned head.
+// One thread per output element: merge the position ranges of a kept head (pruned
+// heads were zeroed by the streaming kernel).  All loads are issued before any is used.
 template <typename T, int DH>
 __global__ void attn_combine_kernel(const float* __restrict__ part, int H, const int32_t* __restrict__ heads,
                                     int kh, int nsplit, T* __restrict__ out) {
-    const int h = blockIdx.x, seq = blockIdx.y;
+    const int slot = blockIdx.x, seq = blockIdx.y;
     const int c = threadIdx.x;
-    int slot = -1;
-    for (int j = 0; j < kh; ++j)
-        if (heads[seq * kh + j] == h) slot = j;
-    T* o = out + ((size_t)seq * H + h) * DH;
-    if (slot < 0) { store1(o + c, 0.f); return; }
+    const int h = heads[seq * kh + slot];
     const float* pp = part + ((size_t)seq * kh + slot) * nsplit * (DH + 2);
-    float mtot = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) mtot = fmaxf(mtot, pp[(size_t)s * (DH + 2)]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
+    float mx[AT_MAX_SPLIT], sm[AT_MAX_SPLIT], ac[AT_MAX_SPLIT];
+#pragma unroll
+    for (int s = 0; s < AT_MAX_SPLIT; ++s) {
         const float* ps = pp + (size_t)s * (DH + 2);
-        if (ps[0] > -INFINITY) {
-            const float w = exp2f(ps[0] - mtot);
-            num += w * ps[2 + c];
-            den += w * ps[1];
-        }
+        mx[s] = s < nsplit ? ps[0] : -INFINITY;
+        sm[s] = s < nsplit ? ps[1] : 0.f;
+        ac[s] = s < nsplit ? ps[2 + c] : 0.f;
     }
-    store1(o + c, den > 0.f ? num / den : 0.f);
+    if (h < 0 || h >= H) return;
+    float mtot = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < AT_MAX_SPLIT; ++s) mtot = fmaxf(mtot, mx[s]);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int s = 0; s < AT_MAX_SPLIT; ++s) {
+        const float w = mx[s] > -INFINITY ? exp2f(mx[s] - mtot) : 0.f;
+        num += w * ac[s];
+        den += w * sm[s];
+    }
+    store1(out + ((size_t)seq * H + h) * DH + c, den > 0.f ? num / den : 0.f);
 }
 
+// Number of position ranges per head and their length.  One range (the result is
+// written directly) only when the cache is short.
 static void attn_split(const AttnArgs& a, int& nsplit, int& span) {
     const long pairs = (long)a.B * a.kh;
-    long want = pairs > 0 ? (2048 + pairs - 1) / pairs : 1;
-    if (want < 1) want = 1;
+    long want = pairs > 0 ? (AT_TARGET_WGS + pairs - 1) / pairs : 1;
+    if (want > AT_MAX_SPLIT) want = AT_MAX_SPLIT;
     long sp = (a.L + want - 1) / want;
     sp = ((sp + 63) / 64) * 64;
     span = (int)sp;
     nsplit = (a.L + span - 1) / span;
+    if (nsplit == 1) span = a.L;
 }
 
 size_t attn_scratch_bytes(const AttnArgs& a) {
     int nsplit, span;
     attn_split(a, nsplit, span);
-    return (size_t)a.B * a.kh * nsplit * (a.dh + 2) * sizeof(float);
+    return nsplit == 1 ? 0 : (size_t)a.B * a.kh * nsplit * (a.dh + 2) * sizeof(float);
 }
 
 template <typename T, int DH>
@@ -154,11 +198,16 @@ static hipError_t run_attn(const AttnArgs& a, hipStream_t s) {
     int nsplit, span;
     attn_split(a, nsplit, span);
     float* part = reinterpret_cast<float*>(a.scratch);
-    if (a.kh > 0)
-        hipLaunchKernelGGL((attn_partial_kernel<T, DH>), dim3(nsplit, a.kh, a.B), dim3(AT_WAVES * 64), 0, s,
-                           (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, part);
-    hipLaunchKernelGGL((attn_combine_kernel<T, DH>), dim3(a.H, a.B), dim3(DH), 0, s,
-                       part, a.H, a.heads, a.kh, nsplit, (T*)a.out);
+    if (nsplit == 1) {
+        hipLaunchKernelGGL((attn_stream_kernel<T, DH, AT_WAVES, true>), dim3(1, a.H, a.B), dim3(AT_WAVES * 64), 0, s,
+                           (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, part, (T*)a.out);
+    } else {
+        hipLaunchKernelGGL((attn_stream_kernel<T, DH, AT_WAVES, false>), dim3(nsplit, a.H, a.B), dim3(AT_WAVES * 64), 0, s,
+                           (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, part, (T*)a.out);
+        if (a.kh > 0)
+            hipLaunchKernelGGL((attn_combine_kernel<T, DH>), dim3(a.kh, a.B), dim3(DH), 0, s,
+                               part, a.H, a.heads, a.kh, nsplit, (T*)a.out);
+    }
     return hipGetLastError();
 }
 

@@ -325,8 +325,23 @@ static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, 
     return true;
 }
 
-template <bool GRAM_LDS>
-__global__ __launch_bounds__(RF_THREADS)
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+// maximum of an unsigned key over the wavefront, returned in every lane
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, dpp_u32<CS_DPP_QUAD_SWAP1>(v));
+    v = max(v, dpp_u32<CS_DPP_QUAD_SWAP2>(v));
+    v = max(v, dpp_u32<CS_DPP_HALF_MIRROR>(v));
+    v = max(v, dpp_u32<CS_DPP_ROW_MIRROR>(v));
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    return max(max(a, b), max(c, d));
+}
+
+template <bool GRAM_LDS, bool WANT_MARGIN>
+__global__ __launch_bounds__(RF_THREADS) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, NT = blockDim.x;
@@ -337,7 +352,6 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     const int round_waves = (N + 63) >> 6;     // waves that own atoms
 
     float* yv = lds + L.off_y;
-    float* rv = lds + L.off_r;
     float* cand = lds + L.off_cand;            // [2][16][4]
     float* beta = lds + L.off_beta;
     float* alpha = lds + L.off_alpha;
@@ -347,119 +361,139 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     float* Dt = lds + L.off_Dt;                // [rows][KS], row c = factor entries of atom c
     float* gl = lds + L.off_gram;
 
-    // ---- bulk loads, many in flight per thread: the Gram matrix into LDS, the sketch
-    if (GRAM_LDS) {
-        const int n4 = (N * N) >> 2;
-        const float4* src = reinterpret_cast<const float4*>(p.gram);
-        float4* dst = reinterpret_cast<float4*>(gl);
-        constexpr int U = 8;
-        for (int base = 0; base < n4; base += NT * U) {
-            float4 r[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * NT + tid;
-                if (idx < n4) r[u] = src[idx];
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * NT + tid;
-                if (idx < n4) dst[idx] = r[u];
-            }
-        }
-        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gl[i] = p.gram[i];
-    }
+    // ---- every independent global load is issued before the first wait: the sketch, the
+    // score weight, the Gram matrix (to LDS) and the first slice of M for c = M^T y
     const float* y = a.y + (size_t)prob * m;
-    int bad = 0;
-    for (int i = tid; i < m; i += NT) {
+    const int mrows = (m + NT - 1) / NT;
+    float yreg = (tid < m) ? y[tid] : 0.f;
+    const float w = (active && p.weighted) ? p.W[tid] : 1.f;
+    constexpr int GU = 16;
+    const int n4 = (N * N) >> 2;
+    float4 greg[GU];
+    if (GRAM_LDS) {
+        const float4* src = reinterpret_cast<const float4*>(p.gram);
+#pragma unroll
+        for (int u = 0; u < GU; ++u) {
+            const int idx = u * NT + tid;
+            greg[u] = idx < n4 ? src[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    // slices of M^T y: a thread takes four adjacent atoms and a contiguous range of rows
+    const bool vec4 = (N & 3) == 0;
+    const int ncg = vec4 ? (N >> 2) : N;
+    const int parts = NT / ncg > 0 ? NT / ncg : 1;
+    const int cg = tid % ncg, part = tid / ncg;
+    const int rows_per = (m + parts - 1) / parts;
+    const int i0 = part * rows_per, i1 = part < parts ? min(m, i0 + rows_per) : i0;
+    constexpr int MU = 8;
+    float4 mreg[MU];
+    if (vec4) {
+        const float4* mr = reinterpret_cast<const float4*>(p.Mr) + cg;
+#pragma unroll
+        for (int u = 0; u < MU; ++u)
+            mreg[u] = (i0 + u < i1) ? mr[(size_t)(i0 + u) * ncg] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    int bad = !isfinite(yreg);
+    if (tid < m) yv[tid] = yreg;
+    for (int i = tid + NT; i < m; i += NT) {          // only when m exceeds the workgroup size
         const float v = y[i];
         yv[i] = v;
         if (!isfinite(v)) bad = 1;
     }
+    if (GRAM_LDS) {
+        float4* dst = reinterpret_cast<float4*>(gl);
+#pragma unroll
+        for (int u = 0; u < GU; ++u) {
+            const int idx = u * NT + tid;
+            if (idx < n4) dst[idx] = greg[u];
+        }
+        const float4* src = reinterpret_cast<const float4*>(p.gram);
+        for (int base = GU * NT; base < n4; base += NT) {     // Gram matrices beyond the first batch
+            const int idx = base + tid;
+            if (idx < n4) dst[idx] = src[idx];
+        }
+        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gl[i] = p.gram[i];
+    }
     bad = __syncthreads_or(bad);
 
-    // ---- c = M^T y from the row-major copy of M.  A thread takes a group of four
-    // adjacent atoms and a slice of the measurement rows; slices are summed through LDS.
     float corr = 0.f;
     {
         float* stage = Dt;                              // [parts][N]
-        if ((N & 3) == 0) {
-            const int ncg = N >> 2;
-            const int parts = NT / ncg > 0 ? NT / ncg : 1;
-            const int cg = tid % ncg, part = tid / ncg;
-            const int rows_per = (m + parts - 1) / parts;
-            if (part < parts) {
-                const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
-                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-                const float4* mr = reinterpret_cast<const float4*>(p.Mr) + cg;
-                constexpr int U = 8;
-                for (int ib = i0; ib < i1; ib += U) {
-                    float4 r[U];
+        if (vec4) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4* mr = reinterpret_cast<const float4*>(p.Mr) + cg;
+            for (int ib = i0; ib < i1; ib += MU) {
+                if (ib != i0) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (ib + u < i1) r[u] = mr[(size_t)(ib + u) * ncg];
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (ib + u < i1) {
-                            const float yy = yv[ib + u];
-                            acc.x += r[u].x * yy; acc.y += r[u].y * yy; acc.z += r[u].z * yy; acc.w += r[u].w * yy;
-                        }
+                    for (int u = 0; u < MU; ++u)
+                        mreg[u] = (ib + u < i1) ? mr[(size_t)(ib + u) * ncg] : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
-                reinterpret_cast<float4*>(stage)[part * ncg + cg] = acc;
+#pragma unroll
+                for (int u = 0; u < MU; ++u)
+                    if (ib + u < i1) {
+                        const float yy = yv[ib + u];
+                        acc.x += mreg[u].x * yy; acc.y += mreg[u].y * yy; acc.z += mreg[u].z * yy; acc.w += mreg[u].w * yy;
+                    }
             }
-            __syncthreads();
-            if (active) for (int q = 0; q < parts; ++q) corr += stage[q * N + tid];
+            if (part < parts) reinterpret_cast<float4*>(stage)[part * ncg + cg] = acc;
         } else {
-            const int parts = NT / N > 0 ? NT / N : 1;
-            const int c = tid % N, part = tid / N;
-            const int rows_per = (m + parts - 1) / parts;
-            if (part < parts) {
-                const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
-                float acc = 0.f;
+            float acc = 0.f;
 #pragma unroll 8
-                for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + c] * yv[i];
-                stage[part * N + c] = acc;
-            }
-            __syncthreads();
-            if (active) for (int q = 0; q < parts; ++q) corr += stage[q * N + tid];
+            for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + cg] * yv[i];
+            if (part < parts) stage[part * N + cg] = acc;
         }
+        __syncthreads();
+        if (active) for (int q = 0; q < parts; ++q) corr += stage[q * N + tid];
         __syncthreads();                                // the staging area becomes the factor
     }
-    const float w = (active && p.weighted) ? p.W[tid] : 1.f;
     bool selected = false;
     float margin = 1.f;
     float* myrow = Dt + (size_t)(tid < L.rows ? tid : 0) * KS;
 
     for (int J = 0; J < k; ++J) {
         if (wave < round_waves) {
-            float score = -1.f;
+            // key: 0 for lanes without a candidate, else 1 + the bit pattern of the (non-negative) score
+            uint32_t key = 0u;
             if (active && !selected) {
                 const float t = w * corr;
-                score = t * t;
+                float score = t * t;
                 if (!(score >= 0.f)) score = 0.f;        // NaN scores tie at zero
+                key = __float_as_uint(score) + 1u;
             }
-            const float m1 = wave_max(score);
-            const unsigned long long hit = __ballot(score == m1);
+            const uint32_t m1 = wave_max_u32(key);
+            const unsigned long long hit = __ballot(key == m1);
             const int l1 = __ffsll((long long)hit) - 1;
             const float c1 = readlane_f32(corr, l1);
-            const float m2 = wave_max(lane == l1 ? -2.f : score);
-            float* cd = cand + ((J & 1) * 16 + wave) * 4;
-            if (lane == 0) { cd[0] = m1; cd[1] = __int_as_float(wave * 64 + l1); cd[2] = m2; cd[3] = c1; }
+            uint32_t m2 = 0u;
+            if (WANT_MARGIN) m2 = wave_max_u32(lane == l1 ? 0u : key);
+            if (lane == 0) {
+                float4 cv;
+                cv.x = __uint_as_float(m1); cv.y = __int_as_float(wave * 64 + l1); cv.z = __uint_as_float(m2); cv.w = c1;
+                *reinterpret_cast<float4*>(cand + ((J & 1) * 16 + wave) * 4) = cv;
+            }
         }
         __syncthreads();
         if (wave < round_waves) {
-            const float* cb = cand + (J & 1) * 16 * 4;
-            float s1 = cb[0], s2 = cb[2], ccol = cb[3];
-            int gstar = __float_as_int(cb[1]);
+            const float4* cb = reinterpret_cast<const float4*>(cand + (J & 1) * 16 * 4);
+            float4 c0 = cb[0];
+            uint32_t k1 = __float_as_uint(c0.x), k2 = __float_as_uint(c0.z);
+            int gstar = __float_as_int(c0.y);
+            float ccol = c0.w;
             for (int wv = 1; wv < round_waves; ++wv) {
-                const float o1 = cb[wv * 4];
-                if (o1 > s1) {                            // ties keep the lower wave = lower index
-                    s2 = fmaxf(fmaxf(s2, s1), cb[wv * 4 + 2]);
-                    s1 = o1; gstar = __float_as_int(cb[wv * 4 + 1]); ccol = cb[wv * 4 + 3];
+                const float4 cw = cb[wv];
+                const uint32_t o1 = __float_as_uint(cw.x);
+                if (o1 > k1) {                            // ties keep the lower wave = lower index
+                    k2 = max(max(k2, k1), __float_as_uint(cw.z));
+                    k1 = o1; gstar = __float_as_int(cw.y); ccol = cw.w;
                 } else {
-                    s2 = fmaxf(s2, o1);
+                    k2 = max(k2, o1);
                 }
             }
-            margin = fminf(margin, s1 > 0.f ? (s1 - fmaxf(s2, 0.f)) / s1 : 0.f);
+            if (WANT_MARGIN) {
+                const float s1 = __uint_as_float(k1 - 1u);
+                const float s2 = k2 ? __uint_as_float(k2 - 1u) : 0.f;
+                margin = fminf(margin, s1 > 0.f ? (s1 - s2) * __builtin_amdgcn_rcpf(s1) : 0.f);
+            }
             if (tid == gstar) selected = true;
 
             const float* grow = (GRAM_LDS ? gl : p.gram) + (size_t)gstar * N;
@@ -481,7 +515,7 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             }
             const float nrm2 = gdiag - piv;
             float inv = 0.f;
-            if (nrm2 > 1e-10f * gdiag && nrm2 > 0.f) inv = 1.0f / sqrtf(nrm2);
+            if (nrm2 > 1e-10f * gdiag && nrm2 > 0.f) inv = __builtin_amdgcn_rsqf(nrm2);
             else bad = 1;
             const float dv = (gmine - dot) * inv;
             const float bt = ccol * inv;
@@ -494,27 +528,48 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
 
     const bool want_fit = a.coef != nullptr || a.resid != nullptr;
     if (want_fit) {
-        // R[j][i] = Dt[selcol[i]][j] (j <= i).  One wavefront solves the triangular systems;
-        // lane i holds component i and pivots travel by scalar lane reads.
+        // R[j][i] = Dt[selcol[i]][j] (j <= i).  One wavefront solves the triangular systems: lane l
+        // holds component l, row l of R (upper solve) and column l of R (transposed solve) in
+        // registers, and the pivots travel by scalar lane reads.
+        float rrow[RF_MAXK], rcol[RF_MAXK], rinv = 0.f;
+        if (wave == 0) {
+            const bool lk = lane < k;
+            const float* own = Dt + (size_t)selcol[lk ? lane : 0] * KS;
+#pragma unroll
+            for (int i = 0; i < RF_MAXK; i += 4) {
+                const float4 v = (i < k) ? *reinterpret_cast<const float4*>(own + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                rcol[i] = (lk && i < lane) ? v.x : 0.f;
+                rcol[i + 1] = (lk && i + 1 < lane) ? v.y : 0.f;
+                rcol[i + 2] = (lk && i + 2 < lane) ? v.z : 0.f;
+                rcol[i + 3] = (lk && i + 3 < lane) ? v.w : 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < RF_MAXK; ++i)
+                rrow[i] = (i < k && lk && i > lane) ? Dt[(size_t)selcol[i] * KS + lane] : 0.f;
+            const float rd = lk ? own[lane] : 0.f;
+            rinv = rd > 0.f ? 1.0f / rd : 0.f;
+        }
         auto solve_upper = [&](float rhs) -> float {      // R x = rhs, back substitution
             float x = 0.f;
-            for (int i = k - 1; i >= 0; --i) {
-                const float* ri = Dt + (size_t)selcol[i] * KS;
-                const float rii = ri[i];
-                const float xi = rii > 0.f ? readlane_f32(rhs, i) / rii : 0.f;
-                if (lane == i) x = xi;
-                if (lane < i) rhs -= ri[lane] * xi;
+#pragma unroll
+            for (int i = RF_MAXK - 1; i >= 0; --i) {
+                if (i < k) {
+                    const float xi = readlane_f32(rhs, i) * readlane_f32(rinv, i);
+                    x = lane == i ? xi : x;
+                    rhs -= rrow[i] * xi;
+                }
             }
             return x;
         };
         auto solve_lower_t = [&](float rhs) -> float {    // R^T x = rhs, forward substitution
             float x = 0.f;
-            const float* rl = Dt + (size_t)selcol[lane < k ? lane : 0] * KS;
-            for (int i = 0; i < k; ++i) {
-                const float rii = Dt[(size_t)selcol[i] * KS + i];
-                const float xi = rii > 0.f ? readlane_f32(rhs, i) / rii : 0.f;
-                if (lane == i) x = xi;
-                if (lane > i && lane < k) rhs -= rl[i] * xi;
+#pragma unroll
+            for (int i = 0; i < RF_MAXK; ++i) {
+                if (i < k) {
+                    const float xi = readlane_f32(rhs, i) * readlane_f32(rinv, i);
+                    x = lane == i ? xi : x;
+                    rhs -= rcol[i] * xi;
+                }
             }
             return x;
         };
@@ -524,10 +579,10 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
         }
         __syncthreads();
         // explicit residual; thread i keeps its row of M_S in registers for the second pass
-        const int mrows = (m + NT - 1) / NT;              // rows per thread (1 unless m > NT)
         const bool one_row = mrows == 1;
         float mv[RF_MAXK];
         float racc = 0.f;
+        float* rv = lds + L.off_r;
         if (one_row) {
             if (tid < m) {
 #pragma unroll
@@ -535,7 +590,6 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
                 racc = yv[tid];
 #pragma unroll
                 for (int j = 0; j < RF_MAXK; ++j) if (j < k) racc -= alpha[j] * mv[j];
-                rv[tid] = racc;
             }
         } else {
             for (int i = tid; i < m; i += NT) {
@@ -543,8 +597,8 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
                 for (int j = 0; j < k; ++j) s -= alpha[j] * p.Mr[(size_t)i * N + selcol[j]];
                 rv[i] = s;
             }
+            __syncthreads();
         }
-        __syncthreads();
         // g = M_S^T r
         if (one_row) {
             const int mwaves = (m + 63) >> 6;
@@ -610,11 +664,22 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             for (int wv = 0; wv < nwaves; ++wv) tot += red[wv];
             a.resid[prob] = bad ? __int_as_float(0x7fc00000) : sqrtf(tot);
         }
-        if (a.margin) {
-            // every round wave tracked the same margin; wave 0 always owns atoms
-            a.margin[prob] = bad ? 0.f : margin;
-        }
+        if (WANT_MARGIN) a.margin[prob] = bad ? 0.f : margin;   // every round wave tracked the same value
     }
+}
+
+template <bool GRAM_LDS, bool WANT_MARGIN>
+static hipError_t launch_fast(const Plan& p, const RecoverArgs& a, const FastLayout& FL, int nthreads, hipStream_t s) {
+    const size_t bytes = (size_t)FL.total_floats * 4;
+    static size_t allowed = 0;              // raise the dynamic LDS limit only when a launch needs more
+    if (bytes > allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<GRAM_LDS, WANT_MARGIN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        allowed = bytes;
+    }
+    hipLaunchKernelGGL((recover_fast_kernel<GRAM_LDS, WANT_MARGIN>), dim3(a.B), dim3(nthreads), bytes, s, p, a, FL);
+    return hipGetLastError();
 }
 
 hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hipStream_t s) {
@@ -625,19 +690,11 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
         const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : RF_THREADS;
         FastLayout FL;
         if (make_fast_layout(p, a.k, lds_limit, nthreads, FL)) {
-            const size_t bytes = (size_t)FL.total_floats * 4;
-            if (FL.off_gram >= 0) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<true>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-                if (e != hipSuccess) return e;
-                hipLaunchKernelGGL(recover_fast_kernel<true>, dim3(a.B), dim3(nthreads), bytes, s, p, a, FL);
-            } else {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<false>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-                if (e != hipSuccess) return e;
-                hipLaunchKernelGGL(recover_fast_kernel<false>, dim3(a.B), dim3(nthreads), bytes, s, p, a, FL);
-            }
-            return hipGetLastError();
+            const bool gl = FL.off_gram >= 0, mg = a.margin != nullptr;
+            if (gl && mg) return launch_fast<true, true>(p, a, FL, nthreads, s);
+            if (gl && !mg) return launch_fast<true, false>(p, a, FL, nthreads, s);
+            if (!gl && mg) return launch_fast<false, true>(p, a, FL, nthreads, s);
+            return launch_fast<false, false>(p, a, FL, nthreads, s);
         }
     }
     const RecoverLayout L = make_layout(p, a.k, lds_limit);
@@ -645,9 +702,13 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
     if (p.N > 256) nt = 512;
     if (p.N > 512) nt = 1024;
     const size_t bytes = (size_t)L.total_floats * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess) return e;
+    static size_t allowed = 0;
+    if (bytes > allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        allowed = bytes;
+    }
     hipLaunchKernelGGL(recover_kernel, dim3(a.B), dim3(nt), bytes, s, p, a, L);
     return hipGetLastError();
 }
