@@ -177,6 +177,15 @@ cs_status cs_joint_select(cs_ctx* ctx, const cs_op* tok_op, const float* y_tok, 
                           const cs_op* ch_op, const cs_dict* ch_dict, const float* y_ch, int k_ch,
                           int32_t* tokens, int32_t* support, float* resid_norm, float* margin);
 
+/*
+ * Token-selection operator of Sec. 6 (the retained prompt x~ = Pi(r) x): copy the rows
+ * of x named by `tokens` into a dense matrix, in the order given.
+ *   x: [n_rows][d] in, tokens: int32[k_tok] with entries in [0, n_rows), out: [k_tok][d] out,
+ *   both of type `dtype`.  Requires d % 8 == 0.  An out-of-range entry yields a zero row.
+ */
+cs_status cs_gather_rows(cs_ctx* ctx, int dtype, const void* x, int n_rows, int d,
+                         const int32_t* tokens, int k_tok, void* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ CS_GAUSS, CS_RADEMACHER = 0, 1
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
-           "cs_recover_support", "cs_block_ffn", "cs_head_attn", "cs_joint_select")
+           "cs_recover_support", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_gather_rows")
 
 
 class CsOp(ctypes.Structure):
@@ -53,6 +53,7 @@ def load_library(path=LIB_PATH):
     lib.cs_head_attn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
     lib.cs_joint_select.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
                                     vp, i32, vp, vp, vp, vp]
+    lib.cs_gather_rows.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp]
     for name in EXPORTS:
         if name not in ("cs_destroy", "cs_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -150,6 +151,14 @@ class Context:
             out = torch.empty_like(q)
         self._check(self.lib.cs_head_attn(self._h, _dtype_code(q), _ptr(q), _ptr(K), _ptr(V), B, H, L, dh,
                                           _ptr(heads), kh, _ptr(out)))
+        return out
+
+    def cs_gather_rows(self, x, tokens, out=None):
+        n_rows, d = x.shape
+        k_tok = tokens.shape[0]
+        if out is None:
+            out = torch.empty((k_tok, d), dtype=x.dtype, device=x.device)
+        self._check(self.lib.cs_gather_rows(self._h, _dtype_code(x), _ptr(x), n_rows, d, _ptr(tokens), k_tok, _ptr(out)))
         return out
 
     def cs_joint_select(self, tok_op, y_tok, k_tok, ch_op, ch_dict, y_ch, k_ch):

@@ -332,4 +332,20 @@ cs_status cs_joint_select(cs_ctx* c, const cs_op* tok_op, const float* y_tok, in
                        "cs_joint_select: recovery");
 }
 
+cs_status cs_gather_rows(cs_ctx* c, int dtype, const void* x, int n_rows, int d,
+                         const int32_t* tokens, int k_tok, void* out) {
+    if (!c) return CS_EINVAL;
+    if (dtype != CS_F32 && dtype != CS_BF16) return fail(c, CS_EINVAL, "cs_gather_rows: unknown dtype %d", dtype);
+    if (d < 8 || (d % 8) || n_rows < 1) return fail(c, CS_EINVAL, "cs_gather_rows: need d %% 8 == 0 and n_rows >= 1");
+    if (k_tok < 0 || k_tok > 65535 * 1024) return fail(c, CS_EINVAL, "cs_gather_rows: k_tok out of range");
+    if (k_tok == 0) return CS_OK;
+    if (!x || !tokens || !out) return fail(c, CS_EINVAL, "cs_gather_rows: NULL buffer");
+    if (!aligned16(x) || !aligned16(tokens) || !aligned16(out)) return fail(c, CS_EALIGN, "cs_gather_rows: buffer not 16-byte aligned");
+    cs_status st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    hipError_t e = launch_gather_rows(x, n_rows, (size_t)d * (dtype == CS_F32 ? 4 : 2), tokens, k_tok, out, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_gather_rows");
+    return CS_OK;
+}
+
 }  // extern "C"

@@ -1,0 +1,237 @@
+// Block-sparse gated FFN as two gathered matrix products on the matrix cores, for
+// many rows per call: one shared support (task-conditioned prefill, paper Sec. 4)
+// or per-row supports over their union with a mask (token-adaptive batches, Sec. 5).
+// Here the path really is a dense contraction over the gathered blocks:
+//   H   = silu(X Wg_S^T) * (X Wu_S^T)      [T x |S|*64]   (K = d)
+//   out = H Wd_S                           [T x d]        (K = |S|*64)
+// Both products have K-contiguous operands (X and the weight rows for the first; H
+// and the [d][64] block slices of Wd for the second), so every tile is filled with
+// 16-byte loads.  Workgroup tile 128 x 128 (first product: 64 gate + 64 up columns
+// of one block), K step 64, four waves of 64 x 64, mfma_f32_32x32x16_bf16, fp32
+// accumulation, LDS double buffered with the next tile's global loads in flight
+// during the multiplies.  LDS rows are 128 bytes; the eight 16-byte chunks of a row
+// are stored XOR-swizzled by the row index so that fragment reads are conflict free.
+#include "kernels.hpp"
+
+namespace csk {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+constexpr int GM_BM = 128, GM_BN = 128, GM_BK = 64, GM_THREADS = 256;
+
+struct GemmArgs {
+    const uint16_t *Wg, *Wu, *Wd;
+    const uint16_t* x;
+    uint16_t* hid;            // [T][nb*64]
+    uint16_t* out;            // [T][d]
+    const int32_t* blocks;    // block index per slot of the gathered list
+    const int32_t* nblocks;   // device scalar: number of slots in use
+    const uint32_t* mask;     // [G][mask_words] token bitsets, or nullptr (every row uses every listed block)
+    int mask_words;
+    int T, d, G, nb_max;      // nb_max: row length of hid / 64
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return (row << 3) + (chunk ^ (row & 7)); }
+
+// rows of a [32 x 32] accumulator: register j of lane L is (row 8*(j/4) + 4*(L/32) + j%4, column L%32)
+__device__ __forceinline__ int acc_row(int j, int lane) { return 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3); }
+
+template <int MODE>          // 0: gate/up product with the activation epilogue, 1: down product
+__global__ __launch_bounds__(GM_THREADS)
+void ffn_gemm_kernel(GemmArgs a) {
+    __shared__ bf16x8_t As[2][GM_BM * 8];
+    __shared__ bf16x8_t Bs[2][GM_BN * 8];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nb = *a.nblocks;
+    const int bm = blockIdx.y * GM_BM;
+    const int d = a.d, T = a.T;
+    const int ldh = a.nb_max * 64;
+    int ktiles, g0 = 0, bn = 0;
+    if (MODE == 0) {
+        if ((int)blockIdx.x >= nb) return;
+        g0 = a.blocks[blockIdx.x];
+        ktiles = d / GM_BK;
+    } else {
+        bn = blockIdx.x * GM_BN;
+        ktiles = nb;
+    }
+    // global -> register staging: four 16-byte chunks of A and of B per thread and tile
+    bf16x8_t ra[4], rb[4];
+    auto fetch = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = tid + GM_THREADS * i, row = id >> 3, c = id & 7;
+            const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (MODE == 0) {
+                const int k0 = kt * GM_BK + c * 8;
+                ra[i] = (bm + row < T) ? *reinterpret_cast<const bf16x8_t*>(a.x + (size_t)(bm + row) * d + k0) : zero;
+                const uint16_t* w = row < 64 ? a.Wg + ((size_t)g0 * 64 + row) * d : a.Wu + ((size_t)g0 * 64 + row - 64) * d;
+                rb[i] = *reinterpret_cast<const bf16x8_t*>(w + k0);
+            } else {
+                ra[i] = (bm + row < T) ? *reinterpret_cast<const bf16x8_t*>(a.hid + (size_t)(bm + row) * ldh + kt * 64 + c * 8) : zero;
+                const int g = a.blocks[kt];
+                rb[i] = (bn + row < d) ? *reinterpret_cast<const bf16x8_t*>(a.Wd + ((size_t)g * d + bn + row) * 64 + c * 8) : zero;
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = tid + GM_THREADS * i, row = id >> 3, c = id & 7;
+            As[buf][swz(row, c)] = ra[i];
+            Bs[buf][swz(row, c)] = rb[i];
+        }
+    };
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int lr = lane & 31, lk = lane >> 5;
+    if (ktiles > 0) { fetch(0); stash(0); }
+    __syncthreads();
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < ktiles) fetch(kt + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8_t fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = wm * 64 + i * 32 + lr;
+                fa[i] = As[buf][swz(row, kk * 2 + lk)];
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                // first product: column tile j = 0 is gate, j = 1 the matching up channels
+                const int row = (MODE == 0) ? (j * 64 + wn * 32 + lr) : (wn * 64 + j * 32 + lr);
+                fb[j] = Bs[buf][swz(row, kk * 2 + lk)];
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < ktiles) {
+            stash(buf ^ 1);
+        }
+        __syncthreads();
+    }
+    // epilogue
+    if (MODE == 0) {
+        const int n = wn * 32 + lr;                  // channel inside the block
+        const uint32_t* mrow = a.mask ? a.mask + (size_t)g0 * a.mask_words : nullptr;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = bm + wm * 64 + i * 32 + acc_row(e, lane);
+                if (m < T) {
+                    const float gt = acc[i][0][e], up = acc[i][1][e];
+                    float hv = gt / (1.0f + __expf(-gt)) * up;
+                    if (mrow && !((mrow[m >> 5] >> (m & 31)) & 1u)) hv = 0.f;
+                    a.hid[(size_t)m * ldh + blockIdx.x * 64 + n] = f32_to_bf16(hv);
+                }
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = bm + wm * 64 + i * 32 + acc_row(e, lane);
+                    const int n = bn + wn * 64 + j * 32 + lr;
+                    if (m < T && n < d) a.out[(size_t)m * d + n] = f32_to_bf16(acc[i][j][e]);
+                }
+    }
+}
+
+// Gathered block list for per-row supports: token bitsets per block and the ordered
+// list of blocks used by at least one row.  One workgroup.
+__global__ __launch_bounds__(1024)
+void ffn_union_kernel(const int32_t* __restrict__ support, int T, int k, int G, int mask_words,
+                      uint32_t* __restrict__ mask, int32_t* __restrict__ blocks, int32_t* __restrict__ nblocks) {
+    __shared__ int wcount[16];
+    __shared__ int base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < G * mask_words; i += 1024) mask[i] = 0u;
+    if (tid == 0) base = 0;
+    __syncthreads();
+    __threadfence_block();
+    for (int i = tid; i < T * k; i += 1024) {
+        const int g = support[i], t = i / k;
+        if (g >= 0 && g < G) atomicOr(&mask[(size_t)g * mask_words + (t >> 5)], 1u << (t & 31));
+    }
+    __syncthreads();
+    for (int g0 = 0; g0 < G; g0 += 1024) {
+        const int g = g0 + tid;
+        bool used = false;
+        if (g < G)
+            for (int w = 0; w < mask_words; ++w) used |= mask[(size_t)g * mask_words + w] != 0u;
+        const unsigned long long bal = __ballot(used);
+        if (lane == 0) wcount[wave] = __popcll(bal);
+        __syncthreads();
+        int off = base;
+        for (int w = 0; w < wave; ++w) off += wcount[w];
+        if (used) blocks[off + __popcll(bal & ((1ull << lane) - 1ull))] = g;
+        __syncthreads();
+        if (tid == 0) { int tot = 0; for (int w = 0; w < 16; ++w) tot += wcount[w]; base += tot; }
+        __syncthreads();
+    }
+    if (tid == 0) *nblocks = base;
+}
+
+// Shared support: copy the list (dropping out-of-range entries) and its length.
+__global__ void ffn_shared_list_kernel(const int32_t* __restrict__ support, int k, int G,
+                                       int32_t* __restrict__ blocks, int32_t* __restrict__ nblocks) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        int n = 0;
+        for (int i = 0; i < k; ++i) { const int g = support[i]; if (g >= 0 && g < G) blocks[n++] = g; }
+        *nblocks = n;
+    }
+}
+
+bool ffn_gemm_ok(const FfnArgs& a) {
+    return a.dtype == 1 && a.b == 64 && (a.d % 64) == 0 && a.T > 16;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t ffn_gemm_scratch_bytes(const FfnArgs& a) {
+    const int nb_max = a.shared ? a.k : (a.G < a.T * a.k ? a.G : a.T * a.k);
+    const int mask_words = (a.T + 31) / 32;
+    return align256((size_t)a.T * nb_max * 64 * 2) + align256((size_t)a.G * 4 + 4) +
+           (a.shared ? 0 : align256((size_t)a.G * mask_words * 4)) + 256;
+}
+
+hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s) {
+    const int nb_max = a.shared ? a.k : (a.G < a.T * a.k ? a.G : a.T * a.k);
+    const int mask_words = (a.T + 31) / 32;
+    char* p = static_cast<char*>(a.scratch);
+    GemmArgs g;
+    g.hid = reinterpret_cast<uint16_t*>(p); p += align256((size_t)a.T * nb_max * 64 * 2);
+    int32_t* blocks = reinterpret_cast<int32_t*>(p);
+    int32_t* nblocks = blocks + a.G;
+    p += align256((size_t)a.G * 4 + 4);
+    uint32_t* mask = nullptr;
+    if (!a.shared) { mask = reinterpret_cast<uint32_t*>(p); }
+    g.Wg = (const uint16_t*)a.Wg; g.Wu = (const uint16_t*)a.Wu; g.Wd = (const uint16_t*)a.Wd;
+    g.x = (const uint16_t*)a.x; g.out = (uint16_t*)a.out;
+    g.blocks = blocks; g.nblocks = nblocks; g.mask = mask; g.mask_words = mask_words;
+    g.T = a.T; g.d = a.d; g.G = a.G; g.nb_max = nb_max;
+    if (a.shared) hipLaunchKernelGGL(ffn_shared_list_kernel, dim3(1), dim3(64), 0, s, a.support, a.k, a.G, blocks, nblocks);
+    else hipLaunchKernelGGL(ffn_union_kernel, dim3(1), dim3(1024), 0, s, a.support, a.T, a.k, a.G, mask_words, mask, blocks, nblocks);
+    const int mt = (a.T + GM_BM - 1) / GM_BM;
+    hipLaunchKernelGGL(ffn_gemm_kernel<0>, dim3(nb_max, mt), dim3(GM_THREADS), 0, s, g);
+    hipLaunchKernelGGL(ffn_gemm_kernel<1>, dim3((a.d + GM_BN - 1) / GM_BN, mt), dim3(GM_THREADS), 0, s, g);
+    return hipGetLastError();
+}
+
+}  // namespace csk

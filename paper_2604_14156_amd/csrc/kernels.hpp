@@ -36,6 +36,9 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
 hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s);
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s);
 
+// out[i][:] = x[tokens[i]][:], rows of `row_bytes` bytes (a multiple of 16)
+hipError_t launch_gather_rows(const void* x, int n_rows, size_t row_bytes, const int32_t* tokens, int k_tok,
+                              void* out, hipStream_t s);
 // zero `bytes` bytes (a multiple of 4) with a kernel, so that the call can be captured in a graph
 hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s);
 
@@ -47,6 +50,10 @@ struct FfnArgs {
     void* scratch; size_t scratch_bytes;
 };
 size_t ffn_scratch_bytes(const FfnArgs& a);
+// many-row path on the matrix cores (ffn_gemm.hip)
+bool ffn_gemm_ok(const FfnArgs& a);
+size_t ffn_gemm_scratch_bytes(const FfnArgs& a);
+hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s);
 hipError_t launch_block_ffn(const FfnArgs& a, hipStream_t s);
 
 struct AttnArgs {

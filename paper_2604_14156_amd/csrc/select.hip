@@ -120,6 +120,24 @@ void topk_kernel(const float* __restrict__ scores, int n, int k, int32_t* __rest
     }
 }
 
+// Token-selection operator: gather the kept rows.  One workgroup per output row.
+__global__ void gather_rows_kernel(const uint4* __restrict__ x, int n_rows, int chunks, const int32_t* __restrict__ tokens,
+                                   uint4* __restrict__ out) {
+    const int r = blockIdx.x;
+    const int src = tokens[r];
+    const bool ok = src >= 0 && src < n_rows;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x)
+        out[(size_t)r * chunks + c] = ok ? x[(size_t)src * chunks + c] : make_uint4(0u, 0u, 0u, 0u);
+}
+
+hipError_t launch_gather_rows(const void* x, int n_rows, size_t row_bytes, const int32_t* tokens, int k_tok,
+                              void* out, hipStream_t s) {
+    if (k_tok <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(k_tok), dim3(256), 0, s, reinterpret_cast<const uint4*>(x), n_rows,
+                       (int)(row_bytes / 16), tokens, reinterpret_cast<uint4*>(out));
+    return hipGetLastError();
+}
+
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s) {
     hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(TK_THREADS), 0, s, scores, n, k, out);
     return hipGetLastError();

@@ -42,6 +42,61 @@ def test_ffn_f32_ragged_shapes(cs, T):
     _ffn_case(cs, 1200 + T, 7, 24, 136, 7, T, "f32", False, 0.1)     # k == G: the dense layer
 
 
+@pytest.mark.parametrize("T,shared,G,k,d", [(300, True, 20, 5, 1024), (130, False, 12, 4, 512), (64, False, 9, 9, 256),
+                                            (257, True, 6, 1, 128)])
+def test_ffn_bf16_many_rows_matrix_core_path(cs, T, shared, G, k, d):
+    _ffn_case(cs, 1500 + T, G, 64, d, k, T, "bf16", shared, 0.05)
+
+
+def test_ffn_prefill_shape_full_size(cs):
+    """Task-conditioned prefill at full size: weights drawn on the device, oracle on sampled rows."""
+    c = wl.CFG4
+    T = 2048
+    gen = torch.Generator(device="cuda:0").manual_seed(41)
+    Wg, Wu = (torch.randn((c.G, c.b, c.d), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16) for _ in range(2))
+    Wd = torch.randn((c.G, c.d, c.b), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16)
+    x = torch.randn((T, c.d), generator=gen, device="cuda:0").to(torch.bfloat16)
+    sup = wl.random_supports(wl.rng_for(41), c.G, c.k, 1)[0]
+    out = cs.cs_block_ffn(Wg, Wu, Wd, x, dev_i32(sup), True)
+    torch.cuda.synchronize()
+    rows = [0, 127, 128, 1000, 2047]
+    hx = host(x[rows])
+    # the oracle needs only the kept blocks: gather them on the device, upcast on the host
+    idx = torch.from_numpy(sup.astype(np.int64)).to("cuda:0")
+    hWg, hWu, hWd = host(Wg[idx]), host(Wu[idx]), host(Wd[idx])
+    want = oracle.block_ffn(hWg, hWu, hWd, hx, np.arange(c.k))
+    got = host(out[rows])
+    for i in range(len(rows)):
+        assert rel_err(got[i], want[i]) <= 2e-2, (rows[i], rel_err(got[i], want[i]))
+
+
+def test_joint_prompt_shape_gather_and_ffn(cs):
+    """Kept-token gather followed by the shared-support FFN (joint selection workload), sampled rows."""
+    c = wl.CFG2
+    n_tok, k_tok = 8192, 2048
+    gen = torch.Generator(device="cuda:0").manual_seed(51)
+    Wg, Wu = (torch.randn((c.G, c.b, c.d), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16) for _ in range(2))
+    Wd = torch.randn((c.G, c.d, c.b), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16)
+    X = torch.randn((n_tok, c.d), generator=gen, device="cuda:0").to(torch.bfloat16)
+    rng = wl.rng_for(51)
+    tokens = np.sort(rng.choice(n_tok, size=k_tok, replace=False)).astype(np.int32)
+    sup = wl.random_supports(rng, c.G, c.k, 1)[0]
+    Xk = cs.cs_gather_rows(X, dev_i32(tokens))
+    torch.cuda.synchronize()
+    assert torch.equal(Xk, X[torch.from_numpy(tokens.astype(np.int64)).to("cuda:0")])       # byte-exact copy
+    out = cs.cs_block_ffn(Wg, Wu, Wd, Xk, dev_i32(sup), True)
+    rows = [0, 1, 1023, 2047]
+    idx = torch.from_numpy(sup.astype(np.int64)).to("cuda:0")
+    want = oracle.block_ffn(host(Wg[idx]), host(Wu[idx]), host(Wd[idx]), host(X[tokens[rows].astype(np.int64)]), np.arange(c.k))
+    got = host(out[rows])
+    for i in range(len(rows)):
+        assert rel_err(got[i], want[i]) <= 2e-2
+    # an out-of-range token yields a zero row
+    z = cs.cs_gather_rows(X, dev_i32(np.array([5, n_tok, -1, 7], dtype=np.int32)))
+    torch.cuda.synchronize()
+    assert float(z[1].float().abs().max()) == 0.0 and float(z[2].float().abs().max()) == 0.0 and torch.equal(z[3], X[7])
+
+
 def test_ffn_bf16_block_of_32_channels(cs):
     _ffn_case(cs, 1300, 12, 32, 256, 5, 4, "bf16", False, 0.05)
 
