@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the single-layer side measurements")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="for rocprofv3 --pmc runs: one 1 GiB device copy (calibration), then every call once per "
+                         "layer on one stream, no graphs, no timing")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     return ap.parse_args()
 
@@ -312,6 +315,15 @@ def main():
             rctx.cs_plan(st.ffn_op[l], st.ffn_dict[l], st.psi[l])
             rctx.cs_plan(st.head_op[l], st.head_dict)
         torch.cuda.synchronize()
+        if args.counter_pass:
+            src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+            dst = torch.empty_like(src)
+            dst.copy_(src)                           # known traffic: 1 GiB read + 1 GiB written
+            torch.cuda.synchronize()
+            decode_step(ctx, st, 0)
+            torch.cuda.synchronize()
+            print(json.dumps({"counter_pass": True, "calibration_copy_bytes": 1 << 30}))
+            return
         # one HIP graph per step: the launches of a step (two streams, 8 kernels per layer) are
         # replayed without host work in between
         graphs = None

@@ -15,9 +15,19 @@
 
 namespace csk {
 
-constexpr int AT_UNROLL = 8;            // key/value row pairs in flight per lane
-constexpr int AT_WAVES = 4;             // waves per workgroup
-constexpr int AT_TARGET_WGS = 2048;     // workgroups wanted in flight (8 per compute unit)
+// tuning knobs (overridable at compile time)
+#ifndef CS_AT_UNROLL
+#define CS_AT_UNROLL 8
+#endif
+#ifndef CS_AT_WAVES
+#define CS_AT_WAVES 4
+#endif
+#ifndef CS_AT_TARGET_WGS
+#define CS_AT_TARGET_WGS 2048
+#endif
+constexpr int AT_UNROLL = CS_AT_UNROLL;          // key/value row pairs in flight per lane
+constexpr int AT_WAVES = CS_AT_WAVES;            // waves per workgroup
+constexpr int AT_TARGET_WGS = CS_AT_TARGET_WGS;  // workgroups wanted in flight (8 per compute unit)
 constexpr int AT_MAX_SPLIT = 32;
 
 
@@ -35,6 +45,12 @@ template <> struct Frag8<float> {
         return s;
     }
     __device__ __forceinline__ float get(int i) const { return v[i]; }
+    // acc += w * row; returns the weight actually applied
+    __device__ __forceinline__ float axpy(float w, float acc[8]) const {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += w * v[i];
+        return w;
+    }
 };
 template <> struct Frag8<uint16_t> {
     uint4 r;
@@ -52,6 +68,22 @@ template <> struct Frag8<uint16_t> {
         const uint32_t w = i < 2 ? r.x : (i < 4 ? r.y : (i < 6 ? r.z : r.w));
         return (i & 1) ? bf16_hi(w) : bf16_lo(w);
     }
+    // acc += w * row without unpacking: the weight is rounded to bf16 and paired with a zero, so
+    // one packed dot product per element does the multiply-add.  Returns the rounded weight, which
+    // the caller also uses in the softmax denominator so that numerator and denominator agree.
+    __device__ __forceinline__ float axpy(float w, float acc[8]) const {
+        const uint32_t hi = (__float_as_uint(w) + 0x8000u) & 0xFFFF0000u;    // bf16(w) in the upper half
+        const uint32_t lo = hi >> 16;                                        // bf16(w) in the lower half
+        const bf16x2_t wl = *reinterpret_cast<const bf16x2_t*>(&lo), wh = *reinterpret_cast<const bf16x2_t*>(&hi);
+        const uint32_t rr[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bf16x2_t pr = *reinterpret_cast<const bf16x2_t*>(&rr[j]);
+            acc[2 * j] = __builtin_amdgcn_fdot2_f32_bf16(pr, wl, acc[2 * j], false);
+            acc[2 * j + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr, wh, acc[2 * j + 1], false);
+        }
+        return __uint_as_float(hi);
+    }
 };
 
 template <typename T, int DH, int NW, bool FINAL>
@@ -62,7 +94,7 @@ void attn_stream_kernel(const T* __restrict__ q, const T* __restrict__ K, const 
     constexpr int LPP = DH / 8;              // lanes per position
     constexpr int PPW = 64 / LPP;            // positions per wavefront step
     constexpr int STEP = PPW * NW;           // positions per workgroup step
-    __shared__ float sm[NW * PPW][DH + 2];
+    __shared__ float sm[NW][DH + 2];
 
     const int split = blockIdx.x, h = blockIdx.y, seq = blockIdx.z;
     const int nsplit = gridDim.x;
@@ -101,46 +133,66 @@ void attn_stream_kernel(const T* __restrict__ q, const T* __restrict__ K, const 
             kv[u].load(Kh + (size_t)p * DH);
             vv[u].load(Vh + (size_t)p * DH);
         }
+        // scores of the whole batch first, then one rescale of the running state
+        float sc_u[AT_UNROLL];
+        float mblk = -INFINITY;
 #pragma unroll
         for (int u = 0; u < AT_UNROLL; ++u) {
-            const int p = p0 + u * STEP;
             const float s = group_sum<LPP>(kv[u].dot(qf)) * sc;
-            if (p < p_end) {
-                const float mnew = fmaxf(mrun, s);
-                const float corr = exp2f(mrun - mnew);           // mrun = -inf gives 0
-                const float w = exp2f(s - mnew);
-                lrun = lrun * corr + w;
+            sc_u[u] = (p0 + u * STEP < p_end) ? s : -INFINITY;     // u = 0 is always in range
+            mblk = fmaxf(mblk, sc_u[u]);
+        }
+        const float mnew = fmaxf(mrun, mblk);
+        const float corr = __builtin_amdgcn_exp2f(mrun - mnew);    // first batch: exp2(-inf) = 0
+        mrun = mnew;
+        lrun *= corr;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = acc[i] * corr + w * vv[u].get(i);
-                mrun = mnew;
-            }
+        for (int i = 0; i < 8; ++i) acc[i] *= corr;
+#pragma unroll
+        for (int u = 0; u < AT_UNROLL; ++u) {
+            const float w = __builtin_amdgcn_exp2f(sc_u[u] - mnew);
+            lrun += vv[u].axpy(w, acc);
         }
     }
-    // merge the lane groups of all waves
-    const int row = wave * PPW + grp;
+    // merge the lane groups of a wave on the lane crossbar: after this every group holds the wave's state
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sm[row][sub * 8 + i] = acc[i];
-    if (sub == 0) { sm[row][DH] = mrun; sm[row][DH + 1] = lrun; }
+    for (int off = LPP; off < 64; off <<= 1) {
+        const float mo = __shfl_xor(mrun, off, 64), lo = __shfl_xor(lrun, off, 64);
+        const float mn = fmaxf(mrun, mo);
+        const float c1 = mrun > -INFINITY ? __builtin_amdgcn_exp2f(mrun - mn) : 0.f;
+        const float c2 = mo > -INFINITY ? __builtin_amdgcn_exp2f(mo - mn) : 0.f;
+        lrun = lrun * c1 + lo * c2;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = acc[i] * c1 + __shfl_xor(acc[i], off, 64) * c2;
+        mrun = mn;
+    }
+    // merge the waves through LDS
+    if (grp == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sm[wave][sub * 8 + i] = acc[i];
+        if (sub == 0) { sm[wave][DH] = mrun; sm[wave][DH + 1] = lrun; }
+    }
     __syncthreads();
     float mtot = -INFINITY;
-    for (int r = 0; r < NW * PPW; ++r) mtot = fmaxf(mtot, sm[r][DH]);
-    float den = 0.f;
-    if (FINAL || threadIdx.x == 0)
-        for (int r = 0; r < NW * PPW; ++r) {
-            const float mr = sm[r][DH];
-            if (mr > -INFINITY) den += exp2f(mr - mtot) * sm[r][DH + 1];
-        }
+#pragma unroll
+    for (int r = 0; r < NW; ++r) mtot = fmaxf(mtot, sm[r][DH]);
+    float wr[NW], den = 0.f;
+#pragma unroll
+    for (int r = 0; r < NW; ++r) {
+        const float mr = sm[r][DH];
+        wr[r] = mr > -INFINITY ? __builtin_amdgcn_exp2f(mr - mtot) : 0.f;
+        den += wr[r] * sm[r][DH + 1];
+    }
     float* dst = FINAL ? nullptr : part + (((size_t)seq * kh + slot) * nsplit + split) * (DH + 2);
     for (int c = threadIdx.x; c < DH; c += NW * 64) {
         float v = 0.f;
-        for (int r = 0; r < NW * PPW; ++r) {
-            const float mr = sm[r][DH];
-            if (mr > -INFINITY) v += exp2f(mr - mtot) * sm[r][c];
-        }
+#pragma unroll
+        for (int r = 0; r < NW; ++r) v += wr[r] * sm[r][c];
         if (FINAL) store1(out + head_off * DH + c, den > 0.f ? v / den : 0.f);
         else dst[2 + c] = v;                                     // layout: [max, sum, acc[DH]]
     }
-    if (!FINAL && threadIdx.x == 0) { dst[0] = mtot; dst[1] = den; }
+    if (FINAL) return;
+    if (threadIdx.x == 0) { dst[0] = mtot; dst[1] = den; }
 }
 
 // One thread per output element: merge the position ranges of a kept head (pruned

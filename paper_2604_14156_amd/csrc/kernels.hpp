@@ -61,6 +61,7 @@ struct AttnArgs {
     const void *q, *K, *V; int B, H, L, dh;
     const int32_t* heads; int kh; void* out;
     void* scratch; size_t scratch_bytes;
+    void* sync; size_t sync_bytes;      // zero-initialised counters; every kernel leaves them at zero
 };
 size_t attn_scratch_bytes(const AttnArgs& a);
 hipError_t launch_head_attn(const AttnArgs& a, hipStream_t s);
