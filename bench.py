@@ -102,10 +102,13 @@ class DecodeState:
         self.resid = torch.empty((B,), device=dev)
         self.margin = torch.empty((B,), device=dev)
         self.marginh = torch.empty((B,), device=dev)
-        self.y2 = [torch.empty((B, c.m), device=dev) for _ in range(2)]
-        self.yh2 = [torch.empty((B, hs.m), device=dev) for _ in range(2)]
-        self.margin2 = [torch.empty((B,), device=dev) for _ in range(2)]
-        self.marginh2 = [torch.empty((B,), device=dev) for _ in range(2)]
+        # per-layer buffers of the pipelined step
+        self.y_l = [torch.empty((B, c.m), device=dev) for _ in range(layers)]
+        self.yh_l = [torch.empty((B, hs.m), device=dev) for _ in range(layers)]
+        self.S_l = [torch.empty((B, c.k), dtype=torch.int32, device=dev) for _ in range(layers)]
+        self.heads_l = [torch.empty((B, hs.kh), dtype=torch.int32, device=dev) for _ in range(layers)]
+        self.margin_l = [torch.empty((B,), device=dev) for _ in range(layers)]
+        self.marginh_l = [torch.empty((B,), device=dev) for _ in range(layers)]
         self.o = torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf)
         self.out = torch.empty((B, c.d), device=dev, dtype=bf)
 
@@ -133,30 +136,35 @@ def decode_step(ctx, st, i, ev=None):
         timed("ffn", lambda: ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S[0], False, st.out))
 
 
-def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec):
-    """The same step with measurement and recovery on a second stream, one layer ahead of
-    execution (the recovered support is consumed by the next piece of reduced computation,
-    paper Sec. 5).  Support buffers are double buffered; events order the two streams."""
+PIPE_DEPTH = 4      # layers the recovery stream may run ahead of execution
+
+
+def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec, depth=None):
+    """The same step with measurement and recovery on a second stream, running ahead of execution
+    (the recovered support is consumed by a later piece of reduced computation, paper Sec. 5).
+    Every layer has its own support buffers; execution of layer l waits for the event that marks
+    its supports ready, and recovery of layer l waits until execution has finished layer l - depth,
+    which keeps the two streams interleaved when the step is replayed as a graph."""
     c, hs = st.c, st.hs
+    depth = PIPE_DEPTH if depth is None else depth
     s_rec.wait_stream(s_exec)
     done = [None] * st.layers
     for l in range(st.layers):
-        buf = l & 1
         with torch.cuda.stream(s_rec):
-            if l >= 2:
-                s_rec.wait_event(done[l - 2])            # layer l-2 has finished reading this buffer
-            rctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh2[buf])
-            rctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh2[buf], st.heads[buf],
-                                    None, None, st.marginh2[buf], want_coef=False, want_resid=False)
-            rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y2[buf])
-            rctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y2[buf], st.S[buf],
-                                    None, None, st.margin2[buf], want_coef=False, want_resid=False)
+            if l >= depth:
+                s_rec.wait_event(done[l - depth])
+            rctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh_l[l])
+            rctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh_l[l], st.heads_l[l],
+                                    None, None, st.marginh_l[l], want_coef=False, want_resid=False)
+            rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y_l[l])
+            rctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y_l[l], st.S_l[l],
+                                    None, None, st.margin_l[l], want_coef=False, want_resid=False)
             ready = torch.cuda.Event()
             ready.record(s_rec)
         with torch.cuda.stream(s_exec):
             s_exec.wait_event(ready)
-            ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads[buf], st.o)
-            ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S[buf], False, st.out)
+            ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads_l[l], st.o)
+            ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S_l[l], False, st.out)
             done[l] = torch.cuda.Event()
             done[l].record(s_exec)
     s_exec.wait_stream(s_rec)

@@ -285,7 +285,7 @@ cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, con
     FfnArgs a;
     a.dtype = dtype; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.d = d; a.G = G; a.b = b;
     a.x = x; a.T = T; a.support = support; a.k = k; a.shared = shared ? 1 : 0; a.out = out;
-    a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes;
+    a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes; a.sync = c->sync;
     const size_t need = ffn_scratch_bytes(a);
     if (need > c->scratch_bytes)
         return fail(c, CS_ENOMEM, "cs_block_ffn: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);

@@ -122,79 +122,96 @@ __device__ __forceinline__ bf16x8_t zero_frag() {
 
 // Token masks per block and the compacted list of blocks used by at least one token.
 // mask[g] bit t = token t lists block g.  Returns the number of listed blocks.
+template <int NWAVES>
 __device__ __forceinline__ int build_block_list(const int32_t* __restrict__ support, int T, int k, int shared, int G,
                                                 uint32_t* mask, uint16_t* ulist, int* wcount) {
+    constexpr int NTH = NWAVES * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int g = tid; g < G; g += FD_THREADS) mask[g] = 0u;
+    for (int g = tid; g < G; g += NTH) mask[g] = 0u;
     __syncthreads();
     const int total = shared ? k : T * k;
     const uint32_t allbits = T >= 32 ? 0xFFFFFFFFu : ((1u << T) - 1u);
-    for (int i = tid; i < total; i += FD_THREADS) {
+    for (int i = tid; i < total; i += NTH) {
         const int g = support[i];
         if (g >= 0 && g < G) atomicOr(&mask[g], shared ? allbits : (1u << (i / k)));
     }
     __syncthreads();
-    // ordered compaction, 64 blocks per wave
-    const int g = wave * 64 + lane;
-    const bool used = g < G && mask[g] != 0u;
-    const unsigned long long bal = __ballot(used);
-    if (lane == 0) wcount[wave] = __popcll(bal);
-    __syncthreads();
-    int off = 0, tot = 0;
-    for (int w = 0; w < FD_WAVES; ++w) { const int c = wcount[w]; if (w < wave) off += c; tot += c; }
-    if (used) ulist[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)g;
-    __syncthreads();
-    return tot;
+    // ordered compaction, 64 blocks per wave and pass
+    int base = 0;
+    for (int g0 = 0; g0 < G; g0 += NTH) {
+        const int g = g0 + tid;
+        const bool used = g < G && mask[g] != 0u;
+        const unsigned long long bal = __ballot(used);
+        if (lane == 0) wcount[wave] = __popcll(bal);
+        __syncthreads();
+        int off = base, tot = 0;
+        for (int w = 0; w < NWAVES; ++w) { const int c = wcount[w]; if (w < wave) off += c; tot += c; }
+        if (used) ulist[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)g;
+        base += tot;
+        __syncthreads();
+    }
+    return base;
 }
 
 template <int NS>
 __global__ __launch_bounds__(FD_THREADS)
 void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
                      const uint16_t* __restrict__ x, int T, const int32_t* __restrict__ support, int k, int shared,
-                     uint16_t* __restrict__ hbuf) {
+                     uint16_t* __restrict__ hbuf, int* __restrict__ sync) {
     __shared__ uint32_t mask[FD_MAXG];
     __shared__ uint16_t ulist[FD_MAXG];
     __shared__ int wcount[FD_WAVES];
     __shared__ float red[2][FD_WAVES][256];
+    __shared__ int ticket[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nblocks = build_block_list(support, T, k, shared, G, mask, ulist, wcount);
-    const int cpb = b >> 3;                           // 8-channel chunks per block
-    const int nitems = nblocks * cpb;
     const int ln = lane & 15, kg = lane >> 4;         // tile column / row index, k-group
+    // k-steps of this wave: pairs of adjacent 32-column steps, so that a wave reads whole 128-byte lines
+    auto kcol = [&](int s) { return (((s >> 1) * FD_WAVES + wave) * 2 + (s & 1)) * 32; };
 
-    // this wave's slice of the token rows, kept in registers
+    // this wave's slice of the token rows, kept in registers (issued before the block list is built)
     bf16x8_t xa[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-        const int kk = (wave + FD_WAVES * s) * 32;
+        const int kk = kcol(s);
         xa[s] = (kk < d && ln < T) ? load_frag(x + (size_t)ln * d + kk + kg * 8) : zero_frag();
     }
+    // work items are handed out by a device-wide counter (sync[0]); a workgroup that starts late, or
+    // not at all while its compute unit is busy with another kernel, simply takes fewer items.
+        // Tickets are drawn two items ahead so that the atomic's latency never sits on the critical path.
+    // The first item of a workgroup is its own index; the rest are tickets gridDim.x + n.
+    int t_first = 0;
+    if (tid == 0) t_first = atomicAdd(&sync[0], 1);   // result not needed before the list is built
+    const int nblocks = build_block_list<FD_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
+    const int cpb = b >> 3;                           // 8-channel chunks per block
+    const int nitems = nblocks * cpb;
+    if (tid == 0) { ticket[0] = blockIdx.x; ticket[1] = (int)gridDim.x + t_first; }
+    __syncthreads();
     auto row_ptr = [&](int item) -> const uint16_t* {
         const int g = ulist[item / cpb], cc = item % cpb;
         const uint16_t* base = ln < 8 ? Wg : Wu;
         return base + ((size_t)g * b + cc * 8 + (ln & 7)) * d + kg * 8;
     };
     bf16x8_t wb[NS], wn[NS];
-    int item = blockIdx.x;
+    int item = ticket[0], next = ticket[1];
     if (item < nitems) {
         const uint16_t* rp = row_ptr(item);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            const int kk = (wave + FD_WAVES * s) * 32;
+            const int kk = kcol(s);
             wb[s] = kk < d ? load_frag(rp + kk) : zero_frag();
         }
     }
-    int buf = 0;
-    for (; item < nitems; item += gridDim.x) {
-        const int next = item + gridDim.x;
+    int buf = 0, it = 0;
+    while (item < nitems) {
         if (next < nitems) {
             const uint16_t* rp = row_ptr(next);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-                const int kk = (wave + FD_WAVES * s) * 32;
+                const int kk = kcol(s);
                 wn[s] = kk < d ? load_frag(rp + kk) : zero_frag();
             }
         }
+        if (tid == 0) ticket[(it & 1) + 2] = (int)gridDim.x + atomicAdd(&sync[0], 1);   // the item after next
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[s], wb[s], acc, 0, 0, 0);
@@ -215,43 +232,68 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
             }
         }
         buf ^= 1;
+        item = next;
+        next = ticket[(it & 1) + 2];          // written before the barrier above
+        ++it;
 #pragma unroll
         for (int s = 0; s < NS; ++s) wb[s] = wn[s];
     }
+    // the last workgroup to leave puts the counters back to zero for the next launch
+    __syncthreads();
+    if (tid == 0) {
+        const int gone = atomicAdd(&sync[1], 1);
+        if (gone == (int)gridDim.x - 1) { sync[0] = 0; sync[1] = 0; }
+    }
 }
 
-__global__ __launch_bounds__(FD_THREADS)
+// Down projection.  8 waves per workgroup and at most 128 registers per lane, so that two
+// workgroups fit on a compute unit when some units are busy with another stream's kernels.
+constexpr int DN_WAVES = 8;
+constexpr int DN_UB = 6;                              // blocks in flight per wave
+
+__global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
-                   int T, const int32_t* __restrict__ support, int k, int shared, uint16_t* __restrict__ out) {
+                   int T, const int32_t* __restrict__ support, int k, int shared, uint16_t* __restrict__ out,
+                   int* __restrict__ sync) {
     __shared__ uint32_t mask[FD_MAXG];
     __shared__ uint16_t ulist[FD_MAXG];
-    __shared__ int wcount[FD_WAVES];
-    __shared__ float red[FD_WAVES][256];
+    __shared__ int wcount[DN_WAVES];
+    __shared__ float red[DN_WAVES][256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nblocks = build_block_list(support, T, k, shared, G, mask, ulist, wcount);
+    __shared__ int ticket[2];
+    int t_first = 0;
+    if (tid == 0) t_first = atomicAdd(&sync[2], 1);
+    const int nblocks = build_block_list<DN_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
     const int ln = lane & 15, kg = lane >> 4;
-    const int col0 = blockIdx.x * 16;
-    const bool row_ok = col0 + ln < d;
+    const bool tok_ok = ln < T;                       // rows of the hidden-value operand beyond T are zero
     const int ksteps = b >> 5;                        // 32 channels per matrix instruction
+    const int ntiles = (d + 15) >> 4;
+    // column tiles are handed out like the items of the gate/up kernel: own index first, then tickets
+    int tile = blockIdx.x, it = 0;
+    if (tid == 0) ticket[0] = (int)gridDim.x + t_first;
+    __syncthreads();
+    while (tile < ntiles) {
+    const int col0 = tile * 16;
+    const bool row_ok = col0 + ln < d;
+    if (tid == 0 && it > 0) ticket[it & 1] = (int)gridDim.x + atomicAdd(&sync[2], 1);
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-    constexpr int UB = 4;                             // blocks in flight per wave
-    for (int u0 = wave; u0 < nblocks; u0 += FD_WAVES * UB) {
+    for (int u0 = wave; u0 < nblocks; u0 += DN_WAVES * DN_UB) {
         for (int ks = 0; ks < ksteps; ks += 2) {
-            bf16x8_t wa[UB][2], hb[UB][2];
+            bf16x8_t wa[DN_UB][2], hb[DN_UB][2];
 #pragma unroll
-            for (int q = 0; q < UB; ++q) {
-                const int u = u0 + q * FD_WAVES;
+            for (int q = 0; q < DN_UB; ++q) {
+                const int u = u0 + q * DN_WAVES;
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
                     const bool ok = u < nblocks && ks + e < ksteps;
                     const int g = ok ? ulist[u] : 0;
                     const int ch = (ks + e) * 32 + kg * 8;
                     wa[q][e] = (ok && row_ok) ? load_frag(Wd + ((size_t)g * d + col0 + ln) * b + ch) : zero_frag();
-                    hb[q][e] = ok ? load_frag(hbuf + ((size_t)g * 16 + ln) * b + ch) : zero_frag();
+                    hb[q][e] = (ok && tok_ok) ? load_frag(hbuf + ((size_t)g * 16 + ln) * b + ch) : zero_frag();
                 }
             }
 #pragma unroll
-            for (int q = 0; q < UB; ++q)
+            for (int q = 0; q < DN_UB; ++q)
 #pragma unroll
                 for (int e = 0; e < 2; ++e)
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[q][e], hb[q][e], acc, 0, 0, 0);
@@ -263,31 +305,49 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     if (tid < 256) {
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < FD_WAVES; ++w) s += red[w][tid];
+        for (int w = 0; w < DN_WAVES; ++w) s += red[w][tid];
         const int col = col0 + 4 * (tid >> 6) + (tid & 3), tok = (tid >> 2) & 15;
         if (tok < T && col < d) out[(size_t)tok * d + col] = f32_to_bf16(s);
     }
+    tile = ticket[it & 1];                            // drawn at the top of this round (or before the loop)
+    ++it;
+    __syncthreads();                                  // red[] and the ticket slot are reused
+    }
+    if (tid == 0) {
+        const int gone = atomicAdd(&sync[3], 1);
+        if (gone == (int)gridDim.x - 1) { sync[2] = 0; sync[3] = 0; }
+    }
+}
+
+// k-steps per wave of the gate/up kernel: pairs of 32-column steps dealt round-robin to the 16 waves
+static int gateup_steps(int d) {
+    const int pairs = (d + 63) / 64;
+    return 2 * ((pairs + FD_WAVES - 1) / FD_WAVES);
 }
 
 static bool mfma_decode_ok(const FfnArgs& a) {
     return a.dtype == 1 && a.T <= 16 && a.G <= FD_MAXG && (a.d % 32) == 0 && (a.b % 32) == 0 &&
-           (a.d / 32 + FD_WAVES - 1) / FD_WAVES <= 16;
+           gateup_steps(a.d) <= 16;
 }
 
 static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(a.scratch);
-    const int ns = (a.d / 32 + FD_WAVES - 1) / FD_WAVES;
+    const int ns = gateup_steps(a.d);
     const int cpb = a.b / 8;
     const int union_max = a.shared ? a.k : (a.T * a.k < a.G ? a.T * a.k : a.G);
     int grid = union_max * cpb;
     if (grid > 256) grid = 256;                       // one workgroup of 16 waves per compute unit
     if (grid < 1) grid = 1;
 #define CS_GU(NSV) hipLaunchKernelGGL((ffn_gateup_mfma<NSV>), dim3(grid), dim3(FD_THREADS), 0, s, \
-        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf)
-    if (ns <= 1) CS_GU(1); else if (ns <= 2) CS_GU(2); else if (ns <= 4) CS_GU(4); else if (ns <= 8) CS_GU(8); else CS_GU(16);
+        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf, \
+        reinterpret_cast<int*>(a.sync))
+    if (ns <= 2) CS_GU(2); else if (ns <= 4) CS_GU(4); else if (ns <= 8) CS_GU(8); else CS_GU(16);
 #undef CS_GU
-    hipLaunchKernelGGL(ffn_down_mfma, dim3((a.d + 15) / 16), dim3(FD_THREADS), 0, s,
-                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, a.support, a.k, a.shared, (uint16_t*)a.out);
+    int dgrid = (a.d + 15) / 16;
+    if (dgrid > 256) dgrid = 256;
+    hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), 0, s,
+                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, a.support, a.k, a.shared, (uint16_t*)a.out,
+                       reinterpret_cast<int*>(a.sync));
     return hipGetLastError();
 }
 

@@ -48,6 +48,7 @@ struct FfnArgs {
     const void* x; int T; const int32_t* support; int k; int shared;
     void* out;
     void* scratch; size_t scratch_bytes;
+    void* sync;           // zero-initialised device counters; every kernel leaves them at zero
 };
 size_t ffn_scratch_bytes(const FfnArgs& a);
 // many-row path on the matrix cores (ffn_gemm.hip)
