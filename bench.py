@@ -136,37 +136,44 @@ def decode_step(ctx, st, i, ev=None):
         timed("ffn", lambda: ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S[0], False, st.out))
 
 
-PIPE_DEPTH = 4      # layers the recovery stream may run ahead of execution
+PIPE_CHUNK = 1      # layers per synchronisation point between the two streams
+PIPE_AHEAD = 4      # chunks the recovery stream may run ahead of execution
 
 
-def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec, depth=None):
+def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec, chunk=None, ahead=None):
     """The same step with measurement and recovery on a second stream, running ahead of execution
     (the recovered support is consumed by a later piece of reduced computation, paper Sec. 5).
-    Every layer has its own support buffers; execution of layer l waits for the event that marks
-    its supports ready, and recovery of layer l waits until execution has finished layer l - depth,
-    which keeps the two streams interleaved when the step is replayed as a graph."""
+    Every layer has its own support buffers.  The streams meet once per chunk of layers: execution
+    of a chunk waits for the event that marks the chunk's supports ready, and recovery of chunk c
+    waits until execution has finished chunk c - ahead, which keeps the two streams interleaved
+    when the step is replayed as a graph without a cross-stream edge at every layer."""
     c, hs = st.c, st.hs
-    depth = PIPE_DEPTH if depth is None else depth
+    chunk = PIPE_CHUNK if chunk is None else chunk
+    ahead = PIPE_AHEAD if ahead is None else ahead
     s_rec.wait_stream(s_exec)
-    done = [None] * st.layers
-    for l in range(st.layers):
+    nchunks = (st.layers + chunk - 1) // chunk
+    done = [None] * nchunks
+    for ci in range(nchunks):
+        layers = range(ci * chunk, min(st.layers, (ci + 1) * chunk))
         with torch.cuda.stream(s_rec):
-            if l >= depth:
-                s_rec.wait_event(done[l - depth])
-            rctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh_l[l])
-            rctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh_l[l], st.heads_l[l],
-                                    None, None, st.marginh_l[l], want_coef=False, want_resid=False)
-            rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y_l[l])
-            rctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y_l[l], st.S_l[l],
-                                    None, None, st.margin_l[l], want_coef=False, want_resid=False)
+            if ci >= ahead:
+                s_rec.wait_event(done[ci - ahead])
+            for l in layers:
+                rctx.cs_sketch(st.head_op[l], st.u[i][l], st.yh_l[l])
+                rctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh_l[l], st.heads_l[l],
+                                        None, None, st.marginh_l[l], want_coef=False, want_resid=False)
+                rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y_l[l])
+                rctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y_l[l], st.S_l[l],
+                                        None, None, st.margin_l[l], want_coef=False, want_resid=False)
             ready = torch.cuda.Event()
             ready.record(s_rec)
         with torch.cuda.stream(s_exec):
             s_exec.wait_event(ready)
-            ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads_l[l], st.o)
-            ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S_l[l], False, st.out)
-            done[l] = torch.cuda.Event()
-            done[l].record(s_exec)
+            for l in layers:
+                ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads_l[l], st.o)
+                ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S_l[l], False, st.out)
+            done[ci] = torch.cuda.Event()
+            done[ci].record(s_exec)
     s_exec.wait_stream(s_rec)
 
 
