@@ -25,6 +25,7 @@ struct GemmArgs {
     const uint16_t* x;
     uint16_t* hid;            // [T][nb*64]
     uint16_t* out;            // [T][d]
+    float* partial;           // [splits][T][d] fp32, split-K only
     const int32_t* blocks;    // block index per slot of the gathered list
     const int32_t* nblocks;   // device scalar: number of slots in use
     const uint32_t* mask;     // [G][mask_words] token bitsets, or nullptr (every row uses every listed block)
@@ -37,101 +38,127 @@ __device__ __forceinline__ int swz(int row, int chunk) { return (row << 3) + (ch
 // rows of a [32 x 32] accumulator: register j of lane L is (row 8*(j/4) + 4*(L/32) + j%4, column L%32)
 __device__ __forceinline__ int acc_row(int j, int lane) { return 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3); }
 
-template <int MODE>          // 0: gate/up product with the activation epilogue, 1: down product
+// MODE 0: gate/up product with the activation epilogue; MODE 1: down product.
+// BM: rows per workgroup tile (128, or 64 for short batches).  SPLITK (MODE 1 only): the K range is
+// divided over gridDim.z workgroups that write fp32 partial tiles, summed by ffn_splitk_reduce_kernel.
+template <int MODE, int BM, bool SPLITK>
 __global__ __launch_bounds__(GM_THREADS)
 void ffn_gemm_kernel(GemmArgs a) {
-    __shared__ bf16x8_t As[2][GM_BM * 8];
+    constexpr int MI = BM / 64;                       // 32-row tiles per wave
+    constexpr int ACH = BM / 32;                      // 16-byte chunks of A per thread and tile
+    __shared__ bf16x8_t As[2][BM * 8];
     __shared__ bf16x8_t Bs[2][GM_BN * 8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int nb = *a.nblocks;
-    const int bm = blockIdx.y * GM_BM;
+    const int bm = blockIdx.y * BM;
     const int d = a.d, T = a.T;
     const int ldh = a.nb_max * 64;
-    int ktiles, g0 = 0, bn = 0;
+    int kt0 = 0, kt1, g0 = 0, bn = 0;
     if (MODE == 0) {
         if ((int)blockIdx.x >= nb) return;
         g0 = a.blocks[blockIdx.x];
-        ktiles = d / GM_BK;
+        kt1 = d / GM_BK;
     } else {
         bn = blockIdx.x * GM_BN;
-        ktiles = nb;
+        kt1 = nb;
+        if (SPLITK) {
+            const int per = (nb + (int)gridDim.z - 1) / (int)gridDim.z;
+            kt0 = blockIdx.z * per;
+            kt1 = min(nb, kt0 + per);
+        }
     }
-    // global -> register staging: four 16-byte chunks of A and of B per thread and tile
-    bf16x8_t ra[4], rb[4];
-    auto fetch = [&](int kt) {
+    const int ktiles = kt1 > kt0 ? kt1 - kt0 : 0;
+    // global -> register staging: 16-byte chunks of A and of B per thread and tile.  Two tiles are
+    // kept in flight (register sets 0 and 1) besides the one being multiplied out of LDS.
+    bf16x8_t ra[2][ACH], rb[2][4];
+    auto fetch = [&](int set, int kt) {
+        kt += kt0;
+        const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            const int id = tid + GM_THREADS * i, row = id >> 3, c = id & 7;
+            if (MODE == 0)
+                ra[set][i] = (bm + row < T) ? *reinterpret_cast<const bf16x8_t*>(a.x + (size_t)(bm + row) * d + kt * GM_BK + c * 8) : zero;
+            else
+                ra[set][i] = (bm + row < T) ? *reinterpret_cast<const bf16x8_t*>(a.hid + (size_t)(bm + row) * ldh + kt * 64 + c * 8) : zero;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int id = tid + GM_THREADS * i, row = id >> 3, c = id & 7;
-            const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
             if (MODE == 0) {
-                const int k0 = kt * GM_BK + c * 8;
-                ra[i] = (bm + row < T) ? *reinterpret_cast<const bf16x8_t*>(a.x + (size_t)(bm + row) * d + k0) : zero;
                 const uint16_t* w = row < 64 ? a.Wg + ((size_t)g0 * 64 + row) * d : a.Wu + ((size_t)g0 * 64 + row - 64) * d;
-                rb[i] = *reinterpret_cast<const bf16x8_t*>(w + k0);
+                rb[set][i] = *reinterpret_cast<const bf16x8_t*>(w + kt * GM_BK + c * 8);
             } else {
-                ra[i] = (bm + row < T) ? *reinterpret_cast<const bf16x8_t*>(a.hid + (size_t)(bm + row) * ldh + kt * 64 + c * 8) : zero;
                 const int g = a.blocks[kt];
-                rb[i] = (bn + row < d) ? *reinterpret_cast<const bf16x8_t*>(a.Wd + ((size_t)g * d + bn + row) * 64 + c * 8) : zero;
+                rb[set][i] = (bn + row < d) ? *reinterpret_cast<const bf16x8_t*>(a.Wd + ((size_t)g * d + bn + row) * 64 + c * 8) : zero;
             }
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int set, int buf) {
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            const int id = tid + GM_THREADS * i, row = id >> 3, c = id & 7;
+            As[buf][swz(row, c)] = ra[set][i];
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int id = tid + GM_THREADS * i, row = id >> 3, c = id & 7;
-            As[buf][swz(row, c)] = ra[i];
-            Bs[buf][swz(row, c)] = rb[i];
+            Bs[buf][swz(row, c)] = rb[set][i];
         }
     };
-    f32x16_t acc[2][2];
+    f32x16_t acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int lr = lane & 31, lk = lane >> 5;
-    if (ktiles > 0) { fetch(0); stash(0); }
+    // tile t >= 1 travels in register set (t - 1) & 1
+    if (ktiles > 0) { fetch(0, 0); stash(0, 0); }
+    if (ktiles > 1) fetch(0, 1);
+    if (ktiles > 2) fetch(1, 2);
     __syncthreads();
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < ktiles) fetch(kt + 1);
+    for (int kt = 0; kt < ktiles; kt += 2) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8_t fa[2], fb[2];
+        for (int half = 0; half < 2; ++half) {
+            const int t = kt + half;
+            if (t >= ktiles) break;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = wm * 64 + i * 32 + lr;
-                fa[i] = As[buf][swz(row, kk * 2 + lk)];
+            for (int kk = 0; kk < 4; ++kk) {
+                bf16x8_t fa[MI], fb[2];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) fa[i] = As[half][swz(wm * (BM / 2) + i * 32 + lr, kk * 2 + lk)];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    // first product: column tile j = 0 is gate, j = 1 the matching up channels
+                    const int row = (MODE == 0) ? (j * 64 + wn * 32 + lr) : (wn * 64 + j * 32 + lr);
+                    fb[j] = Bs[half][swz(row, kk * 2 + lk)];
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
             }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                // first product: column tile j = 0 is gate, j = 1 the matching up channels
-                const int row = (MODE == 0) ? (j * 64 + wn * 32 + lr) : (wn * 64 + j * 32 + lr);
-                fb[j] = Bs[buf][swz(row, kk * 2 + lk)];
+            if (t + 1 < ktiles) {
+                stash(half, half ^ 1);                 // tile t+1 sits in set t & 1 = half
+                if (t + 3 < ktiles) fetch(half, t + 3);
             }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            __syncthreads();
         }
-        if (kt + 1 < ktiles) {
-            stash(buf ^ 1);
-        }
-        __syncthreads();
     }
     // epilogue
     if (MODE == 0) {
         const int n = wn * 32 + lr;                  // channel inside the block
         const uint32_t* mrow = a.mask ? a.mask + (size_t)g0 * a.mask_words : nullptr;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int m = bm + wm * 64 + i * 32 + acc_row(e, lane);
+                const int m = bm + wm * (BM / 2) + i * 32 + acc_row(e, lane);
                 if (m < T) {
                     const float gt = acc[i][0][e], up = acc[i][1][e];
                     float hv = gt / (1.0f + __expf(-gt)) * up;
@@ -141,16 +168,28 @@ void ffn_gemm_kernel(GemmArgs a) {
             }
     } else {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int m = bm + wm * 64 + i * 32 + acc_row(e, lane);
+                    const int m = bm + wm * (BM / 2) + i * 32 + acc_row(e, lane);
                     const int n = bn + wn * 64 + j * 32 + lr;
-                    if (m < T && n < d) a.out[(size_t)m * d + n] = f32_to_bf16(acc[i][j][e]);
+                    if (m < T && n < d) {
+                        if (SPLITK) a.partial[((size_t)blockIdx.z * T + m) * d + n] = acc[i][j][e];
+                        else a.out[(size_t)m * d + n] = f32_to_bf16(acc[i][j][e]);
+                    }
                 }
     }
+}
+
+// out = sum over the K splits of the fp32 partial tiles, in a fixed order
+__global__ void ffn_splitk_reduce_kernel(const float* __restrict__ partial, int splits, size_t n, uint16_t* __restrict__ out) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += partial[(size_t)k * n + i];
+    out[i] = f32_to_bf16(s);
 }
 
 // Gathered block list for per-row supports: token bitsets per block and the ordered
@@ -204,11 +243,16 @@ bool ffn_gemm_ok(const FfnArgs& a) {
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// short batches: 64-row tiles and a split of the down product's K range over 8 workgroups
+static bool gemm_short(const FfnArgs& a) { return a.T <= 64; }
+constexpr int GM_SPLITS = 8;
+
 size_t ffn_gemm_scratch_bytes(const FfnArgs& a) {
     const int nb_max = a.shared ? a.k : (a.G < a.T * a.k ? a.G : a.T * a.k);
     const int mask_words = (a.T + 31) / 32;
     return align256((size_t)a.T * nb_max * 64 * 2) + align256((size_t)a.G * 4 + 4) +
-           (a.shared ? 0 : align256((size_t)a.G * mask_words * 4)) + 256;
+           (a.shared ? 0 : align256((size_t)a.G * mask_words * 4)) +
+           (gemm_short(a) ? align256((size_t)GM_SPLITS * a.T * a.d * 4) : 0) + 256;
 }
 
 hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s) {
@@ -221,16 +265,26 @@ hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s) {
     int32_t* nblocks = blocks + a.G;
     p += align256((size_t)a.G * 4 + 4);
     uint32_t* mask = nullptr;
-    if (!a.shared) { mask = reinterpret_cast<uint32_t*>(p); }
+    if (!a.shared) { mask = reinterpret_cast<uint32_t*>(p); p += align256((size_t)a.G * mask_words * 4); }
+    g.partial = reinterpret_cast<float*>(p);
     g.Wg = (const uint16_t*)a.Wg; g.Wu = (const uint16_t*)a.Wu; g.Wd = (const uint16_t*)a.Wd;
     g.x = (const uint16_t*)a.x; g.out = (uint16_t*)a.out;
     g.blocks = blocks; g.nblocks = nblocks; g.mask = mask; g.mask_words = mask_words;
     g.T = a.T; g.d = a.d; g.G = a.G; g.nb_max = nb_max;
     if (a.shared) hipLaunchKernelGGL(ffn_shared_list_kernel, dim3(1), dim3(64), 0, s, a.support, a.k, a.G, blocks, nblocks);
     else hipLaunchKernelGGL(ffn_union_kernel, dim3(1), dim3(1024), 0, s, a.support, a.T, a.k, a.G, mask_words, mask, blocks, nblocks);
-    const int mt = (a.T + GM_BM - 1) / GM_BM;
-    hipLaunchKernelGGL(ffn_gemm_kernel<0>, dim3(nb_max, mt), dim3(GM_THREADS), 0, s, g);
-    hipLaunchKernelGGL(ffn_gemm_kernel<1>, dim3((a.d + GM_BN - 1) / GM_BN, mt), dim3(GM_THREADS), 0, s, g);
+    const int nt = (a.d + GM_BN - 1) / GM_BN;
+    if (gemm_short(a)) {
+        hipLaunchKernelGGL((ffn_gemm_kernel<0, 64, false>), dim3(nb_max, 1), dim3(GM_THREADS), 0, s, g);
+        hipLaunchKernelGGL((ffn_gemm_kernel<1, 64, true>), dim3(nt, 1, GM_SPLITS), dim3(GM_THREADS), 0, s, g);
+        const size_t n = (size_t)a.T * a.d;
+        hipLaunchKernelGGL(ffn_splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           g.partial, GM_SPLITS, n, g.out);
+    } else {
+        const int mt = (a.T + GM_BM - 1) / GM_BM;
+        hipLaunchKernelGGL((ffn_gemm_kernel<0, GM_BM, false>), dim3(nb_max, mt), dim3(GM_THREADS), 0, s, g);
+        hipLaunchKernelGGL((ffn_gemm_kernel<1, GM_BM, false>), dim3(nt, mt), dim3(GM_THREADS), 0, s, g);
+    }
     return hipGetLastError();
 }
 
