@@ -215,6 +215,23 @@ def call_loops(ctx, st, stream):
     return per, union_mean
 
 
+def recorded_traffic(call):
+    """HBM bytes per launch of `call` from the committed rocprofv3 --pmc summary, or None when the
+    kernel sources have changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path)).get("calls", {}).get(call)
+    if rec is None:
+        return None
+    for fname, digest in rec["sources"].items():
+        src = os.path.join(ROOT, "paper_2604_14156_amd", "csrc", fname)
+        if not os.path.exists(src) or hashlib.sha256(open(src, "rb").read()).hexdigest() != digest:
+            return None
+    return rec["hbm_bytes_per_call"]
+
+
 def union_blocks(S, G):
     return int(torch.unique(S).numel())
 
@@ -392,9 +409,13 @@ def main():
     step_share = {k: per[k] * calls_per_step[k] for k in calls_per_step}
     kernels = {
         "attn": {"us_per_call": per["attn"] * 1e3, "active_MB": attn_bytes / 1e6,
-                 "GBs": attn_bytes / (per["attn"] * 1e-3) / 1e9},
+                 "GBs": attn_bytes / (per["attn"] * 1e-3) / 1e9,
+                 "hbm_frac": attn_bytes / (per["attn"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "traffic": recorded_traffic("cs_head_attn")},
         "ffn": {"us_per_call": per["ffn"] * 1e3, "active_MB": ffn_bytes / 1e6,
-                "GBs": ffn_bytes / (per["ffn"] * 1e-3) / 1e9},
+                "GBs": ffn_bytes / (per["ffn"] * 1e-3) / 1e9,
+                "hbm_frac": ffn_bytes / (per["ffn"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "traffic": recorded_traffic("cs_block_ffn")},
         "recover_ffn": {"us_per_call": per["recover_ffn"] * 1e3},
         "recover_heads": {"us_per_call": per["recover_heads"] * 1e3},
         "sketch_ffn": {"us_per_call": per["sketch_ffn"] * 1e3},
@@ -414,7 +435,8 @@ def main():
                    "ffn_blocks_kept": "%d/%d" % (c.k, c.G), "heads_kept": "%d/%d" % (hs.kh, hs.H)},
         "roofline": {"bound": "hbm", "kernel": "cs_head_attn" if dom == "attn" else "cs_block_ffn",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": recorded_traffic("cs_head_attn" if dom == "attn" else "cs_block_ffn")},
         "kernels": kernels,
         "recovery": {"us_per_token": step_share["recover"] * 1e3 / args.batch,
                      "frac_of_serial_step": rec_frac, "margin_pass_rate": margin_pass,
