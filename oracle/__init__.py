@@ -18,6 +18,10 @@ Pin status of each function (what ties it to something other than itself):
                         orthonormal dictionaries, the incoherence guarantee of
                         Prop. 1, exactness in the noiseless case (Thm. 1),
                         sample-complexity shape of Thm. 2, library lstsq.
+* block_iht          -- closed form for orthonormal dictionaries (one step is exact), fixed
+                        point at the planted solution, exact recovery of well-separated
+                        planted supports, brute force on tiny instances, step length
+                        against an explicit line search, library lstsq for the refit.
 * block_ffn          -- dense SwiGLU via an independent formulation, masked
                         dense identity (Sec. 3), additivity over supports.
 * head_attn          -- full softmax attention, L=1, uniform-key closed forms.
@@ -27,12 +31,13 @@ from .philox import philox4x32_10
 from .operator import phi_entries, phi_matrix, GAUSS, RADEMACHER
 from .sketch import sketch
 from .recover import effective_matrix, block_omp
+from .iht import block_iht
 from .ffn import block_ffn
 from .attn import head_attn
 from .joint import top_k_indices, token_proxy, joint_select
 
 __all__ = [
     "philox4x32_10", "phi_entries", "phi_matrix", "GAUSS", "RADEMACHER",
-    "sketch", "effective_matrix", "block_omp", "block_ffn", "head_attn",
+    "sketch", "effective_matrix", "block_omp", "block_iht", "block_ffn", "head_attn",
     "top_k_indices", "token_proxy", "joint_select",
 ]

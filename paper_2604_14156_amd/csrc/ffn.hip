@@ -127,6 +127,26 @@ __device__ __forceinline__ int build_block_list(const int32_t* __restrict__ supp
                                                 uint32_t* mask, uint16_t* ulist, int* wcount) {
     constexpr int NTH = NWAVES * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (shared || T == 1) {
+        // one support for everything: the list is the support itself (entries are distinct by
+        // contract; out-of-range entries are dropped), every row uses every listed block
+        const uint32_t allbits = T >= 32 ? 0xFFFFFFFFu : ((1u << T) - 1u);
+        int base = 0;
+        for (int i0 = 0; i0 < k; i0 += NTH) {
+            const int i = i0 + tid;
+            const int g = i < k ? support[i] : -1;
+            const bool used = g >= 0 && g < G;
+            const unsigned long long bal = __ballot(used);
+            if (lane == 0) wcount[wave] = __popcll(bal);
+            __syncthreads();
+            int off = base, tot = 0;
+            for (int w = 0; w < NWAVES; ++w) { const int c = wcount[w]; if (w < wave) off += c; tot += c; }
+            if (used) { ulist[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)g; mask[g] = allbits; }
+            base += tot;
+            __syncthreads();
+        }
+        return base;
+    }
     for (int g = tid; g < G; g += NTH) mask[g] = 0u;
     __syncthreads();
     const int total = shared ? k : T * k;
