@@ -131,6 +131,23 @@ cs_status cs_recover_support(cs_ctx* ctx, const cs_op* op, const cs_dict* dict, 
                              int32_t* support, float* coef, float* resid_norm, float* margin);
 
 /*
+ * Structured sparse recovery by block iterative hard thresholding: the second cheap
+ * solver the paper names (Sec. 8, "projected proximal methods with a small fixed
+ * number of iterations"), with the projection onto exactly k units (Sec. 7).
+ * `iters` rounds of { g = M^T (y - M alpha); mu = ||g_S||^2 / ||M g_S||^2 on the
+ * current support S (first round: the k units with most gradient energy);
+ * p = alpha + mu g; S = the k units with the largest energy of p (ties -> smaller
+ * index); alpha = p on S }, then one least-squares refit on the final support.
+ * Unit energy: (p_g ||m_g||)^2 with a dictionary, p_g^2 with the identity dictionary.
+ * Arguments and outputs as cs_recover_support; margin is the relative gap between the
+ * k-th and (k+1)-th unit energies at the last projection (1 if k == G).
+ * Supported: one atom per unit (rb == 1), k <= 64, G <= 512 (CS_EINVAL otherwise).
+ */
+cs_status cs_recover_support_iht(cs_ctx* ctx, const cs_op* op, const cs_dict* dict, int k, int iters,
+                                 const float* y, int B,
+                                 int32_t* support, float* coef, float* resid_norm, float* margin);
+
+/*
  * Block-sparse gated (SwiGLU) feed-forward layer restricted to the support
  * (masked execution of Sec. 3; block sparsity of Sec. 7):
  *   out[t] = sum_{g in S_t} Wd_g ( silu(Wg_g x_t) * (Wu_g x_t) ),  silu(u) = u/(1+exp(-u)).

@@ -50,10 +50,14 @@ def block_iht(M, y, G, rb, k, iters, normalised):
     alpha = np.zeros(N)
     support = None
     margin = 1.0
+    min_margin = 1.0
     for _ in range(iters):
         g = M.T @ (y - M @ alpha)
         if support is None:
-            support, _ = _top_units(_unit_energy(g, G, rb, weights), k)
+            e0 = _unit_energy(g, G, rb, weights)
+            support, order0 = _top_units(e0, k)
+            if k < G and e0[order0[k - 1]] > 0.0:
+                min_margin = min(min_margin, (e0[order0[k - 1]] - e0[order0[k]]) / e0[order0[k - 1]])
         cols = np.concatenate([np.arange(u * rb, (u + 1) * rb) for u in support])
         gs = np.zeros(N)
         gs[cols] = g[cols]
@@ -67,6 +71,7 @@ def block_iht(M, y, G, rb, k, iters, normalised):
             margin = (ek - ek1) / ek if ek > 0.0 else 0.0
         else:
             margin = 1.0
+        min_margin = min(min_margin, margin)
         cols = np.concatenate([np.arange(u * rb, (u + 1) * rb) for u in support])
         alpha = np.zeros(N)
         alpha[cols] = p[cols]
@@ -79,4 +84,5 @@ def block_iht(M, y, G, rb, k, iters, normalised):
         "residual": r,
         "resid_norm": float(np.linalg.norm(r)),
         "margin": float(margin),
+        "min_margin": float(min_margin),     # smallest projection gap over all rounds (for test filtering)
     }

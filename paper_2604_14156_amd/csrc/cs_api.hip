@@ -262,6 +262,31 @@ cs_status cs_recover_support(cs_ctx* c, const cs_op* op, const cs_dict* dict, in
     return run_recover(c, op, dict, k, y, B, support, coef, resid_norm, margin, 0, "cs_recover_support");
 }
 
+cs_status cs_recover_support_iht(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k, int iters,
+                                 const float* y, int B,
+                                 int32_t* support, float* coef, float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_recover_args(c, op, dict, k, "cs_recover_support_iht")) != CS_OK) return st;
+    if (iters < 1) return fail(c, CS_EINVAL, "cs_recover_support_iht: iters < 1");
+    if (B < 0) return fail(c, CS_EINVAL, "cs_recover_support_iht: B < 0");
+    if (B == 0) return CS_OK;
+    if (!y || !support) return fail(c, CS_EINVAL, "cs_recover_support_iht: NULL buffer");
+    if (!aligned16(y) || !aligned16(support) || !aligned16(coef) || !aligned16(resid_norm) || !aligned16(margin))
+        return fail(c, CS_EALIGN, "cs_recover_support_iht: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    const Plan* plan = nullptr;
+    if ((st = find_or_build_plan(c, op, dict, &plan)) != CS_OK) return st;
+    if (!recover_iht_supported(*plan, k, c->lds_limit))
+        return fail(c, CS_EINVAL, "cs_recover_support_iht: needs rb == 1, k <= 64 and G <= 512");
+    RecoverArgs a;
+    a.y = y; a.B = B; a.k = k; a.support = support; a.coef = coef; a.resid = resid_norm; a.margin = margin;
+    a.spill = nullptr; a.spill_stride = 0;
+    hipError_t e = launch_recover_iht(*plan, a, iters, c->lds_limit, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_iht");
+    return CS_OK;
+}
+
 cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
                        int d, int G, int b, const void* x, int T,
                        const int32_t* support, int k, int shared, void* out) {

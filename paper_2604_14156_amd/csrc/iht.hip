@@ -1,0 +1,319 @@
+// Structured sparse recovery by block iterative hard thresholding (paper Sec. 8:
+// "projected proximal methods with a small fixed number of iterations", projection
+// onto exactly k units, Sec. 7).  One workgroup per sketch, one atom per unit.
+//
+// Everything runs in the Gram domain (G = M^T M in LDS, c0 = M^T y): the gradient is
+// g = c0 - G alpha, the exact line-search step on the current support is
+// mu = ||g_S||^2 / (g_S^T G g_S), and the projection keeps the k units with the largest
+// weighted energy (w_c p_c)^2.  The k largest are found by rank counting: every atom
+// counts how many atoms beat it (ties -> smaller index); the count is split over the
+// idle threads of the workgroup and summed with integer LDS atomics, so the result
+// does not depend on timing.  After the last iteration the coefficients are refitted
+// by least squares on the final support (Cholesky factor of G_SS built in LDS by one
+// wavefront, then one refinement step against the explicit residual).
+#include "kernels.hpp"
+
+namespace csk {
+
+constexpr int IH_MAXK = 64;
+constexpr int IH_THREADS = 512;
+
+struct IhtLayout {
+    int off_y, off_r, off_alpha, off_g, off_e, off_cnt, off_S, off_t, off_L, off_misc, off_gram, off_stage;
+    int total_floats;
+};
+
+static bool make_iht_layout(const Plan& p, int k, int lds_limit, int nthreads, IhtLayout& L) {
+    const int N = p.N, m = p.op.m;
+    const int Np = (N + 3) & ~3;
+    int o = 0;
+    L.off_y = o; o += (m + 3) & ~3;
+    L.off_r = o; o += (m + 3) & ~3;
+    L.off_alpha = o; o += Np;
+    L.off_g = o; o += Np;
+    L.off_e = o; o += Np;
+    L.off_cnt = o; o += Np;
+    L.off_S = o; o += IH_MAXK;
+    L.off_t = o; o += 4 * IH_MAXK;
+    L.off_L = o; o += IH_MAXK * (IH_MAXK + 1);
+    L.off_misc = o; o += 32;
+    L.off_stage = o; o += nthreads * 4;
+    L.off_gram = -1;
+    const long limit = lds_limit / 4 - 16;
+    if (o > limit) return false;
+    if ((long)o + (long)N * N <= limit) { L.off_gram = o; o += N * N; }
+    L.total_floats = o;
+    return true;
+}
+
+template <bool GRAM_LDS>
+__global__ __launch_bounds__(IH_THREADS)
+void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, NT = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = NT >> 6;
+    const int prob = blockIdx.x;
+    const int N = p.N, m = p.op.m, k = a.k;
+    const bool active = tid < N;
+
+    float* yv = lds + L.off_y;
+    float* rv = lds + L.off_r;
+    float* alpha = lds + L.off_alpha;
+    float* gl_ = lds + L.off_g;
+    float* en = lds + L.off_e;
+    int* cnt = reinterpret_cast<int*>(lds + L.off_cnt);
+    int* S = reinterpret_cast<int*>(lds + L.off_S);
+    float* tv = lds + L.off_t;                  // [4][IH_MAXK] small vectors of the refit
+    float* Lf = lds + L.off_L;                  // Cholesky factor, row stride IH_MAXK + 1
+    float* misc = lds + L.off_misc;
+    float* stage = lds + L.off_stage;
+    float* gram_l = lds + L.off_gram;
+    const float* gram = GRAM_LDS ? gram_l : p.gram;
+
+    // ---- loads: sketch, weight, Gram matrix, M for c0 = M^T y (same scheme as the greedy kernel)
+    const float* y = a.y + (size_t)prob * m;
+    int bad = 0;
+    for (int i = tid; i < m; i += NT) {
+        const float v = y[i];
+        yv[i] = v;
+        if (!isfinite(v)) bad = 1;
+    }
+    float w = 1.f;                                     // atom norm: W holds 1/norm
+    if (active && p.weighted) { const float iw = p.W[tid]; w = iw > 0.f ? 1.0f / iw : 0.f; }
+    if (GRAM_LDS) {
+        const int n4 = (N * N) >> 2;
+        const float4* src = reinterpret_cast<const float4*>(p.gram);
+        float4* dst = reinterpret_cast<float4*>(gram_l);
+        constexpr int U = 8;
+        for (int base = 0; base < n4; base += NT * U) {
+            float4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * NT + tid;
+                r[u] = idx < n4 ? src[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * NT + tid;
+                if (idx < n4) dst[idx] = r[u];
+            }
+        }
+        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gram_l[i] = p.gram[i];
+    }
+    bad = __syncthreads_or(bad);
+    float c0 = 0.f;
+    {
+        const int parts = NT / N > 0 ? NT / N : 1;
+        const int c = tid % N, part = tid / N;
+        const int rows_per = (m + parts - 1) / parts;
+        if (part < parts) {
+            const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
+            float acc = 0.f;
+#pragma unroll 8
+            for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + c] * yv[i];
+            stage[part * N + c] = acc;
+        }
+        __syncthreads();
+        if (active) for (int q = 0; q < parts; ++q) c0 += stage[q * N + tid];
+    }
+    if (active) alpha[tid] = 0.f;
+    // helpers of the rank count: thread (c, part) scans a slice of the candidates
+    const int Npad = (N + 63) & ~63;
+    const int rparts = NT / Npad > 0 ? NT / Npad : 1;
+    const int rc = tid % Npad, rpart = tid / Npad;
+    const int rper = (N + rparts - 1) / rparts;
+    __syncthreads();
+
+    float margin = 1.f;
+    // rank all atoms by the energies in en[]; returns this thread's rank (threads with tid < N)
+    auto rank_atoms = [&]() -> int {
+        if (tid < N) cnt[tid] = 0;
+        __syncthreads();
+        if (rpart < rparts && rc < N) {
+            const float mine = en[rc];
+            const int j0 = rpart * rper, j1 = min(N, j0 + rper);
+            int beat = 0;
+            for (int j = j0; j < j1; ++j) {
+                const float o = en[j];
+                beat += (o > mine) || (o == mine && j < rc);
+            }
+            if (beat) atomicAdd(&cnt[rc], beat);
+        }
+        __syncthreads();
+        return active ? cnt[tid] : 0x7fffffff;
+    };
+
+    float pmine = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        // gradient g = c0 - G alpha (alpha has at most k non-zeros, listed in S after the first pass)
+        float g = c0;
+        if (it > 0 && active)
+            for (int j = 0; j < k; ++j) { const int s = S[j]; g -= alpha[s] * gram[(size_t)s * N + tid]; }
+        if (active) gl_[tid] = g;
+        if (it == 0) {
+            float e = w * g; e = e * e;
+            if (!(e >= 0.f)) e = 0.f;
+            if (active) en[tid] = e;
+            __syncthreads();
+            const int r0 = rank_atoms();
+            if (r0 < k) S[r0] = tid;
+        }
+        __syncthreads();
+        // step length on the current support: one wavefront, lane j owns S[j]
+        if (wave == 0) {
+            float num = 0.f, den = 0.f;
+            if (lane < k) {
+                const int sj = S[lane];
+                const float gj = gl_[sj];
+                float t = 0.f;
+                for (int i = 0; i < k; ++i) { const int si = S[i]; t += gram[(size_t)si * N + sj] * gl_[si]; }
+                num = gj * gj; den = gj * t;
+            }
+            num = wave_sum(num); den = wave_sum(den);
+            if (lane == 0) misc[0] = den > 0.f ? num / den : 0.f;
+        }
+        __syncthreads();
+        const float mu = misc[0];
+        pmine = active ? alpha[tid] + mu * g : 0.f;
+        float e = w * pmine; e = e * e;
+        if (!(e >= 0.f)) e = 0.f;                       // NaN ranks last among equals
+        if (active) en[tid] = e;
+        __syncthreads();
+        const int r = rank_atoms();
+        if (active) alpha[tid] = r < k ? pmine : 0.f;
+        if (r < k) S[r] = tid;
+        if (r == k - 1) misc[1] = e;
+        if (r == k) misc[2] = e;
+        __syncthreads();
+        if (k < p.G) { const float ek = misc[1], ek1 = misc[2]; margin = ek > 0.f ? (ek - ek1) / ek : 0.f; }
+        else margin = 1.f;
+    }
+
+    const bool want_fit = a.coef != nullptr || a.resid != nullptr;
+    float* beta = tv, *xs = tv + IH_MAXK, *gv = tv + 2 * IH_MAXK, *dl = tv + 3 * IH_MAXK;
+    constexpr int LS = IH_MAXK + 1;
+    if (want_fit) {
+        // Cholesky factor of G_SS, one wavefront: lane j builds row j
+        if (wave == 0) {
+            for (int i = 0; i < k; ++i) {
+                const int si = S[i];
+                if (lane >= i && lane < k) {
+                    const int sj = S[lane];
+                    float s = gram[(size_t)si * N + sj];
+                    for (int t = 0; t < i; ++t) s -= Lf[lane * LS + t] * Lf[i * LS + t];
+                    Lf[lane * LS + i] = s;              // un-normalised; row i's own entry is the pivot
+                }
+                __builtin_amdgcn_wave_barrier();
+                const float piv = Lf[i * LS + i];
+                const float inv = piv > 0.f ? __builtin_amdgcn_rsqf(piv) : 0.f;
+                if (piv <= 0.f) bad = 1;
+                __builtin_amdgcn_wave_barrier();
+                if (lane >= i && lane < k) Lf[lane * LS + i] *= inv;      // L[i][i] = sqrt(piv), L[j][i] /= sqrt(piv)
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        bad = __syncthreads_or(bad);
+        // solves with L (lower, rows in LDS): forward L w = rhs, backward L^T x = w; lane i holds component i
+        auto solve = [&](float rhs) -> float {
+            for (int i = 0; i < k; ++i) {                // forward
+                const float lii = Lf[i * LS + i];
+                const float xi = lii > 0.f ? readlane_f32(rhs, i) / lii : 0.f;
+                if (lane == i) rhs = xi;
+                if (lane > i && lane < k) rhs -= Lf[lane * LS + i] * xi;
+            }
+            for (int i = k - 1; i >= 0; --i) {           // backward
+                const float lii = Lf[i * LS + i];
+                const float xi = lii > 0.f ? readlane_f32(rhs, i) / lii : 0.f;
+                if (lane == i) rhs = xi;
+                if (lane < i) rhs -= Lf[i * LS + lane] * xi;
+            }
+            return rhs;
+        };
+        if (active) en[tid] = c0;                        // right-hand side c0_S: published through en[]
+        __syncthreads();
+        if (wave == 0) {
+            const float x = solve(lane < k ? en[S[lane]] : 0.f);
+            if (lane < k) xs[lane] = x;
+        }
+        __syncthreads();
+        for (int i = tid; i < m; i += NT) {
+            float s = yv[i];
+            for (int j = 0; j < k; ++j) s -= xs[j] * p.Mr[(size_t)i * N + S[j]];
+            rv[i] = s;
+        }
+        __syncthreads();
+        for (int j = wave; j < k; j += nwaves) {
+            float s = 0.f;
+            for (int i = lane; i < m; i += 64) s += p.Mr[(size_t)i * N + S[j]] * rv[i];
+            s = wave_sum(s);
+            if (lane == 0) gv[j] = s;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const float d = solve(lane < k ? gv[lane] : 0.f);
+            if (lane < k) { xs[lane] += d; dl[lane] = d; }
+        }
+        __syncthreads();
+        float ss = 0.f;
+        for (int i = tid; i < m; i += NT) {
+            float s = rv[i];
+            for (int j = 0; j < k; ++j) s -= dl[j] * p.Mr[(size_t)i * N + S[j]];
+            ss += s * s;
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) beta[wave] = ss;                  // beta[] is free: per-wave partial sums
+        __syncthreads();
+    }
+    for (int qi = tid; qi < k; qi += NT) {
+        const int gsel = S[qi];
+        int rank = 0;
+        for (int o = 0; o < k; ++o) rank += S[o] < gsel;
+        a.support[(size_t)prob * k + rank] = gsel;
+        if (a.coef) a.coef[(size_t)prob * k + rank] = xs[qi];
+    }
+    if (tid == 0) {
+        if (a.resid) {
+            float tot = 0.f;
+            for (int wv = 0; wv < nwaves; ++wv) tot += beta[wv];
+            a.resid[prob] = bad ? __int_as_float(0x7fc00000) : sqrtf(tot);
+        }
+        if (a.margin) a.margin[prob] = bad ? 0.f : margin;
+    }
+}
+
+bool recover_iht_supported(const Plan& p, int k, int lds_limit) {
+    if (p.rb != 1 || k > IH_MAXK || p.N > IH_THREADS) return false;
+    IhtLayout L;
+    const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : IH_THREADS;
+    return make_iht_layout(p, k, lds_limit, nthreads, L);
+}
+
+hipError_t launch_recover_iht(const Plan& p, const RecoverArgs& a, int iters, int lds_limit, hipStream_t s) {
+    if (a.B <= 0) return hipSuccess;
+    const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : IH_THREADS;
+    IhtLayout L;
+    if (!make_iht_layout(p, a.k, lds_limit, nthreads, L)) return hipErrorInvalidValue;
+    const size_t bytes = (size_t)L.total_floats * 4;
+    if (L.off_gram >= 0) {
+        static size_t allowed = 0;
+        if (bytes > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_iht_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e != hipSuccess) return e;
+            allowed = bytes;
+        }
+        hipLaunchKernelGGL(recover_iht_kernel<true>, dim3(a.B), dim3(nthreads), bytes, s, p, a, iters, L);
+    } else {
+        static size_t allowed = 0;
+        if (bytes > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_iht_kernel<false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e != hipSuccess) return e;
+            allowed = bytes;
+        }
+        hipLaunchKernelGGL(recover_iht_kernel<false>, dim3(a.B), dim3(nthreads), bytes, s, p, a, iters, L);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace csk

@@ -32,6 +32,10 @@ struct RecoverArgs {
 size_t recover_spill_floats(const Plan& p, int k, int lds_limit);
 hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hipStream_t s);
 
+// block iterative hard thresholding (iht.hip): one atom per unit, k <= 64, N <= 512
+bool recover_iht_supported(const Plan& p, int k, int lds_limit);
+hipError_t launch_recover_iht(const Plan& p, const RecoverArgs& a, int iters, int lds_limit, hipStream_t s);
+
 // p[n] = Phi^T y (back-projection), then top-k.
 hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s);
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s);

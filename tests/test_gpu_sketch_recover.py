@@ -240,6 +240,76 @@ def test_recovery_degenerate_and_error_paths(cs):
     assert e.value.status == binding.CS_EINVAL
 
 
+def _check_iht(cs, op, dct, psi_dev, M, Y, G, k, iters, normalised):
+    if psi_dev is not None:
+        cs.cs_plan(op, dct, psi_dev)
+    sup, coef, resid, margin = cs.cs_recover_support_iht(op, dct, k, iters, dev_f32(Y))
+    sup, coef, resid, margin = host(sup), host(coef), host(resid), host(margin)
+    exact = 0
+    for t in range(Y.shape[0]):
+        y = Y[t].astype(np.float64)
+        rec = oracle.block_iht(M, y, G, 1, k, iters, normalised)
+        s = sup[t]
+        assert len(set(s.tolist())) == k and np.all(np.diff(s) > 0) and s.min() >= 0 and s.max() < G
+        ls, *_ = np.linalg.lstsq(M[:, s], y, rcond=None)
+        own = np.linalg.norm(y - M[:, s] @ ls)
+        ynorm = np.linalg.norm(y)
+        assert abs(resid[t] - own) <= RES_TOL * ynorm
+        assert np.linalg.norm(coef[t] - ls) <= 1e-4 * max(np.linalg.norm(ls), 1e-30)
+        if rec["min_margin"] > MARGIN:
+            assert list(s) == list(rec["support"]), (t, rec["min_margin"])
+            assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm
+            assert abs(margin[t] - rec["margin"]) <= 1e-3
+            exact += 1
+    return exact
+
+
+@pytest.mark.parametrize("iters", [1, 4, 12])
+def test_iht_decode_shape(cs, iters):
+    c = wl.CFG2
+    seed = 2200
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 6, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 4, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 4, c.m, c.n, c.G, c.b, 1, psi)
+    Y = oracle.sketch(c.ens, seed, 4, c.m, z).astype(np.float32)
+    exact = _check_iht(cs, op, dct, psi_dev, M, Y, c.G, c.k, iters, True)
+    assert exact >= (4 if iters == 1 else 1)
+
+
+def test_iht_heads_tiny_and_errors(cs):
+    hs = wl.CFG3_HEADS
+    seed = 3300
+    rng = wl.rng_for(seed)
+    u, S = wl.plant_head_usage(rng, hs, 16)
+    op = binding.make_op(hs.ens, seed, 3, hs.m, hs.H)
+    dct = binding.make_dict(None, hs.H, 1, 1)
+    M = oracle.effective_matrix(hs.ens, seed, 3, hs.m, hs.H, hs.H, 1, 1, None)
+    Y = oracle.sketch(hs.ens, seed, 3, hs.m, u).astype(np.float32)
+    assert _check_iht(cs, op, dct, None, M, Y, hs.H, hs.kh, 8, False) >= 4
+    # tiny planted instance: recovered exactly
+    c = wl.CFG1
+    rng = wl.rng_for(1000)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, St = wl.plant_usage(rng, pi, c.k, 1, c.amp, c.bg)
+    op1 = binding.make_op(c.ens, 1000, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    d1 = binding.make_dict(psi_dev, c.G, c.b, 1)
+    y = cs.cs_sketch(op1, dev_f32(z))
+    sup = host(cs.cs_recover_support_iht(op1, d1, c.k, 10, y)[0])
+    assert list(sup[0]) == list(St[0])
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support_iht(op1, d1, c.k, 0, y)
+    assert e.value.status == binding.CS_EINVAL
+    big = binding.make_dict(None, 32, 4, 4)                      # rb > 1 is not supported by this solver
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support_iht(binding.make_op(wl.GAUSS, 1, 0, 48, 128), big, 3, 4, dev_f32(np.zeros((1, 48))))
+    assert e.value.status == binding.CS_EINVAL
+
+
 def test_joint_selection_prompt_shape(cs):
     t = wl.CFG5_TOK
     c = wl.CFG2
