@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--counter-pass", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (calibration), then every call once per "
                          "layer on one stream, no graphs, no timing")
+    ap.add_argument("--solver", choices=["omp", "iht"], default="omp",
+                    help="recovery of the FFN block supports: block-OMP (default) or block iterative hard thresholding")
+    ap.add_argument("--iht-iters", type=int, default=12)
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     return ap.parse_args()
 
@@ -113,6 +116,19 @@ class DecodeState:
         self.out = torch.empty((B, c.d), device=dev, dtype=bf)
 
 
+SOLVER = {"name": "omp", "iters": 12}
+
+
+def recover_ffn(cx, st, l, y, S, margin):
+    """FFN block-support recovery with the selected solver (support + confidence margin only)."""
+    c = st.c
+    if SOLVER["name"] == "iht":
+        return cx.cs_recover_support_iht(st.ffn_op[l], st.ffn_dict[l], c.k, SOLVER["iters"], y, S, None, None, margin,
+                                         want_coef=False, want_resid=False)
+    return cx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, y, S, None, None, margin,
+                                 want_coef=False, want_resid=False)
+
+
 def decode_step(ctx, st, i, ev=None):
     """One decode step over all layers, every call in order on one stream.
     ev: optional dict of event lists for per-call timing."""
@@ -131,8 +147,7 @@ def decode_step(ctx, st, i, ev=None):
                                                         None, None, st.marginh, want_coef=False, want_resid=False))
         timed("attn", lambda: ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.heads[0], st.o))
         timed("sketch", lambda: ctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y))
-        timed("recover", lambda: ctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y, st.S[0],
-                                                        None, None, st.margin, want_coef=False, want_resid=False))
+        timed("recover", lambda: recover_ffn(ctx, st, l, st.y, st.S[0], st.margin))
         timed("ffn", lambda: ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S[0], False, st.out))
 
 
@@ -163,8 +178,7 @@ def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec, chunk=None, ahead=Non
                 rctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh_l[l], st.heads_l[l],
                                         None, None, st.marginh_l[l], want_coef=False, want_resid=False)
                 rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.y_l[l])
-                rctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y_l[l], st.S_l[l],
-                                        None, None, st.margin_l[l], want_coef=False, want_resid=False)
+                recover_ffn(rctx, st, l, st.y_l[l], st.S_l[l], st.margin_l[l])
             ready = torch.cuda.Event()
             ready.record(s_rec)
         with torch.cuda.stream(s_exec):
@@ -186,8 +200,7 @@ def call_loops(ctx, st, stream):
     S_all, H_all = [], []
     for l in range(nl):
         ctx.cs_sketch(st.ffn_op[l], st.z[0][l], st.y)
-        S_all.append(ctx.cs_recover_support(st.ffn_op[l], st.ffn_dict[l], c.k, st.y, None, None, None, st.margin,
-                                            want_coef=False, want_resid=False)[0])
+        S_all.append(recover_ffn(ctx, st, l, st.y, None, st.margin)[0])
         ctx.cs_sketch(st.head_op[l], st.u[0][l], st.yh)
         H_all.append(ctx.cs_recover_support(st.head_op[l], st.head_dict, hs.kh, st.yh, None, None, None, st.marginh,
                                             want_coef=False, want_resid=False)[0])
@@ -197,8 +210,7 @@ def call_loops(ctx, st, stream):
         "attn": lambda i: ctx.cs_head_attn(st.q[0][i % nl], st.K[i % nl], st.V[i % nl], H_all[i % nl], st.o),
         "ffn": lambda i: ctx.cs_block_ffn(st.Wg[i % nl], st.Wu[i % nl], st.Wd[i % nl], st.x[0][i % nl], S_all[i % nl],
                                           False, st.out),
-        "recover_ffn": lambda i: ctx.cs_recover_support(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, st.S[0], None,
-                                                        None, st.margin, want_coef=False, want_resid=False),
+        "recover_ffn": lambda i: recover_ffn(ctx, st, i % nl, st.y, st.S[0], st.margin),
         "recover_heads": lambda i: ctx.cs_recover_support(st.head_op[i % nl], st.head_dict, hs.kh, st.yh, st.heads[0],
                                                           None, None, st.marginh, want_coef=False, want_resid=False),
         "sketch_ffn": lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y),
@@ -236,7 +248,7 @@ def union_blocks(S, G):
     return int(torch.unique(S).numel())
 
 
-def cpu_baseline(wl, layers_sample=2, B=16, seed=3000):
+def cpu_baseline(wl, layers_sample=16, B=16, seed=3000):
     """The CPU oracle on a bounded sample of the same workload: `layers_sample` layers of one step."""
     import oracle
     try:
@@ -335,6 +347,7 @@ def main():
     from paper_2604_14156_amd import binding, workloads as wl
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU and the HIP library; there is no CPU fallback")
+    SOLVER["name"], SOLVER["iters"] = args.solver, args.iht_iters
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
     rstream = torch.cuda.Stream()
@@ -395,8 +408,7 @@ def main():
         attn_bytes = args.batch * hs.kh * 2 * hs.L * hs.dh * 2
         # union of the supports of one call stands for all (same distribution)
         ctx.cs_sketch(st.ffn_op[0], st.z[0][0], st.y)
-        ctx.cs_recover_support(st.ffn_op[0], st.ffn_dict[0], c.k, st.y, st.S[0], None, None, st.margin,
-                               want_coef=False, want_resid=False)
+        recover_ffn(ctx, st, 0, st.y, st.S[0], st.margin)
         torch.cuda.synchronize()
         margin_pass = float((st.margin > 1e-3).float().mean())
         ffn_bytes = union_mean * 3 * c.b * c.d * 2
@@ -432,7 +444,8 @@ def main():
         "config": {"workload": "config 3: full 7B-shaped decode step, %d layers, batch %d, KV length %d, "
                                "supports re-recovered every token" % (args.layers, args.batch, hs.L),
                    "global_batch": args.batch, "layers": args.layers, "kv_len": hs.L,
-                   "ffn_blocks_kept": "%d/%d" % (c.k, c.G), "heads_kept": "%d/%d" % (hs.kh, hs.H)},
+                   "ffn_blocks_kept": "%d/%d" % (c.k, c.G), "heads_kept": "%d/%d" % (hs.kh, hs.H),
+                   "solver": args.solver if args.solver == "omp" else "iht(%d iterations)" % args.iht_iters},
         "roofline": {"bound": "hbm", "kernel": "cs_head_attn" if dom == "attn" else "cs_block_ffn",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

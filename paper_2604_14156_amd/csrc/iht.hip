@@ -25,7 +25,7 @@ struct IhtLayout {
 
 static bool make_iht_layout(const Plan& p, int k, int lds_limit, int nthreads, IhtLayout& L) {
     const int N = p.N, m = p.op.m;
-    const int Np = (N + 3) & ~3;
+    const int Np = (N + 7) & ~7;
     int o = 0;
     L.off_y = o; o += (m + 3) & ~3;
     L.off_r = o; o += (m + 3) & ~3;
@@ -121,7 +121,9 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
     const int Npad = (N + 63) & ~63;
     const int rparts = NT / Npad > 0 ? NT / Npad : 1;
     const int rc = tid % Npad, rpart = tid / Npad;
-    const int rper = (N + rparts - 1) / rparts;
+    const int Np8 = (N + 7) & ~7;
+    const int rper = (((N + rparts - 1) / rparts) + 7) & ~7;
+    for (int i = N + tid; i < Np8; i += NT) en[i] = -1.f;   // padding never beats anything (energies are >= 0)
     __syncthreads();
 
     float margin = 1.f;
@@ -131,11 +133,14 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
         __syncthreads();
         if (rpart < rparts && rc < N) {
             const float mine = en[rc];
-            const int j0 = rpart * rper, j1 = min(N, j0 + rper);
+            const int j0 = rpart * rper, j1 = min(Np8, j0 + rper);     // rper is a multiple of 8
             int beat = 0;
-            for (int j = j0; j < j1; ++j) {
-                const float o = en[j];
-                beat += (o > mine) || (o == mine && j < rc);
+            for (int j = j0; j < j1; j += 8) {
+                const float4 a0 = *reinterpret_cast<const float4*>(en + j);
+                const float4 a1 = *reinterpret_cast<const float4*>(en + j + 4);
+                const float o[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                for (int q = 0; q < 8; ++q) beat += (int)(o[q] > mine) | ((int)(o[q] == mine) & (int)(j + q < rc));   // no branches
             }
             if (beat) atomicAdd(&cnt[rc], beat);
         }
@@ -145,10 +150,28 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
 
     float pmine = 0.f;
     for (int it = 0; it < iters; ++it) {
-        // gradient g = c0 - G alpha (alpha has at most k non-zeros, listed in S after the first pass)
+        // gradient g = c0 - G alpha (alpha has at most k non-zeros, listed in S after the first pass).
+        // Each wave keeps the list and the listed coefficients in the registers of its first k lanes and
+        // hands them out by scalar lane reads, so the k Gram reads below are independent of each other.
         float g = c0;
-        if (it > 0 && active)
-            for (int j = 0; j < k; ++j) { const int s = S[j]; g -= alpha[s] * gram[(size_t)s * N + tid]; }
+        if (it > 0) {
+            const int sreg = lane < k ? S[lane] : 0;
+            const float areg = lane < k ? alpha[sreg] : 0.f;
+            float acc = 0.f;
+            const int ta = active ? tid : 0;
+            for (int j = 0; j < k; j += 4) {
+                float gv4[4], av4[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {       // lanes >= k hold index 0 and coefficient 0; j + q <= 63
+                    const int sj = __builtin_amdgcn_readlane(sreg, j + q);
+                    av4[q] = readlane_f32(areg, j + q);
+                    gv4[q] = gram[(size_t)sj * N + ta];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc += av4[q] * gv4[q];
+            }
+            g -= acc;
+        }
         if (active) gl_[tid] = g;
         if (it == 0) {
             float e = w * g; e = e * e;
@@ -161,15 +184,21 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
         __syncthreads();
         // step length on the current support: one wavefront, lane j owns S[j]
         if (wave == 0) {
-            float num = 0.f, den = 0.f;
-            if (lane < k) {
-                const int sj = S[lane];
-                const float gj = gl_[sj];
-                float t = 0.f;
-                for (int i = 0; i < k; ++i) { const int si = S[i]; t += gram[(size_t)si * N + sj] * gl_[si]; }
-                num = gj * gj; den = gj * t;
+            const int sreg = lane < k ? S[lane] : 0;
+            const float greg = lane < k ? gl_[sreg] : 0.f;
+            float t = 0.f;
+            for (int i = 0; i < k; i += 4) {
+                float gv4[4], gi4[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int si = __builtin_amdgcn_readlane(sreg, i + q);
+                    gi4[q] = readlane_f32(greg, i + q);
+                    gv4[q] = gram[(size_t)si * N + sreg];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) t += gv4[q] * gi4[q];
             }
-            num = wave_sum(num); den = wave_sum(den);
+            const float num = wave_sum(greg * greg), den = wave_sum(greg * t);
             if (lane == 0) misc[0] = den > 0.f ? num / den : 0.f;
         }
         __syncthreads();
