@@ -1,0 +1,100 @@
+"""A captured two-stream decode step replayed several times must reproduce the eager
+results every time (device-side work counters are restored by the kernels themselves,
+no memset nodes are recorded)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_14156_amd import binding, workloads as wl
+from gpu_util import host
+
+pytestmark = pytest.mark.gpu
+
+
+def test_pipelined_step_graph_replays_match_eager():
+    dev = "cuda:0"
+    c = wl.scaled(wl.CFG2, d=512, G=24, k=6, m=64)
+    hs = wl.scaled(wl.CFG3_HEADS, L=300)
+    B, layers = 5, 3
+    s_exec, s_rec = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx, rctx = binding.Context(0, s_exec), binding.Context(0, s_rec)
+    gen = torch.Generator(device=dev).manual_seed(9)
+    bf = torch.bfloat16
+    rn = lambda *shape: torch.randn(shape, generator=gen, device=dev)
+    with torch.cuda.stream(s_exec):
+        Wg = [rn(c.G, c.b, c.d).mul(0.05).to(bf) for _ in range(layers)]
+        Wu = [rn(c.G, c.b, c.d).mul(0.05).to(bf) for _ in range(layers)]
+        Wd = [rn(c.G, c.d, c.b).mul(0.05).to(bf) for _ in range(layers)]
+        K = [rn(B, hs.H, hs.L, hs.dh).to(bf) for _ in range(layers)]
+        V = [rn(B, hs.H, hs.L, hs.dh).to(bf) for _ in range(layers)]
+        psi = []
+        for _ in range(layers):
+            p = rn(c.G, c.b)
+            psi.append((p / p.norm(dim=1, keepdim=True)).reshape(c.G, c.b, 1).contiguous())
+        z = [rn(B, c.n) for _ in range(layers)]
+        u = [rn(B, hs.H) for _ in range(layers)]
+        x = [rn(B, c.d).to(bf) for _ in range(layers)]
+        q = [rn(B, hs.H, hs.dh).to(bf) for _ in range(layers)]
+        fop = [binding.make_op(c.ens, 5, 2 * l, c.m, c.n) for l in range(layers)]
+        hop = [binding.make_op(hs.ens, 5, 2 * l + 1, hs.m, hs.H) for l in range(layers)]
+        fdict = [binding.make_dict(psi[l], c.G, c.b, 1) for l in range(layers)]
+        hdict = binding.make_dict(None, hs.H, 1, 1)
+        for cx in (ctx, rctx):
+            for l in range(layers):
+                cx.cs_plan(fop[l], fdict[l], psi[l])
+                cx.cs_plan(hop[l], hdict)
+        y = [torch.empty((B, c.m), device=dev) for _ in range(layers)]
+        yh = [torch.empty((B, hs.m), device=dev) for _ in range(layers)]
+        S = [torch.empty((B, c.k), dtype=torch.int32, device=dev) for _ in range(layers)]
+        Hh = [torch.empty((B, hs.kh), dtype=torch.int32, device=dev) for _ in range(layers)]
+        mg = [torch.empty((B,), device=dev) for _ in range(2 * layers)]
+        o = [torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf) for _ in range(layers)]
+        out = [torch.empty((B, c.d), device=dev, dtype=bf) for _ in range(layers)]
+        torch.cuda.synchronize()
+
+        def step():
+            s_rec.wait_stream(s_exec)
+            for l in range(layers):
+                with torch.cuda.stream(s_rec):
+                    rctx.cs_sketch(hop[l], u[l], yh[l])
+                    rctx.cs_recover_support(hop[l], hdict, hs.kh, yh[l], Hh[l], None, None, mg[2 * l],
+                                            want_coef=False, want_resid=False)
+                    rctx.cs_sketch(fop[l], z[l], y[l])
+                    rctx.cs_recover_support(fop[l], fdict[l], c.k, y[l], S[l], None, None, mg[2 * l + 1],
+                                            want_coef=False, want_resid=False)
+                    ready = torch.cuda.Event()
+                    ready.record(s_rec)
+                with torch.cuda.stream(s_exec):
+                    s_exec.wait_event(ready)
+                    ctx.cs_head_attn(q[l], K[l], V[l], Hh[l], o[l])
+                    ctx.cs_block_ffn(Wg[l], Wu[l], Wd[l], x[l], S[l], False, out[l])
+            s_exec.wait_stream(s_rec)
+
+        def snapshot():
+            torch.cuda.synchronize()
+            return [t.clone() for t in S + Hh + o + out]
+
+        def scribble():
+            for t in S + Hh:
+                t.fill_(-7)
+            for t in o + out:
+                t.fill_(3.0)
+
+        step()
+        ref = snapshot()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s_exec, capture_error_mode="thread_local"):
+            step()
+        for rep in range(4):
+            scribble()
+            torch.cuda.synchronize()
+            g.replay()
+            got = snapshot()
+            for a, b in zip(ref, got):
+                assert torch.equal(a, b), rep
+            # the library's own eager work in between replays
+            ctx.cs_block_ffn(Wg[0], Wu[0], Wd[0], x[0], S[0], False, out[0])
+            torch.cuda.synchronize()
+            assert torch.equal(out[0], ref[2 * layers + layers + 0])
+    ctx.close()
+    rctx.close()
