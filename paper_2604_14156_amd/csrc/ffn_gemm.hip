@@ -12,6 +12,7 @@
 // during the multiplies.  LDS rows are 128 bytes; the eight 16-byte chunks of a row
 // are stored XOR-swizzled by the row index so that fragment reads are conflict free.
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace csk {
 
@@ -183,6 +184,216 @@ void ffn_gemm_kernel(GemmArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Wide tiles for long batches (T >= 512).  With 128 x 128 tiles the multiplies wait for the
+// compute unit's load path (64 bytes per cycle) and for LDS (every operand byte is written once
+// and read back twice), so here one workgroup owns a 256 x 256 tile: four waves of 128 x 128
+// (256 accumulator registers per lane, one wave per SIMD), K step 32, four LDS stages of 32 KB.
+// The operands go from global memory straight into LDS (global_load_lds_dwordx4: lane p of a
+// wave fills bytes 16p .. 16p+15 of a 1 KB run, i.e. 16 rows of 64 bytes), which needs no staging
+// registers; the XOR swizzle that keeps the fragment reads conflict free is applied on the global
+// side, by choosing which 16-byte chunk of its row a lane fetches.  Tiles travel in pairs (a
+// 64-column step): while one pair is multiplied the next is in flight, and one barrier per pair
+// sits before the pair's last k-step, whose multiplies hide the issue of the following fetch.
+// Fragment reads for the next k-step are spread between the multiplies of the current one.
+// ---------------------------------------------------------------------------
+constexpr int GW_BM = 256, GW_BN = 256, GW_BK = 32;
+constexpr int GW_STAGE = (GW_BM + GW_BN) * 4;          // 16-byte entries per stage
+constexpr int GW_MAX_BLOCKS = 4096;                    // longest gathered list the down product keeps in LDS
+
+__device__ __forceinline__ int swz4(int row, int chunk) { return (row << 2) + (chunk ^ ((row >> 1) & 3)); }
+
+// One wave copies 1 KB from global memory into LDS without passing through registers: lane p
+// supplies the address of its 16 bytes, which land at lds_wave_base + 16 p.  The instruction takes
+// the LDS base from M0, which nothing else in these kernels uses.  It is counted by vmcnt like any
+// other load; the compiler does not see it, so the kernel waits for it explicitly.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, const void* lds_wave_base) {
+    const unsigned l = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)((const __attribute__((address_space(3))) void*)lds_wave_base));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(l) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+template <int MODE>
+__global__ __launch_bounds__(GM_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ffn_gemm_wide_kernel(GemmArgs a) {
+    __shared__ bf16x8_t S[4][GW_STAGE];
+    __shared__ int32_t blk_lds[MODE == 1 ? GW_MAX_BLOCKS : 1];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    // the block list is read through the scalar cache (constant address space), never by a vector
+    // load, whose in-order completion would drain the tiles in flight
+    const __attribute__((address_space(4))) int32_t* blocks = (const __attribute__((address_space(4))) int32_t*)a.blocks;
+    const int nb = *a.nblocks;
+    const int bm = blockIdx.y * GW_BM;
+    const int d = a.d, T = a.T;
+    const int ldh = a.nb_max * 64;
+    int ktiles, bn = 0, g2[2] = {0, 0};
+    if (MODE == 0) {
+        if ((int)blockIdx.x * 2 >= nb) return;
+        g2[0] = blocks[blockIdx.x * 2];
+        g2[1] = blocks[min((int)blockIdx.x * 2 + 1, nb - 1)];
+        ktiles = d / GW_BK;
+    } else {
+        bn = blockIdx.x * GW_BN;
+        ktiles = nb * 2;                               // always even, like d / 32
+        for (int i = tid; i < nb; i += GM_THREADS) blk_lds[i] = a.blocks[i];   // visible after the first barrier
+    }
+    // Per lane and load instruction: the row it fetches and the chunk of that row.  Instruction u of
+    // wave w covers tile rows 16 (4u + w) .. +15; lane p takes row p / 4, LDS slot p % 4.
+    const uint16_t* pa[4];
+    const uint16_t* pb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int r = (u * 4 + wave) * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((r >> 1) & 3);
+        const int m = min(bm + r, T - 1);              // rows past T repeat the last row; never stored
+        pa[u] = (MODE == 0 ? a.x + (size_t)m * d : a.hid + (size_t)m * ldh) + chunk * 8;
+        if (MODE == 0) {
+            const int g = g2[r >> 7], c = r & 127;
+            pb[u] = (c < 64 ? a.Wg + ((size_t)g * 64 + c) * d : a.Wu + ((size_t)g * 64 + c - 64) * d) + chunk * 8;
+        } else {
+            pb[u] = a.Wd + (size_t)min(bn + r, d - 1) * 64 + chunk * 8;
+        }
+    }
+    // Tiles are fetched in pairs (one 64-column step: both 64-byte halves of every 128-byte line
+    // are requested back to back, so each line crosses the L2 -> L1 path once).  Pair q goes to
+    // stages 2 (q & 1) and 2 (q & 1) + 1; a pair past the last one repeats the last one and is never
+    // multiplied.  Part u of 4 is one run of A rows and one run of B rows, for both tiles.
+    // Inside the loop the block id of the down product comes from a copy of the list in LDS: LDS
+    // reads complete in order, so waiting for it does not drain the fragment reads in flight the
+    // way a scalar load's wait would (and a vector load's wait would drain the tiles in flight).
+    const int plast = ktiles / 2 - 1;
+    const bf16x8_t* St_issue = nullptr;
+    size_t aoff_issue = 0, boff_issue = 0;
+    int q_issue = 0;
+    uint32_t g_issue = 0;
+    auto issue_prefetch = [&](int q, bool from_lds) {
+        q_issue = q;
+        if (MODE == 1) g_issue = from_lds ? (uint32_t)blk_lds[min(q, plast)] : (uint32_t)blocks[min(q, plast)];
+    };
+    auto issue_begin = [&]() {
+        St_issue = S[2 * (q_issue & 1)];
+        aoff_issue = (size_t)min(q_issue, plast) * (2 * GW_BK);
+        if (MODE == 0) boff_issue = aoff_issue;
+        else boff_issue = (size_t)g_issue * d * 64;
+    };
+    auto issue_part = [&](int u) {
+        load_to_lds_16(pa[u] + aoff_issue, St_issue + (u * 4 + wave) * 64);
+        load_to_lds_16(pa[u] + aoff_issue + GW_BK, St_issue + GW_STAGE + (u * 4 + wave) * 64);
+        load_to_lds_16(pb[u] + boff_issue, St_issue + GW_BM * 4 + (u * 4 + wave) * 64);
+        load_to_lds_16(pb[u] + boff_issue + GW_BK, St_issue + GW_STAGE + GW_BM * 4 + (u * 4 + wave) * 64);
+    };
+    auto issue = [&](int q) {
+        issue_prefetch(q, false);
+        issue_begin();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) issue_part(u);
+    };
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    const int lr = lane & 31, lk = lane >> 5;
+    bf16x8_t fa[2][4], fb[2][4];
+    // Fragment reads of k-step kk of tile t, in four parts of two: the B fragments first (every
+    // row of multiplies needs all four of them), then the A fragments in the order of use.
+    auto frag_pair = [&](int set, int t, int kk, int i) {
+        const bf16x8_t* St = S[t & 3];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int f = (i & 1) * 2 + h;
+            // first product: the wave's 128 columns are one block, gate channels then up channels
+            if (i < 2) fb[set][f] = St[GW_BM * 4 + swz4(wn * 128 + f * 32 + lr, kk * 2 + lk)];
+            else fa[set][f] = St[swz4(wm * 128 + f * 32 + lr, kk * 2 + lk)];
+        }
+    };
+    auto frags = [&](int set, int t, int kk) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) frag_pair(set, t, kk, i);
+    };
+    auto multiply_row = [&](int set, int i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+    // The order below is pinned with scheduling barriers: left alone, the compiler sinks every
+    // fragment read next to its first use, which exposes the LDS latency four times per tile.
+    // One workgroup barrier per pair of tiles, placed between the two k-steps of the pair's second
+    // tile; s_waitcnt immediates: vmcnt(16) / vmcnt(0), each with lgkmcnt(0) (a pair is 16 loads).
+    if (ktiles > 0) {
+        issue(0); issue(1);
+        __builtin_amdgcn_s_waitcnt(0x4070);            // pair 0 has landed (pair 1 still in flight)
+        __syncthreads();
+        frags(0, 0, 0);
+        // one k-step: the 16 multiplies of fragment set `set`, with the reads of the next k-step's
+        // fragments (two per four multiplies) spread between them
+        auto kstep = [&](int set, int tn, int kkn) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                frag_pair(set ^ 1, tn, kkn, i);
+                multiply_row(set, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        for (int q = 0; q <= plast; ++q) {
+            const int t = 2 * q;
+            issue_prefetch(q + 2, true);
+            kstep(0, t, 1);
+            kstep(1, t + 1, 0);
+            kstep(0, t + 1, 1);
+            __builtin_amdgcn_s_waitcnt(0x0070);        // pair q+1 has landed, own reads of pair q are done
+            __syncthreads();                            // ... for every wave: the stages of pair q are free
+            issue_begin();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                frag_pair(0, t + 2, 0, i);
+                multiply_row(1, i);
+                issue_part(i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);            // surplus fetches land before the LDS is released
+    }
+    if (MODE == 0) {
+        const int slot = blockIdx.x * 2 + wn;
+        if (slot >= nb) return;
+        const uint32_t* mrow = a.mask ? a.mask + (size_t)g2[wn] * a.mask_words : nullptr;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = bm + wm * 128 + i * 32 + acc_row(e, lane);
+                    if (m < T) {
+                        const float gt = acc[i][j][e], up = acc[i][j + 2][e];
+                        float hv = gt / (1.0f + __expf(-gt)) * up;
+                        if (mrow && !((mrow[m >> 5] >> (m & 31)) & 1u)) hv = 0.f;
+                        a.hid[(size_t)m * ldh + slot * 64 + j * 32 + lr] = f32_to_bf16(hv);
+                    }
+                }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = bm + wm * 128 + i * 32 + acc_row(e, lane);
+                    const int n = bn + wn * 128 + j * 32 + lr;
+                    if (m < T && n < d) a.out[(size_t)m * d + n] = f32_to_bf16(acc[i][j][e]);
+                }
+    }
+}
+
 // out = sum over the K splits of the fp32 partial tiles, in a fixed order
 __global__ void ffn_splitk_reduce_kernel(const float* __restrict__ partial, int splits, size_t n, uint16_t* __restrict__ out) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -280,6 +491,10 @@ hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s) {
         const size_t n = (size_t)a.T * a.d;
         hipLaunchKernelGGL(ffn_splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                            g.partial, GM_SPLITS, n, g.out);
+    } else if (a.T >= 512 && (a.d % GW_BK) == 0 && nb_max <= GW_MAX_BLOCKS) {
+        const int mt = (a.T + GW_BM - 1) / GW_BM;
+        hipLaunchKernelGGL((ffn_gemm_wide_kernel<0>), dim3((nb_max + 1) / 2, mt), dim3(GM_THREADS), 0, s, g);
+        hipLaunchKernelGGL((ffn_gemm_wide_kernel<1>), dim3((a.d + GW_BN - 1) / GW_BN, mt), dim3(GM_THREADS), 0, s, g);
     } else {
         const int mt = (a.T + GM_BM - 1) / GM_BM;
         hipLaunchKernelGGL((ffn_gemm_kernel<0, GM_BM, false>), dim3(nb_max, mt), dim3(GM_THREADS), 0, s, g);

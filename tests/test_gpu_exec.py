@@ -43,7 +43,11 @@ def test_ffn_f32_ragged_shapes(cs, T):
 
 
 @pytest.mark.parametrize("T,shared,G,k,d", [(300, True, 20, 5, 1024), (130, False, 12, 4, 512), (64, False, 9, 9, 256),
-                                            (257, True, 6, 1, 128)])
+                                            (257, True, 6, 1, 128),
+                                            # long batches (wide tiles): ragged last row tile, odd block count,
+                                            # output width that is no multiple of the tile, per-row supports
+                                            (600, True, 20, 5, 1024), (515, False, 12, 4, 320), (1024, True, 8, 8, 256),
+                                            (513, True, 5, 1, 64)])
 def test_ffn_bf16_many_rows_matrix_core_path(cs, T, shared, G, k, d):
     _ffn_case(cs, 1500 + T, G, 64, d, k, T, "bf16", shared, 0.05)
 
