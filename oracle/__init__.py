@@ -22,6 +22,12 @@ Pin status of each function (what ties it to something other than itself):
                         point at the planted solution, exact recovery of well-separated
                         planted supports, brute force on tiny instances, step length
                         against an explicit line search, library lstsq for the refit.
+* incremental_block_omp -- swaps = k is block_omp itself, swaps = 0 is library lstsq on the
+                        previous support, brute force over every support within the drift
+                        budget (orthonormal dictionaries: exact), closed-form ridge for the
+                        regularised refit, the gamma -> infinity limit, planted drift, and
+                        the measurement saving of the incremental proposition (Sec. 10).
+* support_drift      -- hand-computed examples of D_t (Sec. 15).
 * block_ffn          -- dense SwiGLU via an independent formulation, masked
                         dense identity (Sec. 3), additivity over supports.
 * head_attn          -- full softmax attention, L=1, uniform-key closed forms.
@@ -32,12 +38,13 @@ from .operator import phi_entries, phi_matrix, GAUSS, RADEMACHER
 from .sketch import sketch
 from .recover import effective_matrix, block_omp
 from .iht import block_iht
+from .incremental import incremental_block_omp, support_drift
 from .ffn import block_ffn
 from .attn import head_attn
 from .joint import top_k_indices, token_proxy, joint_select
 
 __all__ = [
     "philox4x32_10", "phi_entries", "phi_matrix", "GAUSS", "RADEMACHER",
-    "sketch", "effective_matrix", "block_omp", "block_iht", "block_ffn", "head_attn",
+    "sketch", "effective_matrix", "block_omp", "block_iht", "incremental_block_omp", "support_drift", "block_ffn", "head_attn",
     "top_k_indices", "token_proxy", "joint_select",
 ]
