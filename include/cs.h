@@ -148,6 +148,37 @@ cs_status cs_recover_support_iht(cs_ctx* ctx, const cs_op* op, const cs_dict* di
                                  int32_t* support, float* coef, float* resid_norm, float* margin);
 
 /*
+ * Warm-started (incremental) recovery: the previous token's support is corrected instead
+ * of being recovered from nothing (Sec. 5: temporal regulariser
+ * gamma ||alpha_t - alpha_{t-1}||^2 and incremental support updates; Sec. 10, proposition
+ * on incremental token-adaptive recovery: a drift of Delta units costs about
+ * Delta log(eG/Delta) measurements).  Per sketch:
+ *   1. alpha1 = argmin ||y - M_S a||^2 + gamma ||a - alpha_prev||^2 on S = prev_support
+ *      (plain least squares when prev_coef is NULL or gamma == 0);
+ *   2. the `swaps` units of S with the least energy (alpha1_g ||m_g||)^2 (identity
+ *      dictionary: alpha1_g^2) leave, among equal energies the larger index first;
+ *   3. `swaps` greedy rounds of cs_recover_support's rule, started from the kept units,
+ *      bring the support back to k units;
+ *   4. least-squares refit on the final support.
+ * swaps == k is cs_recover_support itself; swaps == 0 only refits on prev_support.
+ *   prev_support: device int32 [B][k], k distinct units per row in any order
+ *   prev_coef:    device float [B][k] in the order of prev_support, or NULL
+ *   gamma:        >= 0
+ *   swaps:        0 .. k, the drift budget (up to 2*swaps units of symmetric difference)
+ *   support, coef, resid_norm: as cs_recover_support; support/coef may alias
+ *                 prev_support/prev_coef (a row is read completely before it is written)
+ *   margin:       min over the greedy rounds of (best - runner_up)/best; 1 if swaps == 0
+ * A row whose prev_support is out of range or repeats a unit, or whose sketch is not
+ * finite, does not abort the call: it reports support = -1 in every slot, coef = 0,
+ * resid_norm = NaN and margin = 0.
+ * Supported: one atom per unit (rb == 1), k <= 64, G <= 512 (CS_EINVAL otherwise).
+ */
+cs_status cs_recover_support_inc(cs_ctx* ctx, const cs_op* op, const cs_dict* dict, int k,
+                                 const float* y, int B,
+                                 const int32_t* prev_support, const float* prev_coef, float gamma, int swaps,
+                                 int32_t* support, float* coef, float* resid_norm, float* margin);
+
+/*
  * Block-sparse gated (SwiGLU) feed-forward layer restricted to the support
  * (masked execution of Sec. 3; block sparsity of Sec. 7):
  *   out[t] = sum_{g in S_t} Wd_g ( silu(Wg_g x_t) * (Wu_g x_t) ),  silu(u) = u/(1+exp(-u)).

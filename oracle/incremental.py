@@ -45,7 +45,8 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
     """Returns a dict: support (ascending), coef ([k*rb], ascending-support order, plain refit),
     residual, resid_norm, margin (min over the forward rounds of (best - runner_up)/best; 1 when
     swaps == 0), kept / dropped / added (unit lists), coef_step1 (the regularised refit on
-    prev_support, in prev_support order).
+    prev_support, in prev_support order), drop_margin (relative energy gap between the last unit
+    dropped and the weakest unit kept; 1 when nothing or everything is dropped).
 
     prev_support: k distinct units in any order; prev_coef: [k*rb] in the order of prev_support.
     """
@@ -82,6 +83,11 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
     # 2. backward step
     energy = ((alpha1 * weights[cols]) ** 2).reshape(k, rb).sum(axis=1)
     order = sorted(range(k), key=lambda i: (energy[i], -prev[i]))      # first = dropped first
+    e_sorted = [energy[i] for i in order]
+    if 0 < swaps < k and e_sorted[swaps] > 0.0:
+        drop_margin = float((e_sorted[swaps] - e_sorted[swaps - 1]) / e_sorted[swaps])
+    else:
+        drop_margin = 1.0 if swaps in (0, k) else 0.0
     dropped = [prev[i] for i in order[:swaps]]
     chosen = [prev[i] for i in order[swaps:]]
     kept = list(chosen)
@@ -127,4 +133,5 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
         "dropped": dropped,
         "added": added,
         "coef_step1": alpha1,
+        "drop_margin": drop_margin,
     }

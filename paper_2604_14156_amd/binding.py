@@ -17,7 +17,7 @@ CS_GAUSS, CS_RADEMACHER = 0, 1
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
-           "cs_recover_support", "cs_recover_support_iht", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_gather_rows")
+           "cs_recover_support", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_gather_rows")
 
 
 class CsOp(ctypes.Structure):
@@ -50,6 +50,8 @@ def load_library(path=LIB_PATH):
     lib.cs_sketch.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, vp]
     lib.cs_recover_support.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
     lib.cs_recover_support_iht.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, i32, vp, i32, vp, vp, vp, vp]
+    lib.cs_recover_support_inc.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32,
+                                           vp, vp, ctypes.c_float, i32, vp, vp, vp, vp]
     lib.cs_block_ffn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, i32, vp, i32, i32, vp]
     lib.cs_head_attn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
     lib.cs_joint_select.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
@@ -148,6 +150,23 @@ class Context:
         if margin is None:
             margin = torch.empty((B,), dtype=torch.float32, device=dev)
         self._check(self.lib.cs_recover_support_iht(self._h, ctypes.byref(op), ctypes.byref(dct), k, iters, _ptr(y), B,
+                                                    _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
+        return support, coef, resid, margin
+
+    def cs_recover_support_inc(self, op, dct, k, y, prev_support, swaps, prev_coef=None, gamma=0.0,
+                               support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True):
+        B = y.shape[0]
+        dev = y.device
+        if support is None:
+            support = torch.empty((B, k), dtype=torch.int32, device=dev)
+        if coef is None and want_coef:
+            coef = torch.empty((B, k * dct.rb), dtype=torch.float32, device=dev)
+        if resid is None and want_resid:
+            resid = torch.empty((B,), dtype=torch.float32, device=dev)
+        if margin is None:
+            margin = torch.empty((B,), dtype=torch.float32, device=dev)
+        self._check(self.lib.cs_recover_support_inc(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
+                                                    _ptr(prev_support), _ptr(prev_coef), float(gamma), swaps,
                                                     _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 

@@ -287,6 +287,36 @@ cs_status cs_recover_support_iht(cs_ctx* c, const cs_op* op, const cs_dict* dict
     return CS_OK;
 }
 
+cs_status cs_recover_support_inc(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k,
+                                 const float* y, int B,
+                                 const int32_t* prev_support, const float* prev_coef, float gamma, int swaps,
+                                 int32_t* support, float* coef, float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_recover_args(c, op, dict, k, "cs_recover_support_inc")) != CS_OK) return st;
+    if (swaps < 0 || swaps > k) return fail(c, CS_EINVAL, "cs_recover_support_inc: swaps=%d out of range [0, k=%d]", swaps, k);
+    if (!(gamma >= 0.f)) return fail(c, CS_EINVAL, "cs_recover_support_inc: gamma must be >= 0");
+    if (B < 0) return fail(c, CS_EINVAL, "cs_recover_support_inc: B < 0");
+    if (B == 0) return CS_OK;
+    if (!y || !support || !prev_support) return fail(c, CS_EINVAL, "cs_recover_support_inc: NULL buffer");
+    if (!aligned16(y) || !aligned16(support) || !aligned16(coef) || !aligned16(resid_norm) || !aligned16(margin) ||
+        !aligned16(prev_support) || !aligned16(prev_coef))
+        return fail(c, CS_EALIGN, "cs_recover_support_inc: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    const Plan* plan = nullptr;
+    if ((st = find_or_build_plan(c, op, dict, &plan)) != CS_OK) return st;
+    if (!recover_inc_supported(*plan, k, c->lds_limit))
+        return fail(c, CS_EINVAL, "cs_recover_support_inc: needs rb == 1, k <= 64 and G <= 512");
+    RecoverArgs a;
+    a.y = y; a.B = B; a.k = k; a.support = support; a.coef = coef; a.resid = resid_norm; a.margin = margin;
+    a.spill = nullptr; a.spill_stride = 0;
+    IncArgs q;
+    q.prev_support = prev_support; q.prev_coef = prev_coef; q.gamma = gamma; q.swaps = swaps;
+    hipError_t e = launch_recover_inc(*plan, a, q, c->lds_limit, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_inc");
+    return CS_OK;
+}
+
 cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
                        int d, int G, int b, const void* x, int T,
                        const int32_t* support, int k, int shared, void* out) {

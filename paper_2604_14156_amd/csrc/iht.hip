@@ -12,6 +12,7 @@
 // by least squares on the final support (Cholesky factor of G_SS built in LDS by one
 // wavefront, then one refinement step against the explicit residual).
 #include "kernels.hpp"
+#include "small_dense.hpp"
 
 namespace csk {
 
@@ -223,41 +224,9 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
     constexpr int LS = IH_MAXK + 1;
     if (want_fit) {
         // Cholesky factor of G_SS, one wavefront: lane j builds row j
-        if (wave == 0) {
-            for (int i = 0; i < k; ++i) {
-                const int si = S[i];
-                if (lane >= i && lane < k) {
-                    const int sj = S[lane];
-                    float s = gram[(size_t)si * N + sj];
-                    for (int t = 0; t < i; ++t) s -= Lf[lane * LS + t] * Lf[i * LS + t];
-                    Lf[lane * LS + i] = s;              // un-normalised; row i's own entry is the pivot
-                }
-                __builtin_amdgcn_wave_barrier();
-                const float piv = Lf[i * LS + i];
-                const float inv = piv > 0.f ? __builtin_amdgcn_rsqf(piv) : 0.f;
-                if (piv <= 0.f) bad = 1;
-                __builtin_amdgcn_wave_barrier();
-                if (lane >= i && lane < k) Lf[lane * LS + i] *= inv;      // L[i][i] = sqrt(piv), L[j][i] /= sqrt(piv)
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
+        if (wave == 0) bad |= wave_cholesky(gram, N, S, k, 0.f, Lf, LS, lane);
         bad = __syncthreads_or(bad);
-        // solves with L (lower, rows in LDS): forward L w = rhs, backward L^T x = w; lane i holds component i
-        auto solve = [&](float rhs) -> float {
-            for (int i = 0; i < k; ++i) {                // forward
-                const float lii = Lf[i * LS + i];
-                const float xi = lii > 0.f ? readlane_f32(rhs, i) / lii : 0.f;
-                if (lane == i) rhs = xi;
-                if (lane > i && lane < k) rhs -= Lf[lane * LS + i] * xi;
-            }
-            for (int i = k - 1; i >= 0; --i) {           // backward
-                const float lii = Lf[i * LS + i];
-                const float xi = lii > 0.f ? readlane_f32(rhs, i) / lii : 0.f;
-                if (lane == i) rhs = xi;
-                if (lane < i) rhs -= Lf[i * LS + lane] * xi;
-            }
-            return rhs;
-        };
+        auto solve = [&](float rhs) -> float { return wave_cholesky_solve(Lf, LS, k, rhs, lane); };
         if (active) en[tid] = c0;                        // right-hand side c0_S: published through en[]
         __syncthreads();
         if (wave == 0) {

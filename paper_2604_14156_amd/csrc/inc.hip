@@ -1,0 +1,338 @@
+// Warm-started structured recovery: the previous token's support is corrected by a
+// backward/forward exchange instead of being recovered from nothing (paper Sec. 5: temporal
+// regulariser gamma ||alpha_t - alpha_{t-1}||^2 and incremental support updates; Sec. 10,
+// proposition on incremental token-adaptive recovery).  One workgroup per sketch, one atom
+// per unit.
+//
+//   1. alpha1 = argmin ||y - M_S a||^2 + gamma ||a - alpha_prev||^2 on the previous support S;
+//   2. the `swaps` units of S with the least energy (alpha1_j ||m_j||)^2 leave (among equal
+//      energies the larger index first);
+//   3. `swaps` greedy rounds (score of the unselected units on the residual of the least-squares
+//      fit of the current units, ties -> smaller index) bring the support back to k units;
+//   4. least-squares refit, explicit residual, one refinement step.
+//
+// Everything runs in the Gram domain (G = M^T M in LDS, c0 = M^T y): the correlation with the
+// residual of a fit on S is c0 - G[:, S] alpha, the fits are Cholesky solves of G_SS by one
+// wavefront (a factorisation per refit of a changed list, one appended row per greedy round).
+#include "kernels.hpp"
+#include "small_dense.hpp"
+
+namespace csk {
+
+constexpr int IN_MAXK = 64;
+constexpr int IN_THREADS = 512;
+
+struct IncLayout {
+    int off_y, off_r, off_c0, off_nrm, off_flag, off_S, off_S2, off_t, off_L, off_misc, off_red, off_gram, off_stage;
+    int total_floats;
+};
+
+static bool make_inc_layout(const Plan& p, int lds_limit, int nthreads, IncLayout& L) {
+    const int N = p.N, m = p.op.m;
+    const int Np = (N + 7) & ~7;
+    int o = 0;
+    L.off_y = o; o += (m + 3) & ~3;
+    L.off_r = o; o += (m + 3) & ~3;
+    L.off_c0 = o; o += Np;
+    L.off_nrm = o; o += Np;
+    L.off_flag = o; o += Np;
+    L.off_S = o; o += IN_MAXK;
+    L.off_S2 = o; o += IN_MAXK;
+    L.off_t = o; o += 4 * IN_MAXK;
+    L.off_L = o; o += IN_MAXK * (IN_MAXK + 1);
+    L.off_misc = o; o += 32;
+    L.off_red = o; o += 64;                  // per wave: 64-bit best key, runner-up score
+    L.off_stage = o; o += nthreads * 4;
+    L.off_gram = -1;
+    const long limit = lds_limit / 4 - 16;
+    if (o > limit) return false;
+    if ((long)o + (long)N * N <= limit) { L.off_gram = o; o += N * N; }
+    L.total_floats = o;
+    return true;
+}
+
+template <bool GRAM_LDS>
+__global__ __launch_bounds__(IN_THREADS)
+void recover_inc_kernel(Plan p, RecoverArgs a, IncArgs q, IncLayout L) {
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, NT = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = NT >> 6;
+    const int prob = blockIdx.x;
+    const int N = p.N, m = p.op.m, k = a.k;
+    const int swaps = q.swaps, K0 = k - swaps;
+    const bool active = tid < N;
+
+    float* yv = lds + L.off_y;
+    float* rv = lds + L.off_r;
+    float* c0v = lds + L.off_c0;
+    float* nrm = lds + L.off_nrm;
+    int* flag = reinterpret_cast<int*>(lds + L.off_flag);
+    int* S = reinterpret_cast<int*>(lds + L.off_S);
+    int* S2 = reinterpret_cast<int*>(lds + L.off_S2);
+    float* tv = lds + L.off_t;                  // [4][IN_MAXK] small vectors
+    float* Lf = lds + L.off_L;                  // Cholesky factor, row stride IN_MAXK + 1
+    int* misc = reinterpret_cast<int*>(lds + L.off_misc);
+    float* red = lds + L.off_red;
+    float* stage = lds + L.off_stage;
+    float* gram_l = lds + L.off_gram;
+    const float* gram = GRAM_LDS ? gram_l : p.gram;
+    constexpr int LS = IN_MAXK + 1;
+    float* beta = tv, *xs = tv + IN_MAXK, *gv = tv + 2 * IN_MAXK, *dl = tv + 3 * IN_MAXK;
+
+    // ---- loads: sketch, atom norms, Gram matrix, c0 = M^T y
+    const float* y = a.y + (size_t)prob * m;
+    int bad = 0;
+    for (int i = tid; i < m; i += NT) {
+        const float v = y[i];
+        yv[i] = v;
+        if (!isfinite(v)) bad = 1;
+    }
+    float iw = 1.f, w = 1.f;                           // W holds 1/norm of the atom
+    if (active && p.weighted) { iw = p.W[tid]; w = iw > 0.f ? 1.0f / iw : 0.f; }
+    if (active) { nrm[tid] = w; flag[tid] = 0; }
+    if (GRAM_LDS) {
+        const int n4 = (N * N) >> 2;
+        const float4* src = reinterpret_cast<const float4*>(p.gram);
+        float4* dst = reinterpret_cast<float4*>(gram_l);
+        constexpr int U = 8;
+        for (int base = 0; base < n4; base += NT * U) {
+            float4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * NT + tid;
+                r[u] = idx < n4 ? src[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * NT + tid;
+                if (idx < n4) dst[idx] = r[u];
+            }
+        }
+        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gram_l[i] = p.gram[i];
+    }
+    // previous support: in range and without repeats, else the row is reported as failed
+    if (wave == 0) {
+        const int u = lane < k ? q.prev_support[(size_t)prob * k + lane] : -1;
+        int ok = lane >= k || (u >= 0 && u < p.G);
+        for (int i = 0; i < k; ++i) {
+            const int ui = __builtin_amdgcn_readlane(u, i);
+            if (lane < k && lane != i && ui == u) ok = 0;
+        }
+        if (!ok) bad = 1;
+        if (lane < k) S[lane] = ok ? u : 0;
+    }
+    bad = __syncthreads_or(bad);
+    float c0 = 0.f;
+    {
+        const int parts = NT / N > 0 ? NT / N : 1;
+        const int c = tid % N, part = tid / N;
+        const int rows_per = (m + parts - 1) / parts;
+        if (part < parts) {
+            const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
+            float acc = 0.f;
+#pragma unroll 8
+            for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + c] * yv[i];
+            stage[part * N + c] = acc;
+        }
+        __syncthreads();
+        if (active) for (int qq = 0; qq < parts; ++qq) c0 += stage[qq * N + tid];
+    }
+    if (active) c0v[tid] = c0;
+    __syncthreads();
+    if (bad) {                                           // uniform: NaN sketch or invalid previous support
+        for (int i = tid; i < k; i += NT) {
+            a.support[(size_t)prob * k + i] = -1;
+            if (a.coef) a.coef[(size_t)prob * k + i] = 0.f;
+        }
+        if (tid == 0) {
+            if (a.resid) a.resid[prob] = __int_as_float(0x7fc00000);
+            if (a.margin) a.margin[prob] = 0.f;
+        }
+        return;
+    }
+
+    // ---- 1./2. regularised refit on the previous support, then the backward step
+    const bool ridge = q.prev_coef != nullptr && q.gamma > 0.f;
+    if (wave == 0) {
+        int wbad = wave_cholesky(gram, N, S, k, ridge ? q.gamma : 0.f, Lf, LS, lane);
+        float rhs = lane < k ? c0v[S[lane]] : 0.f;
+        if (ridge && lane < k) rhs += q.gamma * q.prev_coef[(size_t)prob * k + lane];
+        const float x = wave_cholesky_solve(Lf, LS, k, rhs, lane);
+        if (swaps == 0) {
+            if (lane < k) { S2[lane] = S[lane]; xs[lane] = x; }
+        } else {
+            const int u = lane < k ? S[lane] : 0x7fffffff;
+            float e = lane < k ? x * nrm[lane < k ? S[lane] : 0] : -1.f;
+            e = e * e;
+            if (lane >= k) e = -1.f;
+            else if (!(e >= 0.f)) e = 0.f;
+            int rank = 0;                                // 0 = strongest; equal energies: smaller index first
+            for (int i = 0; i < k; ++i) {
+                const float ei = readlane_f32(e, i);
+                const int ui = __builtin_amdgcn_readlane(u, i);
+                rank += (int)(ei > e) | ((int)(ei == e) & (int)(ui < u));
+            }
+            if (lane < k && rank < K0) S2[rank] = u;
+        }
+        if (wbad && lane == 0) misc[0] = 1;
+        if (!wbad && lane == 0) misc[0] = 0;
+    }
+    __syncthreads();
+    // ---- kept units: flags, factor and fit (a changed list, or a ridge in the first factor, needs a new factor)
+    if (tid < K0) flag[S2[tid]] = 1;
+    if (wave == 0) {
+        if (lane < K0) S[lane] = S2[lane];
+        __builtin_amdgcn_wave_barrier();
+        if (swaps > 0 || ridge) {
+            const int wbad = K0 > 0 ? wave_cholesky(gram, N, S, K0, 0.f, Lf, LS, lane) : 0;
+            const float x = wave_cholesky_solve(Lf, LS, K0, lane < K0 ? c0v[S[lane]] : 0.f, lane);
+            if (lane < K0) xs[lane] = x;
+            if (wbad && lane == 0) misc[0] = 1;
+        }
+    }
+    __syncthreads();
+
+    // ---- 3. forward step
+    float margin = 1.f;
+    unsigned long long* redk = reinterpret_cast<unsigned long long*>(red);       // [nwaves] best keys
+    float* red2 = red + 32;                                                       // [nwaves] runner-up scores
+    for (int it = 0; it < swaps; ++it) {
+        const int K = K0 + it;
+        // correlation with the residual of the current fit: c0 - G[:, S] alpha.  Every wave keeps the
+        // list and its coefficients in its first K lanes and hands them out by scalar lane reads.
+        const int sreg = lane < K ? S[lane] : 0;
+        const float areg = lane < K ? xs[lane] : 0.f;
+        const int ta = active ? tid : 0;
+        float acc = 0.f;
+        for (int j = 0; j < K; j += 4) {
+            float gv4[4], av4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {               // lanes >= K hold index 0 and coefficient 0; j + u <= 63
+                const int sj = __builtin_amdgcn_readlane(sreg, j + u);
+                av4[u] = readlane_f32(areg, j + u);
+                gv4[u] = gram[(size_t)sj * N + ta];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc += av4[u] * gv4[u];
+        }
+        float sc = iw * (c0 - acc);
+        sc = sc * sc;
+        if (!(sc >= 0.f)) sc = 0.f;
+        const bool cand = active && flag[tid] == 0;
+        // best (ties -> smaller index) and runner-up: keys order by score, then by descending index
+        unsigned long long key = cand ? ((unsigned long long)__float_as_uint(sc) << 32) | (0xffffffffu - (unsigned)tid) : 0ull;
+        unsigned long long kb = key;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const unsigned long long o = __shfl_xor(kb, off);
+            kb = o > kb ? o : kb;
+        }
+        const float s2w = wave_max(cand && key != kb ? sc : -1.f);
+        if (lane == 0) { redk[wave] = kb; red2[wave] = s2w; }
+        __syncthreads();
+        unsigned long long gb = 0ull;
+        for (int wv = 0; wv < nwaves; ++wv) { const unsigned long long o = redk[wv]; gb = o > gb ? o : gb; }
+        float s2 = 0.f;
+        for (int wv = 0; wv < nwaves; ++wv) {
+            const unsigned long long o = redk[wv];
+            if (o != gb && o != 0ull) s2 = fmaxf(s2, __uint_as_float((unsigned)(o >> 32)));
+            s2 = fmaxf(s2, red2[wv]);
+        }
+        const float s1 = __uint_as_float((unsigned)(gb >> 32));
+        const int best = min(max((int)(0xffffffffu - (unsigned)(gb & 0xffffffffull)), 0), N - 1);   // always a candidate: K < k <= N
+        margin = fminf(margin, s1 > 0.f ? (s1 - s2) / s1 : 0.f);
+        if (wave == 0) {
+            const int wbad = wave_cholesky_append(gram, N, S, K, best, Lf, LS, lane);
+            if (lane == 0) { S[K] = best; flag[best] = 1; if (wbad) misc[0] = 1; }
+            __builtin_amdgcn_wave_barrier();
+            const float x = wave_cholesky_solve(Lf, LS, K + 1, lane <= K ? c0v[lane < K ? sreg : best] : 0.f, lane);
+            if (lane <= K) xs[lane] = x;
+        }
+        __syncthreads();
+    }
+    bad = misc[0];
+
+    // ---- 4. explicit residual and one refinement step on the final support
+    const bool want_fit = a.coef != nullptr || a.resid != nullptr;
+    if (want_fit) {
+        for (int i = tid; i < m; i += NT) {
+            float s = yv[i];
+            for (int j = 0; j < k; ++j) s -= xs[j] * p.Mr[(size_t)i * N + S[j]];
+            rv[i] = s;
+        }
+        __syncthreads();
+        for (int j = wave; j < k; j += nwaves) {
+            float s = 0.f;
+            for (int i = lane; i < m; i += 64) s += p.Mr[(size_t)i * N + S[j]] * rv[i];
+            s = wave_sum(s);
+            if (lane == 0) gv[j] = s;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const float d = wave_cholesky_solve(Lf, LS, k, lane < k ? gv[lane] : 0.f, lane);
+            if (lane < k) { xs[lane] += d; dl[lane] = d; }
+        }
+        __syncthreads();
+        float ss = 0.f;
+        for (int i = tid; i < m; i += NT) {
+            float s = rv[i];
+            for (int j = 0; j < k; ++j) s -= dl[j] * p.Mr[(size_t)i * N + S[j]];
+            ss += s * s;
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) beta[wave] = ss;                  // beta[] is free: per-wave partial sums
+        __syncthreads();
+    }
+    for (int qi = tid; qi < k; qi += NT) {
+        const int gsel = S[qi];
+        int rank = 0;
+        for (int o = 0; o < k; ++o) rank += S[o] < gsel;
+        a.support[(size_t)prob * k + rank] = gsel;
+        if (a.coef) a.coef[(size_t)prob * k + rank] = xs[qi];
+    }
+    if (tid == 0) {
+        if (a.resid) {
+            float tot = 0.f;
+            for (int wv = 0; wv < nwaves; ++wv) tot += beta[wv];
+            a.resid[prob] = bad ? __int_as_float(0x7fc00000) : sqrtf(tot);
+        }
+        if (a.margin) a.margin[prob] = bad ? 0.f : margin;
+    }
+}
+
+bool recover_inc_supported(const Plan& p, int k, int lds_limit) {
+    if (p.rb != 1 || k > IN_MAXK || p.N > IN_THREADS) return false;
+    IncLayout L;
+    const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : IN_THREADS;
+    return make_inc_layout(p, lds_limit, nthreads, L);
+}
+
+hipError_t launch_recover_inc(const Plan& p, const RecoverArgs& a, const IncArgs& q, int lds_limit, hipStream_t s) {
+    if (a.B <= 0) return hipSuccess;
+    const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : IN_THREADS;
+    IncLayout L;
+    if (!make_inc_layout(p, lds_limit, nthreads, L)) return hipErrorInvalidValue;
+    const size_t bytes = (size_t)L.total_floats * 4;
+    if (L.off_gram >= 0) {
+        static size_t allowed = 0;
+        if (bytes > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_inc_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e != hipSuccess) return e;
+            allowed = bytes;
+        }
+        hipLaunchKernelGGL(recover_inc_kernel<true>, dim3(a.B), dim3(nthreads), bytes, s, p, a, q, L);
+    } else {
+        static size_t allowed = 0;
+        if (bytes > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_inc_kernel<false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e != hipSuccess) return e;
+            allowed = bytes;
+        }
+        hipLaunchKernelGGL(recover_inc_kernel<false>, dim3(a.B), dim3(nthreads), bytes, s, p, a, q, L);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace csk

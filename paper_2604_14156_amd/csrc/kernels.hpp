@@ -36,6 +36,16 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
 bool recover_iht_supported(const Plan& p, int k, int lds_limit);
 hipError_t launch_recover_iht(const Plan& p, const RecoverArgs& a, int iters, int lds_limit, hipStream_t s);
 
+// warm-started recovery around the previous support (inc.hip): one atom per unit, k <= 64, N <= 512
+struct IncArgs {
+    const int32_t* prev_support;   // [B][k]
+    const float* prev_coef;        // [B][k] in the order of prev_support, or nullptr
+    float gamma;                   // weight of the pull towards prev_coef in the first refit
+    int swaps;                     // units that may leave and enter
+};
+bool recover_inc_supported(const Plan& p, int k, int lds_limit);
+hipError_t launch_recover_inc(const Plan& p, const RecoverArgs& a, const IncArgs& q, int lds_limit, hipStream_t s);
+
 // p[n] = Phi^T y (back-projection), then top-k.
 hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s);
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s);

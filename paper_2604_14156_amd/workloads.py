@@ -125,6 +125,33 @@ def plant_usage(rng, pi, k, B, amp, bg):
     return z.astype(np.float32), supports
 
 
+def drift_supports(rng, supports, G, swaps):
+    """Next-token supports: every row of `supports` [B, k] has `swaps` of its units replaced by
+    units it did not hold (planted support drift of 2*swaps units).  Rows come back ascending."""
+    out = np.empty_like(supports)
+    for t in range(supports.shape[0]):
+        S = supports[t].tolist()
+        leave = set(rng.choice(len(S), size=swaps, replace=False).tolist())
+        pool = np.setdiff1d(np.arange(G), np.array(S))
+        enter = rng.choice(pool, size=swaps, replace=False).tolist()
+        out[t] = np.sort(np.array([g for i, g in enumerate(S) if i not in leave] + enter))
+    return out
+
+
+def plant_usage_on(rng, pi, supports, amp, bg):
+    """Planted usage vectors on given supports [B, k] (same value recipe as plant_usage)."""
+    G, b = pi.shape
+    B, k = supports.shape
+    z = np.zeros((B, G * b))
+    for t in range(B):
+        a = np.ones(k) if amp == "unit" else rng.laplace(0.0, 1.0, size=k)
+        for j, g in enumerate(supports[t]):
+            z[t, g * b:(g + 1) * b] = a[j] * pi[g]
+        if bg > 0.0:
+            z[t] += bg * rng.standard_normal(G * b)
+    return z.astype(np.float32)
+
+
 def plant_usage_literal(rng, G, b, k, B, amp, bg):
     """The literal reading: every active entry is its own draw (z is not in the
     span of any rank-1 dictionary).  Used for timing and parity only."""

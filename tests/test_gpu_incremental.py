@@ -1,0 +1,135 @@
+"""GPU parity: warm-started (incremental) recovery against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_14156_amd import binding, workloads as wl
+from gpu_util import dev_f32, dev_i32, host
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-3          # supports are compared bit-exactly only when the oracle's decisions are this clear
+RES_TOL = 1e-5
+
+
+def _check(cs, op, dct, M, Y, G, k, prev, swaps, normalised, prev_coef=None, gamma=0.0):
+    sup, coef, resid, margin = cs.cs_recover_support_inc(
+        op, dct, k, dev_f32(Y), dev_i32(prev), swaps,
+        prev_coef=None if prev_coef is None else dev_f32(prev_coef), gamma=gamma)
+    sup, coef, resid, margin = host(sup), host(coef), host(resid), host(margin)
+    exact = 0
+    for t in range(Y.shape[0]):
+        y = Y[t].astype(np.float64)
+        rec = oracle.incremental_block_omp(M, y, G, 1, k, prev[t], swaps, normalised,
+                                           prev_coef=None if prev_coef is None else prev_coef[t].astype(np.float64),
+                                           gamma=gamma)
+        s = sup[t]
+        assert len(set(s.tolist())) == k and np.all(np.diff(s) > 0) and s.min() >= 0 and s.max() < G, (t, s)
+        assert len(set(s.tolist()) & set(prev[t].tolist())) >= k - swaps          # within the drift budget
+        ls, *_ = np.linalg.lstsq(M[:, s], y, rcond=None)
+        own = np.linalg.norm(y - M[:, s] @ ls)
+        ynorm = np.linalg.norm(y)
+        assert abs(resid[t] - own) <= RES_TOL * ynorm
+        assert np.linalg.norm(coef[t] - ls) <= 1e-4 * max(np.linalg.norm(ls), 1e-30)
+        if rec["margin"] > MARGIN and rec["drop_margin"] > MARGIN:
+            assert list(s) == list(rec["support"]), (t, rec["margin"], rec["drop_margin"])
+            assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm
+            assert abs(margin[t] - rec["margin"]) <= 1e-3
+            exact += 1
+    return exact
+
+
+def _decode_case(seed, B, true_swaps):
+    c = wl.CFG2
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    _, S_prev = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
+    S_now = wl.drift_supports(rng, S_prev, c.G, true_swaps)
+    z = wl.plant_usage_on(rng, pi, S_now, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 4, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 4, c.m, c.n, c.G, c.b, 1, psi)
+    Y = oracle.sketch(c.ens, seed, 4, c.m, z).astype(np.float32)
+    prev = np.stack([rng.permutation(S_prev[t]) for t in range(B)]).astype(np.int32)     # any order
+    return c, op, dct, psi_dev, M, Y, prev, S_now, rng
+
+
+@pytest.mark.parametrize("swaps,true_swaps", [(0, 0), (1, 1), (4, 3), (12, 12), (43, 5)])
+def test_incremental_decode_shape(cs, swaps, true_swaps):
+    c, op, dct, psi_dev, M, Y, prev, S_now, rng = _decode_case(4100 + swaps, 5, true_swaps)
+    cs.cs_plan(op, dct, psi_dev)
+    exact = _check(cs, op, dct, M, Y, c.G, c.k, prev, swaps, True)
+    assert exact >= 2
+
+
+def test_incremental_with_temporal_regulariser(cs):
+    c, op, dct, psi_dev, M, Y, prev, S_now, rng = _decode_case(4200, 4, 3)
+    cs.cs_plan(op, dct, psi_dev)
+    prev_coef = rng.laplace(0.0, 1.0, size=prev.shape).astype(np.float32)
+    for gamma in (0.05, 2.0):
+        assert _check(cs, op, dct, M, Y, c.G, c.k, prev, 4, True, prev_coef=prev_coef, gamma=gamma) >= 1
+    # gamma without previous coefficients is the unregularised call
+    a = host(cs.cs_recover_support_inc(op, dct, c.k, dev_f32(Y), dev_i32(prev), 4, gamma=3.0)[0])
+    b = host(cs.cs_recover_support_inc(op, dct, c.k, dev_f32(Y), dev_i32(prev), 4)[0])
+    assert np.array_equal(a, b)
+
+
+def test_full_budget_equals_recovery_from_scratch_and_in_place_update(cs):
+    c, op, dct, psi_dev, M, Y, prev, S_now, rng = _decode_case(4300, 4, 2)
+    cs.cs_plan(op, dct, psi_dev)
+    y = dev_f32(Y)
+    ref = cs.cs_recover_support(op, dct, c.k, y)
+    got = cs.cs_recover_support_inc(op, dct, c.k, y, dev_i32(prev), c.k)
+    assert np.array_equal(host(got[0]), host(ref[0]))
+    assert np.allclose(host(got[2]), host(ref[2]), rtol=0, atol=RES_TOL * np.linalg.norm(Y, axis=1).max())
+    # the support buffer may be the previous-support buffer
+    buf = dev_i32(prev)
+    want = host(cs.cs_recover_support_inc(op, dct, c.k, y, dev_i32(prev), 3)[0])
+    cs.cs_recover_support_inc(op, dct, c.k, y, buf, 3, support=buf)
+    assert np.array_equal(host(buf), want)
+
+
+def test_incremental_head_selection_identity_dictionary(cs):
+    hs = wl.CFG3_HEADS
+    seed = 4400
+    rng = wl.rng_for(seed)
+    B = 8
+    _, S_prev = wl.plant_head_usage(rng, hs, B)
+    S_now = wl.drift_supports(rng, S_prev, hs.H, 2)
+    u = (hs.bg * rng.standard_normal((B, hs.H)))
+    for t in range(B):
+        u[t, S_now[t]] += rng.standard_normal(hs.kh)
+    op = binding.make_op(hs.ens, seed, 3, hs.m, hs.H)
+    dct = binding.make_dict(None, hs.H, 1, 1)
+    M = oracle.effective_matrix(hs.ens, seed, 3, hs.m, hs.H, hs.H, 1, 1, None)
+    Y = oracle.sketch(hs.ens, seed, 3, hs.m, u.astype(np.float32)).astype(np.float32)
+    for swaps in (0, 2, 5):
+        assert _check(cs, op, dct, M, Y, hs.H, hs.kh, S_prev.astype(np.int32), swaps, False) >= 3
+
+
+def test_invalid_rows_and_arguments(cs):
+    c, op, dct, psi_dev, M, Y, prev, S_now, rng = _decode_case(4500, 3, 2)
+    cs.cs_plan(op, dct, psi_dev)
+    bad = prev.copy()
+    bad[0, 5] = bad[0, 6]              # a repeated unit
+    bad[2, 0] = c.G                    # out of range
+    sup, coef, resid, margin = cs.cs_recover_support_inc(op, dct, c.k, dev_f32(Y), dev_i32(bad), 2)
+    sup, coef, resid, margin = host(sup), host(coef), host(resid), host(margin)
+    for t in (0, 2):
+        assert np.all(sup[t] == -1) and np.all(coef[t] == 0.0) and np.isnan(resid[t]) and margin[t] == 0.0
+    rec = oracle.incremental_block_omp(M, Y[1].astype(np.float64), c.G, 1, c.k, prev[1], 2, True)
+    if rec["margin"] > MARGIN and rec["drop_margin"] > MARGIN:
+        assert list(sup[1]) == list(rec["support"])
+    assert np.isfinite(resid[1]) and len(set(sup[1].tolist())) == c.k
+    y = dev_f32(Y)
+    for kwargs, args in (({}, (c.k + 1,)), ({"gamma": -1.0}, (2,))):
+        with pytest.raises(binding.CsError) as e:
+            cs.cs_recover_support_inc(op, dct, c.k, y, dev_i32(prev), *args, **kwargs)
+        assert e.value.status == binding.CS_EINVAL
+    big = binding.make_dict(None, 32, 4, 4)                      # rb > 1 is not supported by this solver
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support_inc(binding.make_op(wl.GAUSS, 1, 0, 48, 128), big, 3, dev_f32(np.zeros((1, 48))),
+                                  dev_i32(np.array([[0, 1, 2]])), 1)
+    assert e.value.status == binding.CS_EINVAL
