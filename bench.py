@@ -333,6 +333,15 @@ def extra_measurements(ctx, st, wl, stream):
                                               st.resid if fit else None, st.marginh, want_coef=False, want_resid=False)
         time_loop(fn, nl, stream)
         res["recover_heads_us_per_call_B%d_%s" % (B, tag)] = time_loop(fn, 2 * nl, stream) * 1e3
+    # warm-started recovery: previous supports = an earlier recovery of the same shape, drift budget `swaps`
+    prev = torch.empty((B, c.k), dtype=torch.int32, device=dev)
+    ctx.cs_recover_support(st.ffn_op[0], st.ffn_dict[0], c.k, st.y, prev, None, None, st.margin,
+                           want_coef=False, want_resid=False)
+    for swaps in (0, 2, 4, 8):
+        fn = lambda i: ctx.cs_recover_support_inc(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, prev, swaps,
+                                                  support=st.S[0], margin=st.margin, want_coef=False, want_resid=False)
+        time_loop(fn, nl, stream)
+        res["recover_ffn_incremental_us_per_call_B%d_swaps%d" % (B, swaps)] = time_loop(fn, 2 * nl, stream) * 1e3
     fn = lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y)
     time_loop(fn, nl, stream)
     res["sketch_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3

@@ -13,6 +13,7 @@
 // wavefront, then one refinement step against the explicit residual).
 #include "kernels.hpp"
 #include "small_dense.hpp"
+#include "gram_loads.hpp"
 
 namespace csk {
 
@@ -71,52 +72,12 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
     float* gram_l = lds + L.off_gram;
     const float* gram = GRAM_LDS ? gram_l : p.gram;
 
-    // ---- loads: sketch, weight, Gram matrix, M for c0 = M^T y (same scheme as the greedy kernel)
+    // ---- loads: sketch, weight, Gram matrix, c0 = M^T y
     const float* y = a.y + (size_t)prob * m;
     int bad = 0;
-    for (int i = tid; i < m; i += NT) {
-        const float v = y[i];
-        yv[i] = v;
-        if (!isfinite(v)) bad = 1;
-    }
     float w = 1.f;                                     // atom norm: W holds 1/norm
     if (active && p.weighted) { const float iw = p.W[tid]; w = iw > 0.f ? 1.0f / iw : 0.f; }
-    if (GRAM_LDS) {
-        const int n4 = (N * N) >> 2;
-        const float4* src = reinterpret_cast<const float4*>(p.gram);
-        float4* dst = reinterpret_cast<float4*>(gram_l);
-        constexpr int U = 8;
-        for (int base = 0; base < n4; base += NT * U) {
-            float4 r[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * NT + tid;
-                r[u] = idx < n4 ? src[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * NT + tid;
-                if (idx < n4) dst[idx] = r[u];
-            }
-        }
-        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gram_l[i] = p.gram[i];
-    }
-    bad = __syncthreads_or(bad);
-    float c0 = 0.f;
-    {
-        const int parts = NT / N > 0 ? NT / N : 1;
-        const int c = tid % N, part = tid / N;
-        const int rows_per = (m + parts - 1) / parts;
-        if (part < parts) {
-            const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
-            float acc = 0.f;
-#pragma unroll 8
-            for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + c] * yv[i];
-            stage[part * N + c] = acc;
-        }
-        __syncthreads();
-        if (active) for (int q = 0; q < parts; ++q) c0 += stage[q * N + tid];
-    }
+    const float c0 = load_sketch_gram_c0<GRAM_LDS>(p, y, yv, gram_l, stage, bad);
     if (active) alpha[tid] = 0.f;
     // helpers of the rank count: thread (c, part) scans a slice of the candidates
     const int Npad = (N + 63) & ~63;
@@ -221,12 +182,11 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
 
     const bool want_fit = a.coef != nullptr || a.resid != nullptr;
     float* beta = tv, *xs = tv + IH_MAXK, *gv = tv + 2 * IH_MAXK, *dl = tv + 3 * IH_MAXK;
-    constexpr int LS = IH_MAXK + 1;
     if (want_fit) {
         // Cholesky factor of G_SS, one wavefront: lane j builds row j
-        if (wave == 0) bad |= wave_cholesky(gram, N, S, k, 0.f, Lf, LS, lane);
+        if (wave == 0) bad |= wave_cholesky(gram, N, S, k, 0.f, Lf, gv, lane);
         bad = __syncthreads_or(bad);
-        auto solve = [&](float rhs) -> float { return wave_cholesky_solve(Lf, LS, k, rhs, lane); };
+        auto solve = [&](float rhs) -> float { return wave_cholesky_solve(Lf, k, rhs, lane); };
         if (active) en[tid] = c0;                        // right-hand side c0_S: published through en[]
         __syncthreads();
         if (wave == 0) {

@@ -16,6 +16,7 @@
 // wavefront (a factorisation per refit of a changed list, one appended row per greedy round).
 #include "kernels.hpp"
 #include "small_dense.hpp"
+#include "gram_loads.hpp"
 
 namespace csk {
 
@@ -76,40 +77,14 @@ void recover_inc_kernel(Plan p, RecoverArgs a, IncArgs q, IncLayout L) {
     float* stage = lds + L.off_stage;
     float* gram_l = lds + L.off_gram;
     const float* gram = GRAM_LDS ? gram_l : p.gram;
-    constexpr int LS = IN_MAXK + 1;
     float* beta = tv, *xs = tv + IN_MAXK, *gv = tv + 2 * IN_MAXK, *dl = tv + 3 * IN_MAXK;
 
     // ---- loads: sketch, atom norms, Gram matrix, c0 = M^T y
     const float* y = a.y + (size_t)prob * m;
     int bad = 0;
-    for (int i = tid; i < m; i += NT) {
-        const float v = y[i];
-        yv[i] = v;
-        if (!isfinite(v)) bad = 1;
-    }
     float iw = 1.f, w = 1.f;                           // W holds 1/norm of the atom
     if (active && p.weighted) { iw = p.W[tid]; w = iw > 0.f ? 1.0f / iw : 0.f; }
     if (active) { nrm[tid] = w; flag[tid] = 0; }
-    if (GRAM_LDS) {
-        const int n4 = (N * N) >> 2;
-        const float4* src = reinterpret_cast<const float4*>(p.gram);
-        float4* dst = reinterpret_cast<float4*>(gram_l);
-        constexpr int U = 8;
-        for (int base = 0; base < n4; base += NT * U) {
-            float4 r[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * NT + tid;
-                r[u] = idx < n4 ? src[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * NT + tid;
-                if (idx < n4) dst[idx] = r[u];
-            }
-        }
-        for (int i = (n4 << 2) + tid; i < N * N; i += NT) gram_l[i] = p.gram[i];
-    }
     // previous support: in range and without repeats, else the row is reported as failed
     if (wave == 0) {
         const int u = lane < k ? q.prev_support[(size_t)prob * k + lane] : -1;
@@ -121,22 +96,7 @@ void recover_inc_kernel(Plan p, RecoverArgs a, IncArgs q, IncLayout L) {
         if (!ok) bad = 1;
         if (lane < k) S[lane] = ok ? u : 0;
     }
-    bad = __syncthreads_or(bad);
-    float c0 = 0.f;
-    {
-        const int parts = NT / N > 0 ? NT / N : 1;
-        const int c = tid % N, part = tid / N;
-        const int rows_per = (m + parts - 1) / parts;
-        if (part < parts) {
-            const int i0 = part * rows_per, i1 = min(m, i0 + rows_per);
-            float acc = 0.f;
-#pragma unroll 8
-            for (int i = i0; i < i1; ++i) acc += p.Mr[(size_t)i * N + c] * yv[i];
-            stage[part * N + c] = acc;
-        }
-        __syncthreads();
-        if (active) for (int qq = 0; qq < parts; ++qq) c0 += stage[qq * N + tid];
-    }
+    const float c0 = load_sketch_gram_c0<GRAM_LDS>(p, y, yv, gram_l, stage, bad);
     if (active) c0v[tid] = c0;
     __syncthreads();
     if (bad) {                                           // uniform: NaN sketch or invalid previous support
@@ -151,45 +111,82 @@ void recover_inc_kernel(Plan p, RecoverArgs a, IncArgs q, IncLayout L) {
         return;
     }
 
-    // ---- 1./2. regularised refit on the previous support, then the backward step
+    // ---- 1./2. regularised refit on the previous support, then the backward step.
+    // The list is first put in the order of a cheap proxy of the unit energies (matched filter,
+    // strongest first).  The units that leave are decided by the energies of the fit itself; when
+    // they turn out to be the last `swaps` of that order (the usual case) the leading part of the
+    // factor and of the forward-substituted right-hand side is already the fit of the kept units.
     const bool ridge = q.prev_coef != nullptr && q.gamma > 0.f;
-    if (wave == 0) {
-        int wbad = wave_cholesky(gram, N, S, k, ridge ? q.gamma : 0.f, Lf, LS, lane);
-        float rhs = lane < k ? c0v[S[lane]] : 0.f;
-        if (ridge && lane < k) rhs += q.gamma * q.prev_coef[(size_t)prob * k + lane];
-        const float x = wave_cholesky_solve(Lf, LS, k, rhs, lane);
-        if (swaps == 0) {
-            if (lane < k) { S2[lane] = S[lane]; xs[lane] = x; }
-        } else {
-            const int u = lane < k ? S[lane] : 0x7fffffff;
-            float e = lane < k ? x * nrm[lane < k ? S[lane] : 0] : -1.f;
-            e = e * e;
-            if (lane >= k) e = -1.f;
-            else if (!(e >= 0.f)) e = 0.f;
-            int rank = 0;                                // 0 = strongest; equal energies: smaller index first
+    float zreg = 0.f;                                  // wave 0, lane j: component j of L^{-1} c0_S
+    if (wave == 0 && swaps == k && lane == 0) misc[0] = 0;   // everything leaves: nothing to fit
+    if (wave == 0 && swaps < k) {
+        const int u = lane < k ? S[lane] : 0x7fffffff;
+        float pcoef = (ridge && lane < k) ? q.prev_coef[(size_t)prob * k + lane] : 0.f;
+        // rank by (value descending, unit index ascending) within the first k lanes
+        auto rank_of = [&](float e) -> int {
+            int rank = 0;
             for (int i = 0; i < k; ++i) {
                 const float ei = readlane_f32(e, i);
                 const int ui = __builtin_amdgcn_readlane(u, i);
                 rank += (int)(ei > e) | ((int)(ei == e) & (int)(ui < u));
             }
-            if (lane < k && rank < K0) S2[rank] = u;
+            return rank;
+        };
+        int pos = lane;                                  // position of this lane's unit in the list
+        if (swaps > 0) {
+            float pe = lane < k ? c0v[lane < k ? u : 0] * (p.weighted ? p.W[lane < k ? u : 0] : 1.f) : -1.f;
+            pe = pe * pe;
+            if (lane >= k) pe = -1.f; else if (!(pe >= 0.f)) pe = 0.f;
+            pos = rank_of(pe);
+            __builtin_amdgcn_wave_barrier();
+            if (lane < k) { S[pos] = u; xs[pos] = pcoef; }
+            __builtin_amdgcn_wave_barrier();
+            pcoef = lane < k ? xs[lane] : 0.f;           // previous coefficient of the unit now at `lane`
         }
-        if (wbad && lane == 0) misc[0] = 1;
-        if (!wbad && lane == 0) misc[0] = 0;
+        const int su = lane < k ? S[lane] : 0x7fffffff;   // unit at position `lane`
+        int wbad = wave_cholesky(gram, N, S, k, ridge ? q.gamma : 0.f, Lf, gv, lane);
+        float rhs = lane < k ? c0v[su] : 0.f;
+        if (ridge) rhs += q.gamma * pcoef;
+        zreg = wave_forward(Lf, k, rhs, lane);
+        const float x = wave_backward(Lf, k, zreg, lane);
+        if (swaps == 0) {
+            if (lane < k) xs[lane] = x;
+            if (ridge) {                                 // the fit reported is the plain one: factor without the ridge
+                wbad |= wave_cholesky(gram, N, S, k, 0.f, Lf, gv, lane);
+                const float x0 = wave_cholesky_solve(Lf, k, lane < k ? c0v[su] : 0.f, lane);
+                if (lane < k) xs[lane] = x0;
+            }
+        } else {
+            // energies of the fit decide; same ordering rule, now on the reordered list
+            float e = lane < k ? x * nrm[lane < k ? su : 0] : -1.f;
+            e = e * e;
+            if (lane >= k) e = -1.f; else if (!(e >= 0.f)) e = 0.f;
+            int rank = 0;                                // 0 = strongest; equal energies: smaller index first
+            for (int i = 0; i < k; ++i) {
+                const float ei = readlane_f32(e, i);
+                const int ui = __builtin_amdgcn_readlane(su, i);
+                rank += (int)(ei > e) | ((int)(ei == e) & (int)(ui < su));
+            }
+            const bool keep = lane < k && rank < K0;
+            const bool agrees = lane >= k || (keep == (lane < K0));
+            const bool reuse = !ridge && __ballot(!agrees) == 0ull;
+            if (reuse) {
+                const float xk = wave_backward(Lf, K0, zreg, lane);
+                if (lane < K0) xs[lane] = xk;
+            } else {
+                __builtin_amdgcn_wave_barrier();
+                if (keep) S[rank] = su;                  // kept units to the front (every lane has read its unit)
+                __builtin_amdgcn_wave_barrier();
+                if (K0 > 0) wbad |= wave_cholesky(gram, N, S, K0, 0.f, Lf, gv, lane);
+                zreg = wave_forward(Lf, K0, lane < K0 ? c0v[S[lane]] : 0.f, lane);
+                const float xk = wave_backward(Lf, K0, zreg, lane);
+                if (lane < K0) xs[lane] = xk;
+            }
+        }
+        if (lane == 0) misc[0] = wbad;
     }
     __syncthreads();
-    // ---- kept units: flags, factor and fit (a changed list, or a ridge in the first factor, needs a new factor)
-    if (tid < K0) flag[S2[tid]] = 1;
-    if (wave == 0) {
-        if (lane < K0) S[lane] = S2[lane];
-        __builtin_amdgcn_wave_barrier();
-        if (swaps > 0 || ridge) {
-            const int wbad = K0 > 0 ? wave_cholesky(gram, N, S, K0, 0.f, Lf, LS, lane) : 0;
-            const float x = wave_cholesky_solve(Lf, LS, K0, lane < K0 ? c0v[S[lane]] : 0.f, lane);
-            if (lane < K0) xs[lane] = x;
-            if (wbad && lane == 0) misc[0] = 1;
-        }
-    }
+    if (tid < K0) flag[S[tid]] = 1;
     __syncthreads();
 
     // ---- 3. forward step
@@ -242,10 +239,14 @@ void recover_inc_kernel(Plan p, RecoverArgs a, IncArgs q, IncLayout L) {
         const int best = min(max((int)(0xffffffffu - (unsigned)(gb & 0xffffffffull)), 0), N - 1);   // always a candidate: K < k <= N
         margin = fminf(margin, s1 > 0.f ? (s1 - s2) / s1 : 0.f);
         if (wave == 0) {
-            const int wbad = wave_cholesky_append(gram, N, S, K, best, Lf, LS, lane);
+            // new row of the factor, new last component of L^{-1} c0_S, then only the backward substitution
+            float lrow = 0.f;
+            const int wbad = wave_cholesky_append(gram, N, S, K, best, Lf, lane, &lrow);
+            const float dot = wave_sum(lane < K ? lrow * zreg : 0.f);
+            const float zk = (c0v[best] - dot) * Lf[K * SD_LS + SD_MAXK];
+            if (lane == K) zreg = zk;
             if (lane == 0) { S[K] = best; flag[best] = 1; if (wbad) misc[0] = 1; }
-            __builtin_amdgcn_wave_barrier();
-            const float x = wave_cholesky_solve(Lf, LS, K + 1, lane <= K ? c0v[lane < K ? sreg : best] : 0.f, lane);
+            const float x = wave_backward(Lf, K + 1, zreg, lane);
             if (lane <= K) xs[lane] = x;
         }
         __syncthreads();
@@ -269,7 +270,7 @@ void recover_inc_kernel(Plan p, RecoverArgs a, IncArgs q, IncLayout L) {
         }
         __syncthreads();
         if (wave == 0) {
-            const float d = wave_cholesky_solve(Lf, LS, k, lane < k ? gv[lane] : 0.f, lane);
+            const float d = wave_cholesky_solve(Lf, k, lane < k ? gv[lane] : 0.f, lane);
             if (lane < k) { xs[lane] += d; dl[lane] = d; }
         }
         __syncthreads();
