@@ -298,7 +298,7 @@ def time_loop(fn, iters, stream):
     return a.elapsed_time(b) / iters          # ms per iteration
 
 
-def extra_measurements(ctx, st, wl, stream):
+def extra_measurements(ctx, st, wl, stream, binding_mod):
     """Single-layer side figures: FFN at batch 1/8/64 on rotating layers, recovery and sketch per call."""
     c, hs = st.c, st.hs
     dev = "cuda:0"
@@ -345,6 +345,17 @@ def extra_measurements(ctx, st, wl, stream):
     fn = lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y)
     time_loop(fn, nl, stream)
     res["sketch_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
+    # joint prompt/model selection at the prompt shape: 8192 tokens, 2048 kept (sequential and coupled arm)
+    t = wl.CFG5_TOK
+    tok_op = binding_mod.make_op(t["ens"], 5, 1001, t["m_tok"], t["n_tok"])
+    y_tok = torch.randn((t["m_tok"],), generator=gen, device=dev)
+    Y_ch = torch.randn((t["n_tok"], c.m), generator=gen, device=dev)
+    fn = lambda i: ctx.cs_joint_select(tok_op, y_tok, t["k_tok"], st.ffn_op[i % nl], st.ffn_dict[i % nl], st.y[0], c.k)
+    time_loop(fn, 4, stream)
+    res["joint_select_us_per_call"] = time_loop(fn, 16, stream) * 1e3
+    fn = lambda i: ctx.cs_joint_select_coupled(tok_op, y_tok, t["k_tok"], st.ffn_op[i % nl], st.ffn_dict[i % nl], Y_ch, c.k)
+    time_loop(fn, 4, stream)
+    res["joint_select_coupled_us_per_call"] = time_loop(fn, 16, stream) * 1e3
     return res
 
 
@@ -421,7 +432,7 @@ def main():
         torch.cuda.synchronize()
         margin_pass = float((st.margin > 1e-3).float().mean())
         ffn_bytes = union_mean * 3 * c.b * c.d * 2
-        extra = None if args.no_extra else extra_measurements(ctx, st, wl, stream)
+        extra = None if args.no_extra else extra_measurements(ctx, st, wl, stream, binding)
         torch.cuda.synchronize()
 
     ms_per_step = wall * 1e3 / args.steps

@@ -226,6 +226,27 @@ cs_status cs_joint_select(cs_ctx* ctx, const cs_op* tok_op, const float* y_tok, 
                           int32_t* tokens, int32_t* support, float* resid_norm, float* margin);
 
 /*
+ * Coupled joint selection (Sec. 6: removing a token changes the latent measurements and
+ * therefore the recovered support; constraint z_t = A_t(r) Psi(r) alpha_t).  The smallest
+ * procedure with that coupling:
+ *   tokens  = as cs_joint_select;
+ *   ybar    = mean over the retained tokens t of Y_ch[t][:] (by linearity of the sketch,
+ *             the sketch of the retained tokens' mean usage);
+ *   support = cs_recover_support(ch_op, ch_dict, k_ch) applied to ybar.
+ *   y_tok:  float[tok_op->m]
+ *   Y_ch:   float[tok_op->n][ch_op->m], one channel sketch per prompt token
+ *   tokens: int32[k_tok] out, support: int32[k_ch] out
+ *   ybar:   float[ch_op->m] out or NULL
+ *   resid_norm, margin: float[1] out or NULL (of the channel recovery)
+ * The rows are summed in a fixed order (chunks of 64 retained tokens, then the chunks), so
+ * the result does not depend on timing.
+ */
+cs_status cs_joint_select_coupled(cs_ctx* ctx, const cs_op* tok_op, const float* y_tok, int k_tok,
+                                  const cs_op* ch_op, const cs_dict* ch_dict, const float* Y_ch, int k_ch,
+                                  int32_t* tokens, int32_t* support, float* ybar,
+                                  float* resid_norm, float* margin);
+
+/*
  * Token-selection operator of Sec. 6 (the retained prompt x~ = Pi(r) x): copy the rows
  * of x named by `tokens` into a dense matrix, in the order given.
  *   x: [n_rows][d] in, tokens: int32[k_tok] with entries in [0, n_rows), out: [k_tok][d] out,

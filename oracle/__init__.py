@@ -32,6 +32,9 @@ Pin status of each function (what ties it to something other than itself):
                         dense identity (Sec. 3), additivity over supports.
 * head_attn          -- full softmax attention, L=1, uniform-key closed forms.
 * top_k / joint      -- full sort, permutation invariance, k=n.
+* joint_select_coupled -- pooled sketch = sketch of the pooled usage (linearity), k_tok = n
+                        reduces to the mean over all tokens, planted prompts where the kept
+                        tokens share one support and the dropped ones do not.
 """
 from .philox import philox4x32_10
 from .operator import phi_entries, phi_matrix, GAUSS, RADEMACHER
@@ -41,10 +44,10 @@ from .iht import block_iht
 from .incremental import incremental_block_omp, support_drift
 from .ffn import block_ffn
 from .attn import head_attn
-from .joint import top_k_indices, token_proxy, joint_select
+from .joint import top_k_indices, token_proxy, joint_select, joint_select_coupled
 
 __all__ = [
     "philox4x32_10", "phi_entries", "phi_matrix", "GAUSS", "RADEMACHER",
     "sketch", "effective_matrix", "block_omp", "block_iht", "incremental_block_omp", "support_drift", "block_ffn", "head_attn",
-    "top_k_indices", "token_proxy", "joint_select",
+    "top_k_indices", "token_proxy", "joint_select", "joint_select_coupled",
 ]

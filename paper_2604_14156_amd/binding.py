@@ -17,7 +17,7 @@ CS_GAUSS, CS_RADEMACHER = 0, 1
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
-           "cs_recover_support", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_gather_rows")
+           "cs_recover_support", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows")
 
 
 class CsOp(ctypes.Structure):
@@ -56,6 +56,8 @@ def load_library(path=LIB_PATH):
     lib.cs_head_attn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
     lib.cs_joint_select.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
                                     vp, i32, vp, vp, vp, vp]
+    lib.cs_joint_select_coupled.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
+                                            vp, i32, vp, vp, vp, vp, vp]
     lib.cs_gather_rows.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp]
     for name in EXPORTS:
         if name not in ("cs_destroy", "cs_last_error"):
@@ -188,6 +190,18 @@ class Context:
         self._check(self.lib.cs_head_attn(self._h, _dtype_code(q), _ptr(q), _ptr(K), _ptr(V), B, H, L, dh,
                                           _ptr(heads), kh, _ptr(out)))
         return out
+
+    def cs_joint_select_coupled(self, tok_op, y_tok, k_tok, ch_op, ch_dict, Y_ch, k_ch):
+        dev = y_tok.device
+        tokens = torch.empty((k_tok,), dtype=torch.int32, device=dev)
+        support = torch.empty((k_ch,), dtype=torch.int32, device=dev)
+        ybar = torch.empty((ch_op.m,), dtype=torch.float32, device=dev)
+        resid = torch.empty((1,), dtype=torch.float32, device=dev)
+        margin = torch.empty((1,), dtype=torch.float32, device=dev)
+        self._check(self.lib.cs_joint_select_coupled(self._h, ctypes.byref(tok_op), _ptr(y_tok), k_tok,
+                                                     ctypes.byref(ch_op), ctypes.byref(ch_dict), _ptr(Y_ch), k_ch,
+                                                     _ptr(tokens), _ptr(support), _ptr(ybar), _ptr(resid), _ptr(margin)))
+        return tokens, support, ybar, resid, margin
 
     def cs_gather_rows(self, x, tokens, out=None):
         n_rows, d = x.shape

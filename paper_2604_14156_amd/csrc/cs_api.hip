@@ -400,6 +400,42 @@ cs_status cs_joint_select(cs_ctx* c, const cs_op* tok_op, const float* y_tok, in
                        "cs_joint_select: recovery");
 }
 
+cs_status cs_joint_select_coupled(cs_ctx* c, const cs_op* tok_op, const float* y_tok, int k_tok,
+                                  const cs_op* ch_op, const cs_dict* ch_dict, const float* Y_ch, int k_ch,
+                                  int32_t* tokens, int32_t* support, float* ybar,
+                                  float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    cs_status st;
+    if ((st = check_op(c, tok_op, "cs_joint_select_coupled(tokens)")) != CS_OK) return st;
+    if (k_tok < 1 || k_tok > tok_op->n)
+        return fail(c, CS_EINVAL, "cs_joint_select_coupled: k_tok=%d out of range [1, n=%d]", k_tok, tok_op->n);
+    if ((st = check_recover_args(c, ch_op, ch_dict, k_ch, "cs_joint_select_coupled(channels)")) != CS_OK) return st;
+    if (!y_tok || !Y_ch || !tokens || !support) return fail(c, CS_EINVAL, "cs_joint_select_coupled: NULL buffer");
+    if (!aligned16(y_tok) || !aligned16(Y_ch) || !aligned16(tokens) || !aligned16(support) || !aligned16(ybar) ||
+        !aligned16(resid_norm) || !aligned16(margin))
+        return fail(c, CS_EALIGN, "cs_joint_select_coupled: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    // scratch: token proxy | chunk sums of the pooled sketch | pooled sketch | recovery workspace
+    const size_t proxy_bytes = (((size_t)tok_op->n * sizeof(float)) + 255) & ~(size_t)255;
+    const size_t part_bytes = ((pool_rows_scratch_floats(ch_op->m, k_tok) * sizeof(float)) + 255) & ~(size_t)255;
+    const size_t ybar_bytes = (((size_t)ch_op->m * sizeof(float)) + 255) & ~(size_t)255;
+    const size_t used = proxy_bytes + part_bytes + ybar_bytes;
+    if (used > c->scratch_bytes)
+        return fail(c, CS_ENOMEM, "cs_joint_select_coupled: needs %zu bytes of scratch, context has %zu", used, c->scratch_bytes);
+    char* base = static_cast<char*>(c->scratch);
+    float* proxy = reinterpret_cast<float*>(base);
+    float* partial = reinterpret_cast<float*>(base + proxy_bytes);
+    float* pooled = reinterpret_cast<float*>(base + proxy_bytes + part_bytes);
+    hipError_t e = launch_backproject(make_desc(*tok_op), y_tok, proxy, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select_coupled: back-projection");
+    e = launch_topk(proxy, tok_op->n, k_tok, tokens, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select_coupled: top-k");
+    e = launch_pool_rows(Y_ch, tok_op->n, ch_op->m, tokens, k_tok, partial, pooled, ybar, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select_coupled: pooling");
+    return run_recover(c, ch_op, ch_dict, k_ch, pooled, 1, support, nullptr, resid_norm, margin, used,
+                       "cs_joint_select_coupled: recovery");
+}
+
 cs_status cs_gather_rows(cs_ctx* c, int dtype, const void* x, int n_rows, int d,
                          const int32_t* tokens, int k_tok, void* out) {
     if (!c) return CS_EINVAL;

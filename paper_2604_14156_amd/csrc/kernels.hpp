@@ -50,6 +50,12 @@ hipError_t launch_recover_inc(const Plan& p, const RecoverArgs& a, const IncArgs
 hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s);
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s);
 
+// ybar[m] (and `copy`, if not null) = mean over the listed rows of Y [n_rows][m];
+// partial: pool_rows_scratch_floats(m, k_tok) floats
+size_t pool_rows_scratch_floats(int m, int k_tok);
+hipError_t launch_pool_rows(const float* Y, int n_rows, int m, const int32_t* tokens, int k_tok, float* partial,
+                            float* ybar, float* copy, hipStream_t s);
+
 // out[i][:] = x[tokens[i]][:], rows of `row_bytes` bytes (a multiple of 16)
 hipError_t launch_gather_rows(const void* x, int n_rows, size_t row_bytes, const int32_t* tokens, int k_tok,
                               void* out, hipStream_t s);

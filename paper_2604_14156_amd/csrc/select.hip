@@ -138,6 +138,43 @@ hipError_t launch_gather_rows(const void* x, int n_rows, size_t row_bytes, const
     return hipGetLastError();
 }
 
+// Mean of the listed rows of Y [n_rows][m] in a fixed order: a workgroup sums a chunk of 64 listed
+// rows (thread = column), a second kernel adds the chunk sums in order and scales.
+constexpr int PL_CHUNK = 64;
+__global__ __launch_bounds__(256)
+void pool_rows_partial_kernel(const float* __restrict__ Y, int n_rows, int m, const int32_t* __restrict__ tokens,
+                              int k_tok, float* __restrict__ partial) {
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= m) return;
+    const int i0 = blockIdx.x * PL_CHUNK, i1 = min(k_tok, i0 + PL_CHUNK);
+    float acc = 0.f;
+    for (int i = i0; i < i1; ++i) {
+        const int t = tokens[i];
+        if (t >= 0 && t < n_rows) acc += Y[(size_t)t * m + c];
+    }
+    partial[(size_t)blockIdx.x * m + c] = acc;
+}
+__global__ __launch_bounds__(256)
+void pool_rows_final_kernel(const float* __restrict__ partial, int nchunks, int m, float scale, float* __restrict__ ybar,
+                            float* __restrict__ copy) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= m) return;
+    float acc = 0.f;
+    for (int q = 0; q < nchunks; ++q) acc += partial[(size_t)q * m + c];
+    ybar[c] = acc * scale;
+    if (copy) copy[c] = acc * scale;
+}
+
+size_t pool_rows_scratch_floats(int m, int k_tok) { return (size_t)((k_tok + PL_CHUNK - 1) / PL_CHUNK) * m; }
+
+hipError_t launch_pool_rows(const float* Y, int n_rows, int m, const int32_t* tokens, int k_tok, float* partial,
+                            float* ybar, float* copy, hipStream_t s) {
+    const int nchunks = (k_tok + PL_CHUNK - 1) / PL_CHUNK, cb = (m + 255) / 256;
+    hipLaunchKernelGGL(pool_rows_partial_kernel, dim3(nchunks, cb), dim3(256), 0, s, Y, n_rows, m, tokens, k_tok, partial);
+    hipLaunchKernelGGL(pool_rows_final_kernel, dim3(cb), dim3(256), 0, s, partial, nchunks, m, 1.0f / (float)k_tok, ybar, copy);
+    return hipGetLastError();
+}
+
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s) {
     hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(TK_THREADS), 0, s, scores, n, k, out);
     return hipGetLastError();

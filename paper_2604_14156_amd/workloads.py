@@ -184,6 +184,24 @@ def plant_saliency(rng, n_tok, p_active):
     return s.astype(np.float32), mask
 
 
+def plant_token_usage(rng, pi, S_star, mask, k, amp, bg):
+    """Per-token usage vectors of a prompt [n_tok, n]: salient tokens (mask true) all use the support
+    S_star with their own magnitudes, every other token uses k random units of its own."""
+    G, b = pi.shape
+    n_tok = mask.shape[0]
+    z = np.zeros((n_tok, G * b), dtype=np.float32)
+    for t in range(n_tok):
+        S = S_star if mask[t] else np.sort(rng.choice(G, size=k, replace=False))
+        a = np.ones(k) if amp == "unit" else rng.laplace(0.0, 1.0, size=k)
+        row = np.zeros(G * b)
+        for j, g in enumerate(S):
+            row[g * b:(g + 1) * b] = a[j] * pi[g]
+        if bg > 0.0:
+            row += bg * rng.standard_normal(G * b)
+        z[t] = row
+    return z
+
+
 def make_ffn_weights(rng, G, b, d, std, dtype):
     """Wg, Wu as [G, b, d]; Wd as [G, d, b]; values representable in `dtype`."""
     def draw(shape):

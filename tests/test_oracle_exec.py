@@ -132,3 +132,37 @@ def test_token_proxy_is_backprojection_and_joint_composes():
     assert np.allclose(p, p2)
     assert list(tokens) == list(oracle.top_k_indices(p, k_tok))
     assert list(rec["support"]) == [2, 5, 7]
+
+
+def test_coupled_joint_selection_pools_the_kept_tokens_only():
+    """Sec. 6: the retained tokens change the measurement the support is recovered from."""
+    rng = wl.rng_for(8)
+    n_tok, m_tok, k_tok = 160, 128, 40
+    c = wl.scaled(wl.CFG2, G=24, k=4, m=48, d=64)
+    sal, mask = wl.plant_saliency(rng, n_tok, 0.25)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    S_star = np.sort(rng.choice(c.G, size=c.k, replace=False))
+    # the salient tokens share S* with magnitudes of one sign, so that their mean does not cancel
+    z = wl.plant_token_usage(rng, np.abs(pi), S_star, mask, c.k, "unit", 0.0)
+    tok_op = (RADEMACHER, 81, 3, m_tok, n_tok)
+    y_tok = oracle.sketch(RADEMACHER, 81, 3, m_tok, sal)
+    psi_abs = np.abs(pi) / np.linalg.norm(pi, axis=1, keepdims=True)
+    M = oracle.effective_matrix(c.ens, 81, 0, c.m, c.n, c.G, c.b, 1, psi_abs.reshape(c.G, c.b, 1))
+    Y = oracle.sketch(c.ens, 81, 0, c.m, z)
+    tokens, ybar, rec, p = oracle.joint_select_coupled(tok_op, y_tok, k_tok, M, Y, c.G, 1, c.k, True)
+    assert list(tokens) == list(oracle.top_k_indices(p, k_tok))
+    # linearity: the pooled sketch is the sketch of the pooled usage
+    zbar = z[tokens].astype(np.float64).mean(axis=0)
+    assert np.allclose(ybar, oracle.sketch(c.ens, 81, 0, c.m, zbar), atol=1e-12)
+    assert np.allclose(ybar, Y[tokens].mean(axis=0), atol=1e-12)
+    # keeping every token pools the whole prompt
+    t_all, ybar_all, rec_all, _ = oracle.joint_select_coupled(tok_op, y_tok, n_tok, M, Y, c.G, 1, c.k, True)
+    assert list(t_all) == list(range(n_tok)) and np.allclose(ybar_all, Y.mean(axis=0), atol=1e-12)
+    # the kept tokens are mostly the salient ones, which share S*: the coupled recovery finds it ...
+    assert mask[tokens].mean() > 0.5          # base rate 0.25
+    assert list(rec["support"]) == list(S_star)
+    # ... and it is the token selection that does it: over tokens that do not share a support the
+    # pooled sketch has no common support to find
+    others = np.nonzero(~mask)[0][:k_tok]
+    rec_other = oracle.block_omp(M, Y[others].mean(axis=0), c.G, 1, c.k, True)
+    assert list(rec_other["support"]) != list(S_star)
