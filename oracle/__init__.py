@@ -12,6 +12,11 @@ Pin status of each function (what ties it to something other than itself):
                         rows); the (seed, stream, row, col) -> counter mapping
                         is this project's own convention: parity unpinned by
                         any external vector beyond the generator itself.
+* phi_matrix (SRHT)  -- equals R H D written out with a library Hadamard matrix, the row map is a
+                        bijection, Phi Phi^T = (n/m) I when n is a power of two, a textbook fast
+                        Walsh-Hadamard transform gives the same sketch, norm preservation in
+                        expectation; the (seed, stream) -> signs and rows mapping is this
+                        project's own convention (parity unpinned beyond the generator).
 * sketch             -- equals an explicit dense matrix-vector product;
                         linearity; norm preservation in expectation.
 * block_omp          -- brute force over all supports, closed forms for
@@ -37,7 +42,7 @@ Pin status of each function (what ties it to something other than itself):
                         tokens share one support and the dropped ones do not.
 """
 from .philox import philox4x32_10
-from .operator import phi_entries, phi_matrix, GAUSS, RADEMACHER
+from .operator import phi_entries, phi_matrix, srht_rows, srht_order, GAUSS, RADEMACHER, SRHT
 from .sketch import sketch
 from .recover import effective_matrix, block_omp
 from .iht import block_iht
@@ -47,7 +52,7 @@ from .attn import head_attn
 from .joint import top_k_indices, token_proxy, joint_select, joint_select_coupled
 
 __all__ = [
-    "philox4x32_10", "phi_entries", "phi_matrix", "GAUSS", "RADEMACHER",
+    "philox4x32_10", "phi_entries", "phi_matrix", "srht_rows", "srht_order", "GAUSS", "RADEMACHER", "SRHT",
     "sketch", "effective_matrix", "block_omp", "block_iht", "incremental_block_omp", "support_drift", "block_ffn", "head_attn",
     "top_k_indices", "token_proxy", "joint_select", "joint_select_coupled",
 ]
