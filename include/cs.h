@@ -41,7 +41,7 @@ typedef enum {
     CS_EHIP = -5        /* a HIP runtime call failed; text in cs_last_error */
 } cs_status;
 
-typedef enum { CS_GAUSS = 0, CS_RADEMACHER = 1 } cs_ensemble;
+typedef enum { CS_GAUSS = 0, CS_RADEMACHER = 1, CS_SRHT = 2 } cs_ensemble;
 typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
 
 /*
@@ -54,6 +54,14 @@ typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
  *               bit 0 -> +1, bit 1 -> -1.
  *   Gaussian:   cpc = 4; p = (c % 4) / 2; u1 = (w[2p]+1)/2^32, u2 = (w[2p+1]+1)/2^32;
  *               even columns sqrt(-2 ln u1) cos(2 pi u2), odd columns ... sin(2 pi u2).
+ *   Subsampled randomised Hadamard (CS_SRHT; Sec. 8 names it for implementation efficiency):
+ *               Phi = (1/sqrt(m)) R H D on the first n columns, H the Walsh-Hadamard matrix of
+ *               order n' = 2^b, the smallest power of two >= max(n, 2), H[r][c] =
+ *               (-1)^popcount(r & c); d_c = Rademacher bit of column c under counter
+ *               (c / 128, 0, stream_id, 2); measurement i reads row r_i = perm(i), with w the
+ *               output of counter (0, 1, stream_id, 2): x = (i (w0|1) + w1) mod n';
+ *               x ^= x >> ceil(b/2); x = (x (w2|1) + w3) mod n'; x ^= x >> ceil(b/2).
+ *               Needs m <= n'; cs_sketch evaluates it by a fast transform and needs n' <= 32768.
  *   Phi[row][col] = entry / sqrt(m).
  * Rows do not depend on m, so a change of the measurement budget (Sec. 8.1) only
  * adds or removes rows and rescales.

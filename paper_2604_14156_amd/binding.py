@@ -13,7 +13,7 @@ import torch
 from .buildlib import LIB_PATH
 
 CS_OK, CS_EINVAL, CS_EALIGN, CS_EILLPOSED, CS_ENOMEM, CS_EHIP = 0, -1, -2, -3, -4, -5
-CS_GAUSS, CS_RADEMACHER = 0, 1
+CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",

@@ -32,14 +32,40 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
 struct OpDesc {
     uint32_t k0, k1;      // seed halves
     uint32_t stream;
-    int ens;              // 0 Gaussian, 1 Rademacher
+    int ens;              // 0 Gaussian, 1 Rademacher, 2 subsampled randomised Hadamard
     int m, n;
     float scale;          // 1/sqrt(m)
+    int nbits;            // Hadamard ensemble: the transform has 2^nbits >= max(n, 2) points
 };
 
 // 128 sign bits of row `row`, column group `cg` (columns 128*cg .. 128*cg+127).
 __device__ __forceinline__ u32x4 rademacher_bits(const OpDesc& op, uint32_t row, uint32_t cg) {
     return philox4x32_10(cg, row, op.stream, 1u, op.k0, op.k1);
+}
+
+// Subsampled randomised Hadamard ensemble: entry (i, c) = d_c * (-1)^popcount(r_i & c), with the sign
+// d_c = Rademacher bit of column c under counter (c / 128, 0, stream, 2) and the row map
+// r_i = perm(i), a bijection of [0, 2^nbits) keyed by the Philox call with counter (0, 1, stream, 2):
+// two rounds of (multiply by an odd word, add a word, fold the upper half onto the lower).
+struct SrhtRows { uint32_t a1, c1, a2, c2, mask; int fold; };
+__device__ __forceinline__ SrhtRows srht_rows_key(const OpDesc& op) {
+    const u32x4 w = philox4x32_10(0u, 1u, op.stream, 2u, op.k0, op.k1);
+    SrhtRows r;
+    r.a1 = w.w[0] | 1u; r.c1 = w.w[1]; r.a2 = w.w[2] | 1u; r.c2 = w.w[3];
+    r.mask = op.nbits >= 32 ? 0xFFFFFFFFu : ((1u << op.nbits) - 1u);
+    r.fold = (op.nbits + 1) >> 1;
+    return r;
+}
+__device__ __forceinline__ uint32_t srht_row(const SrhtRows& k, uint32_t i) {
+    uint32_t x = (i * k.a1 + k.c1) & k.mask;
+    x ^= x >> k.fold;
+    x = (x * k.a2 + k.c2) & k.mask;
+    x ^= x >> k.fold;
+    return x;
+}
+// 128 sign bits d_c of column group `cg`
+__device__ __forceinline__ u32x4 srht_sign_bits(const OpDesc& op, uint32_t cg) {
+    return philox4x32_10(cg, 0u, op.stream, 2u, op.k0, op.k1);
 }
 
 // ln(u) for u = (w+1)/2^32 in (0,1], accurate also when u is close to 1, where a

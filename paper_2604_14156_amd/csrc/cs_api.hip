@@ -63,13 +63,21 @@ OpDesc make_desc(const cs_op& op) {
     d.m = op.m;
     d.n = op.n;
     d.scale = (float)(1.0 / std::sqrt((double)op.m));
+    d.nbits = 1;
+    while ((1ll << d.nbits) < (long long)op.n) ++d.nbits;
     return d;
 }
 
 cs_status check_op(cs_ctx* c, const cs_op* op, const char* who) {
     if (!op) return fail(c, CS_EINVAL, "%s: operator is NULL", who);
-    if (op->ens != CS_GAUSS && op->ens != CS_RADEMACHER) return fail(c, CS_EINVAL, "%s: unknown ensemble %d", who, op->ens);
+    if (op->ens != CS_GAUSS && op->ens != CS_RADEMACHER && op->ens != CS_SRHT)
+        return fail(c, CS_EINVAL, "%s: unknown ensemble %d", who, op->ens);
     if (op->m < 1 || op->n < 1) return fail(c, CS_EINVAL, "%s: operator needs m >= 1 and n >= 1 (m=%d n=%d)", who, op->m, op->n);
+    if (op->ens == CS_SRHT) {
+        long long npad = 2;
+        while (npad < op->n) npad *= 2;
+        if (op->m > npad) return fail(c, CS_EINVAL, "%s: the Hadamard ensemble has at most %lld rows for n=%d (m=%d)", who, npad, op->n, op->m);
+    }
     return CS_OK;
 }
 
@@ -242,6 +250,8 @@ cs_status cs_sketch(cs_ctx* c, const cs_op* op, const float* z, int B, float* y)
     if (!z || !y) return fail(c, CS_EINVAL, "cs_sketch: NULL buffer");
     if (!aligned16(z) || !aligned16(y)) return fail(c, CS_EALIGN, "cs_sketch: buffer not 16-byte aligned");
     if ((st = bind_device(c)) != CS_OK) return st;
+    if (op->ens == CS_SRHT && !sketch_srht_supported(make_desc(*op)))
+        return fail(c, CS_EINVAL, "cs_sketch: the Hadamard ensemble is limited to n <= 32768 (n=%d)", op->n);
     hipError_t e = launch_sketch(make_desc(*op), z, B, y, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_sketch");
     return CS_OK;

@@ -9,7 +9,13 @@ namespace csk {
 
 constexpr int CS_MAX_RB_WEIGHTED = 16;
 
-__device__ __forceinline__ float phi_entry_unscaled(const OpDesc& op, uint32_t row, uint32_t col) {
+// `hrow`: the Hadamard row of measurement `row` (Hadamard ensemble only)
+__device__ __forceinline__ float phi_entry_unscaled(const OpDesc& op, uint32_t row, uint32_t hrow, uint32_t col) {
+    if (op.ens == 2) {
+        const u32x4 bits = srht_sign_bits(op, col >> 7);
+        const uint32_t d = (bits.w[(col & 127u) >> 5] >> (col & 31u)) & 1u;
+        return ((__popc(hrow & col) ^ d) & 1u) ? -1.f : 1.f;
+    }
     if (op.ens == 1) {
         const u32x4 bits = rademacher_bits(op, row, col >> 7);
         const uint32_t bit = (bits.w[(col & 127u) >> 5] >> (col & 31u)) & 1u;
@@ -26,15 +32,16 @@ __global__ void build_atoms_kernel(Plan p, const float* __restrict__ psi) {
     const int g = blockIdx.y;
     if (i >= p.op.m) return;
     const int m = p.op.m;
+    const uint32_t hrow = p.op.ens == 2 ? srht_row(srht_rows_key(p.op), (uint32_t)i) : 0u;
     if (psi == nullptr) {
         for (int t = 0; t < p.b; ++t)
-            p.Mt[(size_t)(g * p.b + t) * m + i] = phi_entry_unscaled(p.op, i, g * p.b + t) * p.op.scale;
+            p.Mt[(size_t)(g * p.b + t) * m + i] = phi_entry_unscaled(p.op, i, hrow, g * p.b + t) * p.op.scale;
         return;
     }
     for (int j0 = 0; j0 < p.rb; j0 += 4) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         for (int t = 0; t < p.b; ++t) {
-            const double e = (double)phi_entry_unscaled(p.op, i, g * p.b + t);
+            const double e = (double)phi_entry_unscaled(p.op, i, hrow, g * p.b + t);
             for (int j = 0; j < 4; ++j)
                 if (j0 + j < p.rb) acc[j] += e * (double)psi[((size_t)g * p.b + t) * p.rb + j0 + j];
         }

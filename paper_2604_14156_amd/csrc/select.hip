@@ -12,7 +12,18 @@ __global__ void backproject_kernel(OpDesc op, const float* __restrict__ y, float
     for (int i = threadIdx.x; i < op.m; i += blockDim.x) ys[i] = y[i];
     __syncthreads();
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (op.ens == 1) {
+    if (op.ens == 2) {                                   // Hadamard ensemble: one thread per column
+        if (t >= op.n) return;
+        const SrhtRows key = srht_rows_key(op);
+        const u32x4 b = srht_sign_bits(op, (uint32_t)t >> 7);
+        const uint32_t d = (b.w[((uint32_t)t & 127u) >> 5] >> ((uint32_t)t & 31u)) & 1u;
+        float acc = 0.f;
+        for (int i = 0; i < op.m; ++i) {
+            const uint32_t sgn = ((__popc(srht_row(key, (uint32_t)i) & (uint32_t)t) ^ d) & 1u) << 31;
+            acc += __uint_as_float(__float_as_uint(ys[i]) ^ sgn);
+        }
+        p[t] = acc * op.scale;
+    } else if (op.ens == 1) {
         if (t >= op.n) return;
         const uint32_t cg = (uint32_t)t >> 7, word = ((uint32_t)t & 127u) >> 5, bit = (uint32_t)t & 31u;
         float acc = 0.f;
@@ -37,7 +48,7 @@ __global__ void backproject_kernel(OpDesc op, const float* __restrict__ y, float
 }
 
 hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s) {
-    const int items = op.ens == 1 ? op.n : (op.n + 3) / 4;
+    const int items = op.ens != 0 ? op.n : (op.n + 3) / 4;
     const int block = 64;                    // many small workgroups: the row loop is long
     hipLaunchKernelGGL(backproject_kernel, dim3((items + block - 1) / block), dim3(block),
                        (size_t)op.m * sizeof(float), s, op, y, p);

@@ -11,6 +11,12 @@
 //
 // Gaussian ensemble.  One wavefront per row and token chunk; a lane draws four
 // normals per Philox call (Box-Muller) and applies them to one float4 of z.
+//
+// Subsampled randomised Hadamard ensemble.  y = (1/sqrt(m)) (H (d * z))[r_i]: one workgroup per
+// token holds the signed, zero-padded vector in LDS and runs the fast Walsh-Hadamard transform
+// on it, four butterfly levels per pass with the sixteen values of a group in registers (the
+// levels of the transform commute, so the passes simply walk over the index bits), then reads
+// the m selected entries.  n' log2 n' additions per token instead of m n.
 #include "kernels.hpp"
 
 namespace csk {
@@ -117,9 +123,85 @@ void sketch_gauss_kernel(OpDesc op, const float* __restrict__ z, int B, float* _
     }
 }
 
+// butterfly levels of the index bits [sh, sh + R) on the n' = 2^nbits values in LDS
+template <int R>
+__device__ __forceinline__ void wht_pass(float* x, int nbits, int sh) {
+    const int ngroups = 1 << (nbits - R);
+    for (int g = threadIdx.x; g < ngroups; g += blockDim.x) {
+        const int base = ((g >> sh) << (sh + R)) | (g & ((1 << sh) - 1));
+        float v[1 << R];
+#pragma unroll
+        for (int e = 0; e < (1 << R); ++e) v[e] = x[base + (e << sh)];
+#pragma unroll
+        for (int lv = 0; lv < R; ++lv)
+#pragma unroll
+            for (int e = 0; e < (1 << R); ++e)
+                if (!(e & (1 << lv))) {
+                    const float a = v[e], b = v[e | (1 << lv)];
+                    v[e] = a + b;
+                    v[e | (1 << lv)] = a - b;
+                }
+#pragma unroll
+        for (int e = 0; e < (1 << R); ++e) x[base + (e << sh)] = v[e];
+    }
+}
+
+__global__ __launch_bounds__(1024)
+void sketch_srht_kernel(OpDesc op, const float* __restrict__ z, float* __restrict__ y) {
+    extern __shared__ float xs[];                       // [2^nbits] values, then [2^nbits / 32] sign words
+    const int npad = 1 << op.nbits;
+    uint32_t* sg = reinterpret_cast<uint32_t*>(xs + npad);
+    const int tok = blockIdx.x, tid = threadIdx.x, NT = blockDim.x;
+    const int ngroups = (op.n + 127) >> 7;              // one Philox call signs 128 columns
+    for (int cg = tid; cg < ngroups; cg += NT) {
+        const u32x4 b = srht_sign_bits(op, (uint32_t)cg);
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            if (cg * 4 + w < ((npad + 31) >> 5)) sg[cg * 4 + w] = b.w[w];
+    }
+    __syncthreads();
+    const float* zt = z + (size_t)tok * op.n;
+    for (int c = tid; c < npad; c += NT) {
+        float v = 0.f;
+        if (c < op.n) {
+            const uint32_t sgn = ((sg[c >> 5] >> (c & 31)) & 1u) << 31;
+            v = __uint_as_float(__float_as_uint(zt[c]) ^ sgn);
+        }
+        xs[c] = v;
+    }
+    __syncthreads();
+    int sh = 0;
+    for (; sh + 4 <= op.nbits; sh += 4) { wht_pass<4>(xs, op.nbits, sh); __syncthreads(); }
+    const int rest = op.nbits - sh;
+    if (rest == 3) wht_pass<3>(xs, op.nbits, sh);
+    else if (rest == 2) wht_pass<2>(xs, op.nbits, sh);
+    else if (rest == 1) wht_pass<1>(xs, op.nbits, sh);
+    __syncthreads();
+    const SrhtRows key = srht_rows_key(op);
+    for (int i = tid; i < op.m; i += NT) y[(size_t)tok * op.m + i] = xs[srht_row(key, (uint32_t)i)] * op.scale;
+}
+
+constexpr int SRHT_MAX_BITS = 15;                       // 128 KB of LDS for the values
+
+bool sketch_srht_supported(const OpDesc& op) { return op.nbits <= SRHT_MAX_BITS; }
+
 hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s) {
     if (B <= 0) return hipSuccess;
-    if (op.ens == 1) {
+    if (op.ens == 2) {
+        if (!sketch_srht_supported(op)) return hipErrorInvalidValue;
+        const int npad = 1 << op.nbits;
+        const size_t bytes = (size_t)npad * 4 + (size_t)(((npad + 31) >> 5) + 4) * 4;
+        static size_t allowed = 0;
+        if (bytes > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_srht_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e != hipSuccess) return e;
+            allowed = bytes;
+        }
+        int nthreads = npad / 16;
+        nthreads = nthreads < 64 ? 64 : (nthreads > 1024 ? 1024 : nthreads);
+        hipLaunchKernelGGL(sketch_srht_kernel, dim3(B), dim3(nthreads), bytes, s, op, z, y);
+    } else if (op.ens == 1) {
         dim3 grid((op.m + SR_RR - 1) / SR_RR, (B + SR_TB - 1) / SR_TB);
         hipLaunchKernelGGL(sketch_rademacher_kernel, grid, dim3(SR_WAVES * 64), 0, s, op, z, B, y);
     } else {

@@ -23,6 +23,7 @@ import numpy as np
 
 GAUSS = 0
 RADEMACHER = 1
+SRHT = 2
 
 
 # ----------------------------------------------------------------------------

@@ -1,0 +1,96 @@
+"""GPU parity: subsampled randomised Hadamard ensemble (fast-transform sketch, plan entries,
+back-projection) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_14156_amd import binding, workloads as wl
+from gpu_util import dev_f32, host, rel_err
+from test_gpu_sketch_recover import _check_recovery
+
+pytestmark = pytest.mark.gpu
+SEED = 0x0123456789ABCDEF
+
+
+@pytest.mark.parametrize("m,n,B", [(16, 32, 3), (3, 5, 2), (40, 300, 5), (64, 64, 1), (1, 2, 1), (256, 11008, 4),
+                                   (512, 16384, 2), (2000, 32768, 1), (128, 17000, 2), (15, 16, 17)])
+def test_srht_sketch_matches_oracle(cs, m, n, B):
+    rng = wl.rng_for(7 * m + n + B)
+    z = rng.standard_normal((B, n)).astype(np.float32)
+    op = binding.make_op(wl.SRHT, SEED, 5, m, n)
+    y = host(cs.cs_sketch(op, dev_f32(z)))
+    want = oracle.sketch(oracle.SRHT, SEED, 5, m, z)
+    assert y.shape == (B, m)
+    for t in range(B):
+        assert rel_err(y[t], want[t]) <= 1e-5
+
+
+def test_srht_limits_and_errors(cs):
+    with pytest.raises(binding.CsError) as e:                  # more rows than the transform has
+        cs.cs_sketch(binding.make_op(wl.SRHT, 1, 0, 65, 64), dev_f32(np.zeros((1, 64))))
+    assert e.value.status == binding.CS_EINVAL
+    with pytest.raises(binding.CsError) as e:                  # the padded vector must fit in LDS
+        cs.cs_sketch(binding.make_op(wl.SRHT, 1, 0, 8, 40000), dev_f32(np.zeros((1, 40000))))
+    assert e.value.status == binding.CS_EINVAL
+    z = torch.empty((0, 64), dtype=torch.float32, device="cuda:0")
+    assert cs.cs_sketch(binding.make_op(wl.SRHT, 1, 0, 8, 64), z).shape == (0, 8)
+
+
+def test_recovery_through_a_hadamard_operator_decode_shape(cs):
+    """The plan evaluates the operator entry by entry; the sketch comes from the fast transform."""
+    c = wl.CFG2
+    seed = 7100
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 4, c.amp, c.bg)
+    op = binding.make_op(wl.SRHT, seed, 2, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(oracle.SRHT, seed, 2, c.m, c.n, c.G, c.b, 1, psi)
+    Y = host(cs.cs_sketch(op, dev_f32(z))).astype(np.float32)
+    want = oracle.sketch(oracle.SRHT, seed, 2, c.m, z)
+    for t in range(4):
+        assert rel_err(Y[t], want[t]) <= 1e-5
+    assert _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True) >= 1
+
+
+def test_recovery_identity_dictionary_and_heads(cs):
+    hs = wl.CFG3_HEADS
+    seed = 7200
+    rng = wl.rng_for(seed)
+    u, S = wl.plant_head_usage(rng, hs, 8)
+    op = binding.make_op(wl.SRHT, seed, 3, hs.m, hs.H)
+    dct = binding.make_dict(None, hs.H, 1, 1)
+    M = oracle.effective_matrix(oracle.SRHT, seed, 3, hs.m, hs.H, hs.H, 1, 1, None)
+    Y = oracle.sketch(oracle.SRHT, seed, 3, hs.m, u).astype(np.float32)
+    assert _check_recovery(cs, op, dct, None, M, Y, hs.H, 1, hs.kh, False) >= 2
+
+
+def test_joint_selection_with_a_hadamard_token_operator(cs):
+    seed = 7300
+    rng = wl.rng_for(seed)
+    n_tok, m_tok, k_tok = 1000, 256, 250
+    c = wl.scaled(wl.CFG2, G=24, k=4, m=48, d=64)
+    sal, mask = wl.plant_saliency(rng, n_tok, 0.25)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 1, c.amp, c.bg)
+    tok_op = binding.make_op(wl.SRHT, seed, 9, m_tok, n_tok)
+    ch_op = binding.make_op(wl.SRHT, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    y_tok = oracle.sketch(oracle.SRHT, seed, 9, m_tok, sal).astype(np.float32)
+    y_ch = oracle.sketch(oracle.SRHT, seed, 0, c.m, z[0]).astype(np.float32)
+    tokens, support, resid, margin = cs.cs_joint_select(tok_op, dev_f32(y_tok), k_tok, ch_op, dct, dev_f32(y_ch), c.k)
+    tokens, support = host(tokens), host(support)
+    M = oracle.effective_matrix(oracle.SRHT, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    otok, rec, p = oracle.joint_select((oracle.SRHT, seed, 9, m_tok, n_tok), y_tok, k_tok, M, y_ch, c.G, 1, c.k, True)
+    srt = np.sort(p)[::-1]
+    tol = 1e-5 * np.linalg.norm(y_tok)
+    cut = 0.5 * (srt[k_tok - 1] + srt[k_tok])
+    got = set(tokens.tolist())
+    assert set(np.nonzero(p > cut + tol)[0].tolist()) <= got and not (got & set(np.nonzero(p < cut - tol)[0].tolist()))
+    if srt[k_tok - 1] - srt[k_tok] > 2 * tol:
+        assert list(tokens) == list(otok)
+    if rec["margin"] > 1e-3:
+        assert list(support) == list(rec["support"])
