@@ -345,6 +345,23 @@ def extra_measurements(ctx, st, wl, stream, binding_mod):
     fn = lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y)
     time_loop(fn, nl, stream)
     res["sketch_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3
+    # measurement cost against the budget m (the controller of Sec. 8.1 moves m between steps): dense
+    # Rademacher sketch and the fast-transform Hadamard sketch, and the controller's entropy sensor
+    curve = {}
+    for m_t in (64, 128, 256, 512):
+        yb = torch.empty((B, m_t), device=dev)
+        for name, ens in (("rademacher", wl.RADEMACHER), ("hadamard", wl.SRHT)):
+            op_t = binding_mod.make_op(ens, 5, 2001, m_t, c.n)
+            fn = lambda i: ctx.cs_sketch(op_t, st.z[0][i % nl], yb)
+            time_loop(fn, nl, stream)
+            curve["%s_m%d" % (name, m_t)] = time_loop(fn, 2 * nl, stream) * 1e3
+    res["sketch_us_per_call_B%d_vs_m" % B] = curve
+    logits = torch.randn((B, 128256), generator=gen, device=dev)
+    ent = torch.empty((B,), device=dev)
+    fn = lambda i: ctx.cs_softmax_entropy(logits, ent)
+    time_loop(fn, 4, stream)
+    us = time_loop(fn, 32, stream) * 1e3
+    res["softmax_entropy_B%d_V128256" % B] = {"us": us, "GBs": B * 128256 * 4 / (us * 1e-6) / 1e9}
     # joint prompt/model selection at the prompt shape: 8192 tokens, 2048 kept (sequential and coupled arm)
     t = wl.CFG5_TOK
     tok_op = binding_mod.make_op(t["ens"], 5, 1001, t["m_tok"], t["n_tok"])

@@ -255,6 +255,19 @@ cs_status cs_joint_select_coupled(cs_ctx* ctx, const cs_op* tok_op, const float*
                                   float* resid_norm, float* margin);
 
 /*
+ * Uncertainty-driven measurement budget (Sec. 8.1).  cs_softmax_entropy returns, for every
+ * row of logits, the entropy in nats of the predictive distribution p = softmax(logits),
+ *   H(p) = - sum_v p(v) ln p(v);
+ * cs_uds_budget is the controller itself (host arithmetic, no device work),
+ *   m_t = clip( floor( m_base (1 + gamma H) ), m_min, m_max ),
+ * whose result is the `m` of the next step's cs_op (rows of Phi are nested in m).
+ *   logits: device float[B][V], entropy: device float[B] out; V >= 1.
+ * cs_uds_budget returns the budget, or -1 if m_min > m_max, m_min < 1 or an argument is not finite.
+ */
+cs_status cs_softmax_entropy(cs_ctx* ctx, const float* logits, int B, int V, float* entropy);
+int32_t cs_uds_budget(int32_t m_base, float gamma, float entropy, int32_t m_min, int32_t m_max);
+
+/*
  * Token-selection operator of Sec. 6 (the retained prompt x~ = Pi(r) x): copy the rows
  * of x named by `tokens` into a dense matrix, in the order given.
  *   x: [n_rows][d] in, tokens: int32[k_tok] with entries in [0, n_rows), out: [k_tok][d] out,

@@ -36,6 +36,8 @@ Pin status of each function (what ties it to something other than itself):
 * block_ffn          -- dense SwiGLU via an independent formulation, masked
                         dense identity (Sec. 3), additivity over supports.
 * head_attn          -- full softmax attention, L=1, uniform-key closed forms.
+* softmax_entropy / uds_budget -- uniform, two-point and peaked distributions in closed form,
+                        a library routine for the entropy, hand-computed budgets and clipping.
 * top_k / joint      -- full sort, permutation invariance, k=n.
 * joint_select_coupled -- pooled sketch = sketch of the pooled usage (linearity), k_tok = n
                         reduces to the mean over all tokens, planted prompts where the kept
@@ -49,10 +51,11 @@ from .iht import block_iht
 from .incremental import incremental_block_omp, support_drift
 from .ffn import block_ffn
 from .attn import head_attn
+from .controller import softmax_entropy, uds_budget
 from .joint import top_k_indices, token_proxy, joint_select, joint_select_coupled
 
 __all__ = [
     "philox4x32_10", "phi_entries", "phi_matrix", "srht_rows", "srht_order", "GAUSS", "RADEMACHER", "SRHT",
     "sketch", "effective_matrix", "block_omp", "block_iht", "incremental_block_omp", "support_drift", "block_ffn", "head_attn",
-    "top_k_indices", "token_proxy", "joint_select", "joint_select_coupled",
+    "softmax_entropy", "uds_budget", "top_k_indices", "token_proxy", "joint_select", "joint_select_coupled",
 ]

@@ -17,7 +17,8 @@ CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
-           "cs_recover_support", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows")
+           "cs_recover_support", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
+           "cs_softmax_entropy", "cs_uds_budget")
 
 
 class CsOp(ctypes.Structure):
@@ -58,10 +59,12 @@ def load_library(path=LIB_PATH):
                                     vp, i32, vp, vp, vp, vp]
     lib.cs_joint_select_coupled.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
                                             vp, i32, vp, vp, vp, vp, vp]
+    lib.cs_softmax_entropy.argtypes = [vp, vp, i32, i32, vp]
+    lib.cs_uds_budget.argtypes = [ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_int32]
     lib.cs_gather_rows.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp]
     for name in EXPORTS:
         if name not in ("cs_destroy", "cs_last_error"):
-            getattr(lib, name).restype = ctypes.c_int
+            getattr(lib, name).restype = ctypes.c_int       # cs_status, or the budget of cs_uds_budget
     return lib
 
 
@@ -202,6 +205,16 @@ class Context:
                                                      ctypes.byref(ch_op), ctypes.byref(ch_dict), _ptr(Y_ch), k_ch,
                                                      _ptr(tokens), _ptr(support), _ptr(ybar), _ptr(resid), _ptr(margin)))
         return tokens, support, ybar, resid, margin
+
+    def cs_softmax_entropy(self, logits, entropy=None):
+        B, V = logits.shape
+        if entropy is None:
+            entropy = torch.empty((B,), dtype=torch.float32, device=logits.device)
+        self._check(self.lib.cs_softmax_entropy(self._h, _ptr(logits), B, V, _ptr(entropy)))
+        return entropy
+
+    def cs_uds_budget(self, m_base, gamma, entropy, m_min, m_max):
+        return int(self.lib.cs_uds_budget(int(m_base), float(gamma), float(entropy), int(m_min), int(m_max)))
 
     def cs_gather_rows(self, x, tokens, out=None):
         n_rows, d = x.shape

@@ -446,6 +446,28 @@ cs_status cs_joint_select_coupled(cs_ctx* c, const cs_op* tok_op, const float* y
                        "cs_joint_select_coupled: recovery");
 }
 
+cs_status cs_softmax_entropy(cs_ctx* c, const float* logits, int B, int V, float* entropy) {
+    if (!c) return CS_EINVAL;
+    if (B < 0 || B > 65535 * 32) return fail(c, CS_EINVAL, "cs_softmax_entropy: B out of range");
+    if (V < 1) return fail(c, CS_EINVAL, "cs_softmax_entropy: V < 1");
+    if (B == 0) return CS_OK;
+    if (!logits || !entropy) return fail(c, CS_EINVAL, "cs_softmax_entropy: NULL buffer");
+    if (!aligned16(logits) || !aligned16(entropy)) return fail(c, CS_EALIGN, "cs_softmax_entropy: buffer not 16-byte aligned");
+    cs_status st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    hipError_t e = launch_softmax_entropy(logits, B, V, entropy, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_softmax_entropy");
+    return CS_OK;
+}
+
+int32_t cs_uds_budget(int32_t m_base, float gamma, float entropy, int32_t m_min, int32_t m_max) {
+    if (m_min > m_max || m_min < 1 || !std::isfinite(gamma) || !std::isfinite(entropy)) return -1;
+    const double v = std::floor((double)m_base * (1.0 + (double)gamma * (double)entropy));
+    if (v < (double)m_min) return m_min;
+    if (v > (double)m_max) return m_max;
+    return (int32_t)v;
+}
+
 cs_status cs_gather_rows(cs_ctx* c, int dtype, const void* x, int n_rows, int d,
                          const int32_t* tokens, int k_tok, void* out) {
     if (!c) return CS_EINVAL;

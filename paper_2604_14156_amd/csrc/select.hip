@@ -186,6 +186,46 @@ hipError_t launch_pool_rows(const float* Y, int n_rows, int m, const int32_t* to
     return hipGetLastError();
 }
 
+// Entropy of softmax(logits) per row (paper Sec. 8.1).  One workgroup per row; with mx the row maximum,
+// S = sum exp(x - mx) and T = sum (x - mx) exp(x - mx), the entropy is ln S - T / S.
+constexpr int EN_THREADS = 1024;
+__global__ __launch_bounds__(EN_THREADS)
+void softmax_entropy_kernel(const float* __restrict__ logits, int V, float* __restrict__ entropy) {
+    __shared__ float red[2][EN_THREADS / 64];
+    const float* x = logits + (size_t)blockIdx.x * V;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float mx = -INFINITY;
+    for (int i = tid; i < V; i += EN_THREADS) mx = fmaxf(mx, x[i]);
+    mx = wave_max(mx);
+    if (lane == 0) red[0][wave] = mx;
+    __syncthreads();
+    mx = red[0][0];
+    for (int w = 1; w < EN_THREADS / 64; ++w) mx = fmaxf(mx, red[0][w]);
+    __syncthreads();
+    float S = 0.f, T = 0.f;
+    for (int i = tid; i < V; i += EN_THREADS) {
+        const float d = x[i] - mx;
+        const float e = __expf(d);
+        S += e;
+        if (e > 0.f) T += d * e;                       // exp underflow: the term is 0, not (-inf) * 0
+    }
+    S = wave_sum(S);
+    T = wave_sum(T);
+    if (lane == 0) { red[0][wave] = S; red[1][wave] = T; }
+    __syncthreads();
+    if (tid == 0) {
+        float s = 0.f, t = 0.f;
+        for (int w = 0; w < EN_THREADS / 64; ++w) { s += red[0][w]; t += red[1][w]; }
+        entropy[blockIdx.x] = logf(s) - t / s;
+    }
+}
+
+hipError_t launch_softmax_entropy(const float* logits, int B, int V, float* entropy, hipStream_t s) {
+    if (B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(softmax_entropy_kernel, dim3(B), dim3(EN_THREADS), 0, s, logits, V, entropy);
+    return hipGetLastError();
+}
+
 hipError_t launch_topk(const float* scores, int n, int k, int32_t* out, hipStream_t s) {
     hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(TK_THREADS), 0, s, scores, n, k, out);
     return hipGetLastError();
