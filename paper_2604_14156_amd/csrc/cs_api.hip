@@ -448,14 +448,17 @@ cs_status cs_joint_select_coupled(cs_ctx* c, const cs_op* tok_op, const float* y
 
 cs_status cs_softmax_entropy(cs_ctx* c, const float* logits, int B, int V, float* entropy) {
     if (!c) return CS_EINVAL;
-    if (B < 0 || B > 65535 * 32) return fail(c, CS_EINVAL, "cs_softmax_entropy: B out of range");
+    if (B < 0 || B > 65535) return fail(c, CS_EINVAL, "cs_softmax_entropy: B out of range [0, 65535]");
     if (V < 1) return fail(c, CS_EINVAL, "cs_softmax_entropy: V < 1");
     if (B == 0) return CS_OK;
     if (!logits || !entropy) return fail(c, CS_EINVAL, "cs_softmax_entropy: NULL buffer");
     if (!aligned16(logits) || !aligned16(entropy)) return fail(c, CS_EALIGN, "cs_softmax_entropy: buffer not 16-byte aligned");
     cs_status st;
     if ((st = bind_device(c)) != CS_OK) return st;
-    hipError_t e = launch_softmax_entropy(logits, B, V, entropy, c->stream);
+    const size_t need = softmax_entropy_scratch_floats(B, V) * sizeof(float);
+    if (need > c->scratch_bytes)
+        return fail(c, CS_ENOMEM, "cs_softmax_entropy: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);
+    hipError_t e = launch_softmax_entropy(logits, B, V, reinterpret_cast<float*>(c->scratch), entropy, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_softmax_entropy");
     return CS_OK;
 }

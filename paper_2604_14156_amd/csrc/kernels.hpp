@@ -58,8 +58,9 @@ size_t pool_rows_scratch_floats(int m, int k_tok);
 hipError_t launch_pool_rows(const float* Y, int n_rows, int m, const int32_t* tokens, int k_tok, float* partial,
                             float* ybar, float* copy, hipStream_t s);
 
-// entropy[B] = entropy in nats of softmax(logits[B][V]) per row
-hipError_t launch_softmax_entropy(const float* logits, int B, int V, float* entropy, hipStream_t s);
+// entropy[B] = entropy in nats of softmax(logits[B][V]) per row; part: softmax_entropy_scratch_floats floats
+size_t softmax_entropy_scratch_floats(int B, int V);
+hipError_t launch_softmax_entropy(const float* logits, int B, int V, float* part, float* entropy, hipStream_t s);
 
 // out[i][:] = x[tokens[i]][:], rows of `row_bytes` bytes (a multiple of 16)
 hipError_t launch_gather_rows(const void* x, int n_rows, size_t row_bytes, const int32_t* tokens, int k_tok,

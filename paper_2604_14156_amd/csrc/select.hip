@@ -186,16 +186,41 @@ hipError_t launch_pool_rows(const float* Y, int n_rows, int m, const int32_t* to
     return hipGetLastError();
 }
 
-// Entropy of softmax(logits) per row (paper Sec. 8.1).  One workgroup per row; with mx the row maximum,
-// S = sum exp(x - mx) and T = sum (x - mx) exp(x - mx), the entropy is ln S - T / S.
-constexpr int EN_THREADS = 1024;
+// Entropy of softmax(logits) per row (paper Sec. 8.1).  With mx a reference value, S = sum exp(x - mx)
+// and T = sum (x - mx) exp(x - mx), the entropy is ln S - T / S.  A row is cut into slices so that a few
+// rows still fill the chip: one workgroup reduces a slice to (mx, S, T) with mx the slice maximum, and a
+// second kernel merges the slices of a row in a fixed order: moving the reference from m1 to M scales
+// S1 by e^(m1-M) and turns T1 into (T1 + (m1 - M) S1) e^(m1-M).
+constexpr int EN_THREADS = 256;
+constexpr int EN_SLICE = 8192;                          // logits per workgroup
 __global__ __launch_bounds__(EN_THREADS)
-void softmax_entropy_kernel(const float* __restrict__ logits, int V, float* __restrict__ entropy) {
+void softmax_entropy_slice_kernel(const float* __restrict__ logits, int V, int nslices, float* __restrict__ part) {
     __shared__ float red[2][EN_THREADS / 64];
-    const float* x = logits + (size_t)blockIdx.x * V;
+    const int row = blockIdx.y, sl = blockIdx.x;
+    const float* x = logits + (size_t)row * V;
+    const int i0 = sl * EN_SLICE, i1 = min(V, i0 + EN_SLICE);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the slice is read once: 32 logits per thread, all loads in flight before the first use
+    constexpr int PER = EN_SLICE / EN_THREADS;
+    float v[PER];
+    if ((V & 3) == 0) {                                 // 16-byte aligned rows
+#pragma unroll
+        for (int q = 0; q < PER / 4; ++q) {
+            const int i = i0 + (q * EN_THREADS + tid) * 4;
+            float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (i < i1) t = *reinterpret_cast<const float4*>(x + i);      // i1 - i is a multiple of 4 here
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int i = i0 + q * EN_THREADS + tid;
+            v[q] = i < i1 ? x[i] : -INFINITY;
+        }
+    }
     float mx = -INFINITY;
-    for (int i = tid; i < V; i += EN_THREADS) mx = fmaxf(mx, x[i]);
+#pragma unroll
+    for (int q = 0; q < PER; ++q) mx = fmaxf(mx, v[q]);
     mx = wave_max(mx);
     if (lane == 0) red[0][wave] = mx;
     __syncthreads();
@@ -203,8 +228,9 @@ void softmax_entropy_kernel(const float* __restrict__ logits, int V, float* __re
     for (int w = 1; w < EN_THREADS / 64; ++w) mx = fmaxf(mx, red[0][w]);
     __syncthreads();
     float S = 0.f, T = 0.f;
-    for (int i = tid; i < V; i += EN_THREADS) {
-        const float d = x[i] - mx;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const float d = v[q] - mx;                      // padding: -inf, contributes nothing
         const float e = __expf(d);
         S += e;
         if (e > 0.f) T += d * e;                       // exp underflow: the term is 0, not (-inf) * 0
@@ -216,13 +242,35 @@ void softmax_entropy_kernel(const float* __restrict__ logits, int V, float* __re
     if (tid == 0) {
         float s = 0.f, t = 0.f;
         for (int w = 0; w < EN_THREADS / 64; ++w) { s += red[0][w]; t += red[1][w]; }
-        entropy[blockIdx.x] = logf(s) - t / s;
+        float* o = part + ((size_t)row * nslices + sl) * 3;
+        o[0] = mx; o[1] = s; o[2] = t;
     }
 }
+__global__ void softmax_entropy_merge_kernel(const float* __restrict__ part, int B, int nslices, float* __restrict__ entropy) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= B) return;
+    const float* p = part + (size_t)row * nslices * 3;
+    float M = p[0];
+    for (int q = 1; q < nslices; ++q) M = fmaxf(M, p[3 * q]);
+    float S = 0.f, T = 0.f;
+    for (int q = 0; q < nslices; ++q) {
+        const float dm = p[3 * q] - M;                 // <= 0; -inf - (-inf) cannot occur: logits are finite
+        const float sc = __expf(dm);
+        if (sc > 0.f) {
+            S += p[3 * q + 1] * sc;
+            T += (p[3 * q + 2] + dm * p[3 * q + 1]) * sc;
+        }
+    }
+    entropy[row] = logf(S) - T / S;
+}
 
-hipError_t launch_softmax_entropy(const float* logits, int B, int V, float* entropy, hipStream_t s) {
+size_t softmax_entropy_scratch_floats(int B, int V) { return (size_t)B * ((V + EN_SLICE - 1) / EN_SLICE) * 3; }
+
+hipError_t launch_softmax_entropy(const float* logits, int B, int V, float* part, float* entropy, hipStream_t s) {
     if (B <= 0) return hipSuccess;
-    hipLaunchKernelGGL(softmax_entropy_kernel, dim3(B), dim3(EN_THREADS), 0, s, logits, V, entropy);
+    const int nslices = (V + EN_SLICE - 1) / EN_SLICE;
+    hipLaunchKernelGGL(softmax_entropy_slice_kernel, dim3(nslices, B), dim3(EN_THREADS), 0, s, logits, V, nslices, part);
+    hipLaunchKernelGGL(softmax_entropy_merge_kernel, dim3((B + 63) / 64), dim3(64), 0, s, part, B, nslices, entropy);
     return hipGetLastError();
 }
 

@@ -123,6 +123,23 @@ void sketch_gauss_kernel(OpDesc op, const float* __restrict__ z, int B, float* _
     }
 }
 
+// LDS position of transform index i: one float of padding per 32 keeps both the 16-float runs of the
+// first pass and the unit-stride accesses of the later passes free of bank conflicts
+__device__ __forceinline__ int wht_pos(int i) { return i + (i >> 5); }
+
+template <int R>
+__device__ __forceinline__ void wht_regs(float (&v)[1 << R]) {
+#pragma unroll
+    for (int lv = 0; lv < R; ++lv)
+#pragma unroll
+        for (int e = 0; e < (1 << R); ++e)
+            if (!(e & (1 << lv))) {
+                const float a = v[e], b = v[e | (1 << lv)];
+                v[e] = a + b;
+                v[e | (1 << lv)] = a - b;
+            }
+}
+
 // butterfly levels of the index bits [sh, sh + R) on the n' = 2^nbits values in LDS
 template <int R>
 __device__ __forceinline__ void wht_pass(float* x, int nbits, int sh) {
@@ -131,46 +148,61 @@ __device__ __forceinline__ void wht_pass(float* x, int nbits, int sh) {
         const int base = ((g >> sh) << (sh + R)) | (g & ((1 << sh) - 1));
         float v[1 << R];
 #pragma unroll
-        for (int e = 0; e < (1 << R); ++e) v[e] = x[base + (e << sh)];
+        for (int e = 0; e < (1 << R); ++e) v[e] = x[wht_pos(base + (e << sh))];
+        wht_regs<R>(v);
 #pragma unroll
-        for (int lv = 0; lv < R; ++lv)
-#pragma unroll
-            for (int e = 0; e < (1 << R); ++e)
-                if (!(e & (1 << lv))) {
-                    const float a = v[e], b = v[e | (1 << lv)];
-                    v[e] = a + b;
-                    v[e | (1 << lv)] = a - b;
-                }
-#pragma unroll
-        for (int e = 0; e < (1 << R); ++e) x[base + (e << sh)] = v[e];
+        for (int e = 0; e < (1 << R); ++e) x[wht_pos(base + (e << sh))] = v[e];
     }
 }
 
 __global__ __launch_bounds__(1024)
 void sketch_srht_kernel(OpDesc op, const float* __restrict__ z, float* __restrict__ y) {
-    extern __shared__ float xs[];                       // [2^nbits] values, then [2^nbits / 32] sign words
+    extern __shared__ float xs[];                       // 2^nbits values at their padded positions
     const int npad = 1 << op.nbits;
-    uint32_t* sg = reinterpret_cast<uint32_t*>(xs + npad);
     const int tok = blockIdx.x, tid = threadIdx.x, NT = blockDim.x;
-    const int ngroups = (op.n + 127) >> 7;              // one Philox call signs 128 columns
-    for (int cg = tid; cg < ngroups; cg += NT) {
-        const u32x4 b = srht_sign_bits(op, (uint32_t)cg);
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-            if (cg * 4 + w < ((npad + 31) >> 5)) sg[cg * 4 + w] = b.w[w];
-    }
-    __syncthreads();
     const float* zt = z + (size_t)tok * op.n;
-    for (int c = tid; c < npad; c += NT) {
-        float v = 0.f;
-        if (c < op.n) {
-            const uint32_t sgn = ((sg[c >> 5] >> (c & 31)) & 1u) << 31;
-            v = __uint_as_float(__float_as_uint(zt[c]) ^ sgn);
+    const bool vec = (op.n & 3) == 0;                   // float4 loads need 16-byte aligned rows of z
+    if (op.nbits >= 4) {
+        // first pass fused with the load: a thread takes 16 consecutive columns (one 16-bit run of sign
+        // bits), transforms index bits 0..3 in registers and stores the run
+        for (int g = tid; g < (npad >> 4); g += NT) {
+            const int c0 = g << 4;
+            float v[16];
+            if (c0 < op.n) {
+                const u32x4 b = srht_sign_bits(op, (uint32_t)c0 >> 7);
+                const uint32_t bits = b.w[(c0 & 127) >> 5] >> (c0 & 31);
+                if (vec && c0 + 16 <= op.n) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 t = *reinterpret_cast<const float4*>(zt + c0 + 4 * q);
+                        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) v[e] = c0 + e < op.n ? zt[c0 + e] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) v[e] = __uint_as_float(__float_as_uint(v[e]) ^ (((bits >> e) & 1u) << 31));
+                wht_regs<4>(v);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) v[e] = 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) xs[wht_pos(c0 + e)] = v[e];
         }
-        xs[c] = v;
+    } else {
+        for (int c = tid; c < npad; c += NT) {
+            float v = 0.f;
+            if (c < op.n) {
+                const u32x4 b = srht_sign_bits(op, 0u);
+                v = __uint_as_float(__float_as_uint(zt[c]) ^ (((b.w[0] >> c) & 1u) << 31));
+            }
+            xs[wht_pos(c)] = v;
+        }
     }
     __syncthreads();
-    int sh = 0;
+    int sh = op.nbits >= 4 ? 4 : 0;
     for (; sh + 4 <= op.nbits; sh += 4) { wht_pass<4>(xs, op.nbits, sh); __syncthreads(); }
     const int rest = op.nbits - sh;
     if (rest == 3) wht_pass<3>(xs, op.nbits, sh);
@@ -178,7 +210,7 @@ void sketch_srht_kernel(OpDesc op, const float* __restrict__ z, float* __restric
     else if (rest == 1) wht_pass<1>(xs, op.nbits, sh);
     __syncthreads();
     const SrhtRows key = srht_rows_key(op);
-    for (int i = tid; i < op.m; i += NT) y[(size_t)tok * op.m + i] = xs[srht_row(key, (uint32_t)i)] * op.scale;
+    for (int i = tid; i < op.m; i += NT) y[(size_t)tok * op.m + i] = xs[wht_pos((int)srht_row(key, (uint32_t)i))] * op.scale;
 }
 
 constexpr int SRHT_MAX_BITS = 15;                       // 128 KB of LDS for the values
@@ -190,7 +222,7 @@ hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipS
     if (op.ens == 2) {
         if (!sketch_srht_supported(op)) return hipErrorInvalidValue;
         const int npad = 1 << op.nbits;
-        const size_t bytes = (size_t)npad * 4 + (size_t)(((npad + 31) >> 5) + 4) * 4;
+        const size_t bytes = (size_t)(npad + (npad >> 5) + 4) * 4;
         static size_t allowed = 0;
         if (bytes > allowed) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_srht_kernel),
