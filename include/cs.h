@@ -139,6 +139,21 @@ cs_status cs_recover_support(cs_ctx* ctx, const cs_op* op, const cs_dict* dict, 
                              int32_t* support, float* coef, float* resid_norm, float* margin);
 
 /*
+ * cs_recover_support for several operators in one launch (Sec. 5: the sketch of step t gives the
+ * support that the next step executes, so the recoveries of all layers of a step are independent
+ * of each other and can be solved together).  Operator j, with dictionary j, serves sketches
+ * y[j][0..B) and writes support[j][..], coef[j][..], resid_norm[j][..], margin[j][..]; every
+ * array is laid out [n_ops][B][...].  All operators must agree in m and n and all dictionaries in
+ * G, b, rb and in having psi or not; the arithmetic per sketch is exactly that of
+ * cs_recover_support.  ops and dicts are host arrays of n_ops entries.  The first call with a
+ * given list of operators allocates a small device table (like cs_plan); later calls allocate
+ * nothing.
+ */
+cs_status cs_recover_support_multi(cs_ctx* ctx, int n_ops, const cs_op* ops, const cs_dict* dicts, int k,
+                                   const float* y, int B,
+                                   int32_t* support, float* coef, float* resid_norm, float* margin);
+
+/*
  * Structured sparse recovery by block iterative hard thresholding: the second cheap
  * solver the paper names (Sec. 8, "projected proximal methods with a small fixed
  * number of iterations"), with the projection onto exactly k units (Sec. 7).

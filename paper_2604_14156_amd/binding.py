@@ -17,7 +17,7 @@ CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
-           "cs_recover_support", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
+           "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
            "cs_softmax_entropy", "cs_uds_budget")
 
 
@@ -50,6 +50,7 @@ def load_library(path=LIB_PATH):
     lib.cs_plan.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict)]
     lib.cs_sketch.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, vp]
     lib.cs_recover_support.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
+    lib.cs_recover_support_multi.argtypes = [vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
     lib.cs_recover_support_iht.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, i32, vp, i32, vp, vp, vp, vp]
     lib.cs_recover_support_inc.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32,
                                            vp, vp, ctypes.c_float, i32, vp, vp, vp, vp]
@@ -140,6 +141,28 @@ class Context:
             margin = torch.empty((B,), dtype=torch.float32, device=dev)
         self._check(self.lib.cs_recover_support(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                 _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
+        return support, coef, resid, margin
+
+    def cs_recover_support_multi(self, ops, dcts, k, y, support=None, coef=None, resid=None, margin=None,
+                                 want_coef=True, want_resid=True):
+        """ops, dcts: sequences of n_ops operators / dictionaries (or ctypes arrays); y: [n_ops, B, m]."""
+        n_ops, B = y.shape[0], y.shape[1]
+        dev = y.device
+        if not isinstance(ops, ctypes.Array):
+            ops = (CsOp * n_ops)(*ops)
+        if not isinstance(dcts, ctypes.Array):
+            dcts = (CsDict * n_ops)(*dcts)
+        rb = dcts[0].rb
+        if support is None:
+            support = torch.empty((n_ops, B, k), dtype=torch.int32, device=dev)
+        if coef is None and want_coef:
+            coef = torch.empty((n_ops, B, k * rb), dtype=torch.float32, device=dev)
+        if resid is None and want_resid:
+            resid = torch.empty((n_ops, B), dtype=torch.float32, device=dev)
+        if margin is None:
+            margin = torch.empty((n_ops, B), dtype=torch.float32, device=dev)
+        self._check(self.lib.cs_recover_support_multi(self._h, n_ops, ops, dcts, k, _ptr(y), B,
+                                                      _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 
     def cs_recover_support_iht(self, op, dct, k, iters, y, support=None, coef=None, resid=None, margin=None,

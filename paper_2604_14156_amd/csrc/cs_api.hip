@@ -28,6 +28,10 @@ struct cs_ctx {
     size_t sync_bytes;
     int lds_limit;
     std::vector<PlanEntry> plans;
+    // device arrays of plans for calls that serve several operators at once, keyed by the plans' atom
+    // buffers (one buffer per plan for the lifetime of the context)
+    struct PlanGroup { std::vector<const float*> key; Plan* d_plans; };
+    std::vector<PlanGroup> groups;
     std::string err;
 };
 
@@ -218,6 +222,8 @@ void cs_destroy(cs_ctx* c) {
         if (pe.plan.gram) (void)hipFree(pe.plan.gram);
         if (pe.plan.W) (void)hipFree(pe.plan.W);
     }
+    for (cs_ctx::PlanGroup& g : c->groups)
+        if (g.d_plans) (void)hipFree(g.d_plans);
     if (c->scratch) (void)hipFree(c->scratch);
     if (c->sync) (void)hipFree(c->sync);
     delete c;
@@ -270,6 +276,61 @@ cs_status cs_recover_support(cs_ctx* c, const cs_op* op, const cs_dict* dict, in
         return fail(c, CS_EALIGN, "cs_recover_support: buffer not 16-byte aligned");
     if ((st = bind_device(c)) != CS_OK) return st;
     return run_recover(c, op, dict, k, y, B, support, coef, resid_norm, margin, 0, "cs_recover_support");
+}
+
+cs_status cs_recover_support_multi(cs_ctx* c, int n_ops, const cs_op* ops, const cs_dict* dicts, int k,
+                                   const float* y, int B,
+                                   int32_t* support, float* coef, float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    if (n_ops < 1 || n_ops > 65535) return fail(c, CS_EINVAL, "cs_recover_support_multi: n_ops=%d out of range [1, 65535]", n_ops);
+    if (!ops || !dicts) return fail(c, CS_EINVAL, "cs_recover_support_multi: NULL operator or dictionary list");
+    cs_status st;
+    for (int j = 0; j < n_ops; ++j) {
+        if ((st = check_recover_args(c, &ops[j], &dicts[j], k, "cs_recover_support_multi")) != CS_OK) return st;
+        if (ops[j].m != ops[0].m || ops[j].n != ops[0].n || dicts[j].G != dicts[0].G || dicts[j].b != dicts[0].b ||
+            dicts[j].rb != dicts[0].rb || (dicts[j].psi == nullptr) != (dicts[0].psi == nullptr))
+            return fail(c, CS_EINVAL, "cs_recover_support_multi: operator %d differs in shape from operator 0", j);
+    }
+    if (B < 0) return fail(c, CS_EINVAL, "cs_recover_support_multi: B < 0");
+    if (B == 0) return CS_OK;
+    if (!y || !support) return fail(c, CS_EINVAL, "cs_recover_support_multi: NULL buffer");
+    if (!aligned16(y) || !aligned16(support) || !aligned16(coef) || !aligned16(resid_norm) || !aligned16(margin))
+        return fail(c, CS_EALIGN, "cs_recover_support_multi: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    std::vector<Plan> host_plans((size_t)n_ops);
+    std::vector<const float*> key((size_t)n_ops);
+    for (int j = 0; j < n_ops; ++j) {
+        const Plan* pl = nullptr;
+        if ((st = find_or_build_plan(c, &ops[j], &dicts[j], &pl)) != CS_OK) return st;
+        host_plans[(size_t)j] = *pl;                    // the cache may move its entries; the device buffers stay
+        key[(size_t)j] = pl->Mt;
+    }
+    const Plan* d_plans = nullptr;
+    for (const cs_ctx::PlanGroup& g : c->groups)
+        if (g.key == key) { d_plans = g.d_plans; break; }
+    if (!d_plans) {                                     // first use of this list of operators: cold, like cs_plan
+        Plan* dp = nullptr;
+        hipError_t e = hipMalloc(&dp, sizeof(Plan) * (size_t)n_ops);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(c, CS_ENOMEM, "cs_recover_support_multi: device allocation failed"); }
+        e = hipMemcpy(dp, host_plans.data(), sizeof(Plan) * (size_t)n_ops, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(dp); return hip_fail(c, e, "cs_recover_support_multi: upload of the plan list"); }
+        c->groups.push_back({key, dp});
+        d_plans = dp;
+    }
+    RecoverArgs a;
+    a.y = y; a.B = B; a.k = k; a.support = support; a.coef = coef; a.resid = resid_norm; a.margin = margin;
+    a.plans = d_plans; a.nplans = n_ops;
+    a.spill_stride = recover_spill_floats(host_plans[0], k, c->lds_limit);
+    a.spill = nullptr;
+    if (a.spill_stride) {
+        const size_t need = a.spill_stride * sizeof(float) * (size_t)B * (size_t)n_ops;
+        if (need > c->scratch_bytes)
+            return fail(c, CS_ENOMEM, "cs_recover_support_multi: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);
+        a.spill = reinterpret_cast<float*>(c->scratch);
+    }
+    hipError_t e = launch_recover(host_plans[0], a, c->lds_limit, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_multi");
+    return CS_OK;
 }
 
 cs_status cs_recover_support_iht(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k, int iters,

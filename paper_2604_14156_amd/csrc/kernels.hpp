@@ -29,6 +29,10 @@ struct RecoverArgs {
     int32_t* support; float* coef; float* resid; float* margin;
     float* spill;         // global workspace for the running factor if it does not fit in LDS
     size_t spill_stride;  // floats per problem
+    // Several operators in one launch: plans[j] (device array of nplans plans of identical shape) serves
+    // problems j*B .. j*B+B-1 of y and of the outputs.  nullptr: the plan passed by value serves all B.
+    const Plan* plans = nullptr;
+    int nplans = 1;
 };
 // bytes of global spill workspace needed per problem (0 if everything fits in LDS)
 size_t recover_spill_floats(const Plan& p, int k, int lds_limit);

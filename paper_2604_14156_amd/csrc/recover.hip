@@ -69,7 +69,8 @@ __global__ void recover_kernel(Plan p, RecoverArgs a, RecoverLayout L) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, NT = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = NT >> 6;
-    const int prob = blockIdx.x;
+    const int prob = blockIdx.y * a.B + blockIdx.x;
+    if (a.plans) p = a.plans[blockIdx.y];
     const int N = p.N, m = p.op.m, rb = p.rb, G = p.G, k = a.k, K = k * rb;
 
     float* corr = lds + L.off_corr;
@@ -346,7 +347,8 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, NT = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = NT >> 6;
-    const int prob = blockIdx.x;
+    const int prob = blockIdx.y * a.B + blockIdx.x;
+    if (a.plans) p = a.plans[blockIdx.y];
     const int N = p.N, m = p.op.m, k = a.k, KS = L.KS;
     const bool active = tid < N;
     const int round_waves = (N + 63) >> 6;     // waves that own atoms
@@ -678,7 +680,7 @@ static hipError_t launch_fast(const Plan& p, const RecoverArgs& a, const FastLay
         if (e != hipSuccess) return e;
         allowed = bytes;
     }
-    hipLaunchKernelGGL((recover_fast_kernel<GRAM_LDS, WANT_MARGIN>), dim3(a.B), dim3(nthreads), bytes, s, p, a, FL);
+    hipLaunchKernelGGL((recover_fast_kernel<GRAM_LDS, WANT_MARGIN>), dim3(a.B, a.nplans), dim3(nthreads), bytes, s, p, a, FL);
     return hipGetLastError();
 }
 
@@ -709,7 +711,7 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
         if (e != hipSuccess) return e;
         allowed = bytes;
     }
-    hipLaunchKernelGGL(recover_kernel, dim3(a.B), dim3(nt), bytes, s, p, a, L);
+    hipLaunchKernelGGL(recover_kernel, dim3(a.B, a.nplans), dim3(nt), bytes, s, p, a, L);
     return hipGetLastError();
 }
 

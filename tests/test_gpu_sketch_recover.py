@@ -359,3 +359,66 @@ def test_top_k_ties_and_small_cases(cs):
         tokens = host(cs.cs_joint_select(op, dev_f32(y), k_tok, ch_op, d8, y_ch, 2)[0])
         p = oracle.token_proxy(wl.RADEMACHER, 3, 0, m, n, y)
         assert list(tokens) == list(oracle.top_k_indices(p, k_tok))
+
+
+def test_multi_operator_recovery_equals_separate_calls(cs):
+    """One launch for the operators of several layers: same arithmetic as one call per operator."""
+    c = wl.CFG2
+    seed = 8100
+    rng = wl.rng_for(seed)
+    n_ops, B = 3, 4
+    ops, dcts, psis, Ys = [], [], [], []
+    for j in range(n_ops):
+        pi, psi = wl.make_profiles(rng, c.G, c.b)
+        z, S = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
+        psi_dev = dev_f32(psi)
+        psis.append(psi_dev)
+        ops.append(binding.make_op(c.ens, seed, 10 + j, c.m, c.n))
+        dcts.append(binding.make_dict(psi_dev, c.G, c.b, 1))
+        cs.cs_plan(ops[j], dcts[j], psi_dev)
+        Ys.append(oracle.sketch(c.ens, seed, 10 + j, c.m, z).astype(np.float32))
+    Y = dev_f32(np.stack(Ys))
+    sup, coef, resid, margin = cs.cs_recover_support_multi(ops, dcts, c.k, Y)
+    assert sup.shape == (n_ops, B, c.k)
+    for j in range(n_ops):
+        s1, c1, r1, m1 = cs.cs_recover_support(ops[j], dcts[j], c.k, Y[j])
+        assert torch.equal(sup[j], s1) and torch.equal(coef[j], c1) and torch.equal(resid[j], r1) and torch.equal(margin[j], m1)
+    # and against the oracle for the last operator
+    M = oracle.effective_matrix(c.ens, seed, 10 + n_ops - 1, c.m, c.n, c.G, c.b, 1, host(psis[-1]).reshape(c.G, c.b, 1))
+    hs_, exact = host(sup[-1]), 0
+    for t in range(B):
+        rec = oracle.block_omp(M, Ys[-1][t].astype(np.float64), c.G, 1, c.k, True)
+        if rec["margin"] > MARGIN:
+            assert list(hs_[t]) == list(rec["support"])
+            exact += 1
+    assert exact >= 1
+    # a second call with the same list reuses the device table; without margins and refit outputs too
+    sup2 = cs.cs_recover_support_multi(ops, dcts, c.k, Y, want_coef=False, want_resid=False)[0]
+    assert torch.equal(sup2, sup)
+
+
+def test_multi_operator_heads_generic_sizes_and_errors(cs):
+    hs = wl.CFG3_HEADS
+    seed = 8200
+    rng = wl.rng_for(seed)
+    n_ops, B = 5, 6
+    ops = [binding.make_op(hs.ens, seed, 2 * j + 1, hs.m, hs.H) for j in range(n_ops)]
+    dcts = [binding.make_dict(None, hs.H, 1, 1) for _ in range(n_ops)]
+    Y = dev_f32(rng.standard_normal((n_ops, B, hs.m)))
+    sup, coef, resid, margin = cs.cs_recover_support_multi(ops, dcts, hs.kh, Y)
+    for j in range(n_ops):
+        s1, c1, r1, m1 = cs.cs_recover_support(ops[j], dcts[j], hs.kh, Y[j])
+        assert torch.equal(sup[j], s1) and torch.equal(coef[j], c1) and torch.equal(resid[j], r1)
+    # blocks of several atoms go through the generic kernel
+    G, b, m, k = 12, 4, 40, 3
+    ops2 = [binding.make_op(wl.GAUSS, seed, 50 + j, m, G * b) for j in range(2)]
+    d2 = [binding.make_dict(None, G, b, b) for _ in range(2)]
+    Y2 = dev_f32(rng.standard_normal((2, 3, m)))
+    sup2, coef2, resid2, _ = cs.cs_recover_support_multi(ops2, d2, k, Y2)
+    for j in range(2):
+        s1, c1, r1, _ = cs.cs_recover_support(ops2[j], d2[j], k, Y2[j])
+        assert torch.equal(sup2[j], s1) and torch.equal(coef2[j], c1) and torch.equal(resid2[j], r1)
+    bad = [ops[0], binding.make_op(hs.ens, seed, 3, hs.m + 1, hs.H)]
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support_multi(bad, dcts[:2], hs.kh, Y[:2])
+    assert e.value.status == binding.CS_EINVAL
