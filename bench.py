@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--solver", choices=["omp", "iht"], default="omp",
                     help="recovery of the FFN block supports: block-OMP (default) or block iterative hard thresholding")
     ap.add_argument("--iht-iters", type=int, default=12)
+    ap.add_argument("--recovery", choices=["next-step", "same-step"], default="next-step",
+                    help="next-step: the sketches of step t give the supports step t+1 executes, and the recoveries of "
+                         "all layers are solved in batched launches; same-step: every layer's support is recovered "
+                         "just ahead of that layer's execution in the same step")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     return ap.parse_args()
 
@@ -114,9 +118,35 @@ class DecodeState:
         self.marginh_l = [torch.empty((B,), device=dev) for _ in range(layers)]
         self.o = torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf)
         self.out = torch.empty((B, c.d), device=dev, dtype=bf)
+        # next-step mode: sketches of all layers of a step, and two generations of supports
+        self.Y_all = torch.empty((layers, B, c.m), device=dev)
+        self.Yh_all = torch.empty((layers, B, hs.m), device=dev)
+        self.S_gen = [torch.zeros((layers, B, c.k), dtype=torch.int32, device=dev) for _ in range(2)]
+        self.H_gen = [torch.zeros((layers, B, hs.kh), dtype=torch.int32, device=dev) for _ in range(2)]
+        self.margin_all = torch.empty((layers, B), device=dev)
+        self.marginh_all = torch.empty((layers, B), device=dev)
+        # layer groups of the batched recovery (ctypes arrays of operators and dictionaries per group)
+        self.groups = []
+        ngroups = min(NEXT_GROUPS, layers)
+        per = (layers + ngroups - 1) // ngroups
+        for g0 in range(0, layers, per):
+            ls = list(range(g0, min(layers, g0 + per)))
+            self.groups.append({
+                "layers": ls,
+                "ffn_ops": (binding.CsOp * len(ls))(*[self.ffn_op[l] for l in ls]),
+                "ffn_dicts": (binding.CsDict * len(ls))(*[self.ffn_dict[l] for l in ls]),
+                "head_ops": (binding.CsOp * len(ls))(*[self.head_op[l] for l in ls]),
+                "head_dicts": (binding.CsDict * len(ls))(*[self.head_dict for _ in ls]),
+            })
 
 
 SOLVER = {"name": "omp", "iters": 12}
+NEXT_GROUPS = 2     # batched recovery launches per step and kind (a group starts once its layers are sketched)
+# Layers per ordering point "layer l issued -> sketch of layer l" between the two streams; 0 = none.
+# The usage vectors of this workload are synthetic and resident, so nothing has to be waited for; an
+# event recorded on the execution stream per layer costs that stream about 20 us per layer when the
+# step is replayed as a graph (5.7 ms against 5.4 ms per step), which is why the default is 0.
+NEXT_SYNC = 0
 
 
 def recover_ffn(cx, st, l, y, S, margin):
@@ -191,6 +221,52 @@ def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec, chunk=None, ahead=Non
     s_exec.wait_stream(s_rec)
 
 
+def recover_group(cx, st, grp, gen):
+    """Batched recovery of one group of layers into support generation `gen`."""
+    c, hs = st.c, st.hs
+    l0, l1 = grp["layers"][0], grp["layers"][-1] + 1
+    cx.cs_recover_support_multi(grp["head_ops"], grp["head_dicts"], hs.kh, st.Yh_all[l0:l1], st.H_gen[gen][l0:l1],
+                                None, None, st.marginh_all[l0:l1], want_coef=False, want_resid=False)
+    cx.cs_recover_support_multi(grp["ffn_ops"], grp["ffn_dicts"], c.k, st.Y_all[l0:l1], st.S_gen[gen][l0:l1],
+                                None, None, st.margin_all[l0:l1], want_coef=False, want_resid=False)
+
+
+def decode_step_next(ctx, rctx, st, i, s_exec, s_rec):
+    """One decode step in which the sketches of this step give the supports of the next one (paper Sec. 5:
+    the reduced computation for the next step uses the units recovered now).  Execution of layer l uses
+    the supports of generation i % 2; the second stream sketches every layer (after that layer has been
+    issued when NEXT_SYNC > 0) and, as soon as a group of layers is sketched, recovers the whole group in
+    one launch per kind into generation (i + 1) % 2.  The streams join at the end of the step."""
+    cur, nxt = i % 2, (i + 1) % 2
+    s_rec.wait_stream(s_exec)
+    last_of_group = {g["layers"][-1]: g for g in st.groups}
+    for l in range(st.layers):
+        with torch.cuda.stream(s_exec):
+            ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.H_gen[cur][l], st.o)
+            ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S_gen[cur][l], False, st.out)
+            sync_here = NEXT_SYNC > 0 and (l % NEXT_SYNC) == NEXT_SYNC - 1
+            if sync_here:
+                issued = torch.cuda.Event()
+                issued.record(s_exec)
+        with torch.cuda.stream(s_rec):
+            if sync_here:
+                s_rec.wait_event(issued)
+            rctx.cs_sketch(st.head_op[l], st.u[i][l], st.Yh_all[l])
+            rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.Y_all[l])
+            if l in last_of_group:
+                recover_group(rctx, st, last_of_group[l], nxt)
+    s_exec.wait_stream(s_rec)
+
+
+def prime_supports(ctx, st):
+    """Generation 0 of the supports, from the sketches of step 0 (before the timed region)."""
+    for l in range(st.layers):
+        ctx.cs_sketch(st.head_op[l], st.u[0][l], st.Yh_all[l])
+        ctx.cs_sketch(st.ffn_op[l], st.z[0][l], st.Y_all[l])
+    for grp in st.groups:
+        recover_group(ctx, st, grp, 0)
+
+
 def call_loops(ctx, st, stream):
     """ms per call of each call type, measured with HIP events around loops that launch that
     call for every layer in turn (two passes after one warm pass).  Returns (per, mean union size)."""
@@ -220,7 +296,11 @@ def call_loops(ctx, st, stream):
     for name, fn in loops.items():
         time_loop(fn, nl, stream)
         raw[name] = time_loop(fn, 2 * nl, stream)
-    per = {"attn": raw["attn"], "ffn": raw["ffn"],
+    # batched recovery of a whole step (all groups, both kinds), as the next-step mode launches it
+    fn = lambda i: [recover_group(ctx, st, grp, 1) for grp in st.groups]
+    time_loop(fn, 2, stream)
+    raw["recover_step_batched"] = time_loop(fn, 8, stream)
+    per = {"attn": raw["attn"], "ffn": raw["ffn"], "recover_step_batched": raw["recover_step_batched"],
            "recover": 0.5 * (raw["recover_ffn"] + raw["recover_heads"]),
            "sketch": 0.5 * (raw["sketch_ffn"] + raw["sketch_heads"])}
     per.update({k: raw[k] for k in ("recover_ffn", "recover_heads", "sketch_ffn", "sketch_heads")})
@@ -408,6 +488,16 @@ def main():
             return
         # one HIP graph per step: the launches of a step (two streams, 8 kernels per layer) are
         # replayed without host work in between
+        if args.recovery == "next-step":
+            if args.solver != "omp":
+                raise SystemExit("--recovery next-step batches the block-OMP solver; use --recovery same-step with --solver iht")
+            prime_supports(ctx, st)
+            for grp in st.groups:                       # the recovery context builds its device tables now
+                recover_group(rctx, st, grp, 1)
+            torch.cuda.synchronize()
+            step_fn = decode_step_next
+        else:
+            step_fn = decode_step_pipelined
         graphs = None
         if not args.no_graph:
             try:
@@ -415,7 +505,7 @@ def main():
                 for i in range(nsteps):
                     g = torch.cuda.CUDAGraph()
                     with torch.cuda.graph(g, stream=stream, capture_error_mode="thread_local"):
-                        decode_step_pipelined(ctx, rctx, st, i, stream, rstream)
+                        step_fn(ctx, rctx, st, i, stream, rstream)
                     graphs.append(g)
             except Exception as exc:                # fall back to plain launches
                 print("graph capture failed (%s); running eager" % exc, file=sys.stderr)
@@ -426,7 +516,7 @@ def main():
             if graphs is not None:
                 graphs[i].replay()
             else:
-                decode_step_pipelined(ctx, rctx, st, i, stream, rstream)
+                step_fn(ctx, rctx, st, i, stream, rstream)
 
         for i in range(args.warmup):
             run(i)
@@ -456,6 +546,9 @@ def main():
     tokens_per_s = args.batch / (wall / args.steps)
     calls_per_step = {"sketch": 2 * args.layers, "recover": 2 * args.layers, "attn": args.layers, "ffn": args.layers}
     step_share = {k: per[k] * calls_per_step[k] for k in calls_per_step}
+    per_layer_recover_ms = step_share["recover"]
+    if args.recovery == "next-step":
+        step_share["recover"] = per["recover_step_batched"]
     kernels = {
         "attn": {"us_per_call": per["attn"] * 1e3, "active_MB": attn_bytes / 1e6,
                  "GBs": attn_bytes / (per["attn"] * 1e-3) / 1e9,
@@ -488,9 +581,18 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": recorded_traffic("cs_head_attn" if dom == "attn" else "cs_block_ffn")},
         "kernels": kernels,
-        "recovery": {"us_per_token": step_share["recover"] * 1e3 / args.batch,
-                     "frac_of_serial_step": rec_frac, "margin_pass_rate": margin_pass,
-                     "note": "in the timed region recovery runs on a second stream one layer ahead of execution"},
+        "recovery": {"mode": args.recovery,
+                     "us_per_token": step_share["recover"] * 1e3 / args.batch,
+                     "ms_per_step": step_share["recover"],
+                     "frac_of_serial_step": rec_frac,
+                     "frac_of_step_with_sketches": (step_share["recover"] + step_share["sketch"]) / sum(step_share.values()),
+                     "ms_per_step_one_call_per_layer": per_layer_recover_ms,
+                     "margin_pass_rate": margin_pass,
+                     "note": ("the sketches of step t give the supports step t+1 executes; a second stream sketches the "
+                              "layers and recovers %d groups of layers with one launch per group and kind; the "
+                              "synthetic usage vectors are resident, so that stream is not ordered against the "
+                              "execution of the same step" % len(st.groups)) if args.recovery == "next-step" else
+                             "measurement and recovery run on a second stream up to 4 layers ahead of execution in the same step"},
         "serial_step_breakdown_ms": step_share,
         "ms_per_step_serial_sum": sum(step_share.values()),
         "launch_mode": "hip_graph" if graphs is not None else "eager",

@@ -98,3 +98,93 @@ def test_pipelined_step_graph_replays_match_eager():
             assert torch.equal(out[0], ref[2 * layers + layers + 0])
     ctx.close()
     rctx.close()
+
+
+def test_next_step_graph_with_batched_recovery_replays_match_eager():
+    """The other step shape: execution reads one generation of supports while the second stream sketches
+    all layers and recovers them with one launch per kind into the other generation."""
+    dev = "cuda:0"
+    c = wl.scaled(wl.CFG2, d=512, G=24, k=6, m=64)
+    hs = wl.scaled(wl.CFG3_HEADS, L=200)
+    B, layers = 4, 3
+    s_exec, s_rec = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx, rctx = binding.Context(0, s_exec), binding.Context(0, s_rec)
+    gen = torch.Generator(device=dev).manual_seed(11)
+    bf = torch.bfloat16
+    rn = lambda *shape: torch.randn(shape, generator=gen, device=dev)
+    with torch.cuda.stream(s_exec):
+        Wg = [rn(c.G, c.b, c.d).mul(0.05).to(bf) for _ in range(layers)]
+        Wu = [rn(c.G, c.b, c.d).mul(0.05).to(bf) for _ in range(layers)]
+        Wd = [rn(c.G, c.d, c.b).mul(0.05).to(bf) for _ in range(layers)]
+        K = [rn(B, hs.H, hs.L, hs.dh).to(bf) for _ in range(layers)]
+        V = [rn(B, hs.H, hs.L, hs.dh).to(bf) for _ in range(layers)]
+        psi = []
+        for _ in range(layers):
+            p = rn(c.G, c.b)
+            psi.append((p / p.norm(dim=1, keepdim=True)).reshape(c.G, c.b, 1).contiguous())
+        z, u = rn(layers, B, c.n), rn(layers, B, hs.H)
+        x = [rn(B, c.d).to(bf) for _ in range(layers)]
+        q = [rn(B, hs.H, hs.dh).to(bf) for _ in range(layers)]
+        fop = [binding.make_op(c.ens, 6, 2 * l, c.m, c.n) for l in range(layers)]
+        hop = [binding.make_op(hs.ens, 6, 2 * l + 1, hs.m, hs.H) for l in range(layers)]
+        fdict = [binding.make_dict(psi[l], c.G, c.b, 1) for l in range(layers)]
+        hdict = [binding.make_dict(None, hs.H, 1, 1) for _ in range(layers)]
+        Y = torch.empty((layers, B, c.m), device=dev)
+        Yh = torch.empty((layers, B, hs.m), device=dev)
+        S = [torch.zeros((layers, B, c.k), dtype=torch.int32, device=dev) for _ in range(2)]
+        Hh = [torch.zeros((layers, B, hs.kh), dtype=torch.int32, device=dev) for _ in range(2)]
+        mg = torch.empty((2, layers, B), device=dev)
+        o = [torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf) for _ in range(layers)]
+        out = [torch.empty((B, c.d), device=dev, dtype=bf) for _ in range(layers)]
+
+        def recover_all(cx, gen_idx):
+            cx.cs_recover_support_multi(hop, hdict, hs.kh, Yh, Hh[gen_idx], None, None, mg[0], want_coef=False, want_resid=False)
+            cx.cs_recover_support_multi(fop, fdict, c.k, Y, S[gen_idx], None, None, mg[1], want_coef=False, want_resid=False)
+
+        # generation 0 from the sketches themselves (eager, first stream), device tables of both contexts
+        for l in range(layers):
+            ctx.cs_sketch(hop[l], u[l], Yh[l])
+            ctx.cs_sketch(fop[l], z[l], Y[l])
+        recover_all(ctx, 0)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s_rec):
+            recover_all(rctx, 1)
+        torch.cuda.synchronize()
+
+        def step():
+            s_rec.wait_stream(s_exec)
+            for l in range(layers):
+                with torch.cuda.stream(s_exec):
+                    ctx.cs_head_attn(q[l], K[l], V[l], Hh[0][l], o[l])
+                    ctx.cs_block_ffn(Wg[l], Wu[l], Wd[l], x[l], S[0][l], False, out[l])
+                with torch.cuda.stream(s_rec):
+                    rctx.cs_sketch(hop[l], u[l], Yh[l])
+                    rctx.cs_sketch(fop[l], z[l], Y[l])
+            with torch.cuda.stream(s_rec):
+                recover_all(rctx, 1)
+            s_exec.wait_stream(s_rec)
+
+        def snapshot():
+            torch.cuda.synchronize()
+            return [t.clone() for t in [S[1], Hh[1], Y, Yh] + o + out]
+
+        step()
+        ref = snapshot()
+        assert torch.equal(ref[0], S[0]) and torch.equal(ref[1], Hh[0])      # same sketches, same supports
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s_exec, capture_error_mode="thread_local"):
+            step()
+        for rep in range(4):
+            S[1].fill_(-7); Hh[1].fill_(-7); Y.fill_(0.5); Yh.fill_(0.5)
+            for t in o + out:
+                t.fill_(3.0)
+            torch.cuda.synchronize()
+            g.replay()
+            got = snapshot()
+            for a, b in zip(ref, got):
+                assert torch.equal(a, b), rep
+            ctx.cs_recover_support_multi(fop, fdict, c.k, Y, S[1], None, None, mg[1], want_coef=False, want_resid=False)
+            torch.cuda.synchronize()
+            assert torch.equal(S[1], ref[0])
+    ctx.close()
+    rctx.close()
