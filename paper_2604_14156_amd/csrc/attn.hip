@@ -19,15 +19,18 @@ namespace csk {
 #ifndef CS_AT_UNROLL
 #define CS_AT_UNROLL 8
 #endif
-#ifndef CS_AT_WAVES
-#define CS_AT_WAVES 4
+#ifndef CS_AT_WGS_WIDE
+#define CS_AT_WGS_WIDE 768
 #endif
-#ifndef CS_AT_TARGET_WGS
-#define CS_AT_TARGET_WGS 2048
+#ifndef CS_AT_WGS_NARROW
+#define CS_AT_WGS_NARROW 3072
 #endif
 constexpr int AT_UNROLL = CS_AT_UNROLL;          // key/value row pairs in flight per lane
-constexpr int AT_WAVES = CS_AT_WAVES;            // waves per workgroup
-constexpr int AT_TARGET_WGS = CS_AT_TARGET_WGS;  // workgroups wanted in flight (8 per compute unit)
+// Two workgroup shapes.  Wide (16 waves) streams best when there is enough work for three such
+// workgroups per compute unit; narrow (4 waves) cuts a small batch into more pieces.
+constexpr int AT_WAVES_WIDE = 16, AT_WAVES_NARROW = 4;
+constexpr int AT_WGS_WIDE = CS_AT_WGS_WIDE;      // workgroups wanted, wide shape (2 resident per compute unit)
+constexpr int AT_WGS_NARROW = CS_AT_WGS_NARROW;  // workgroups wanted, narrow shape (8 resident per compute unit)
 constexpr int AT_MAX_SPLIT = 32;
 
 
@@ -86,31 +89,77 @@ template <> struct Frag8<uint16_t> {
     }
 };
 
+// Merge of the position ranges of one head for output element c: partial results are
+// [max, sum, acc[DH]] per range, scores in base 2.  Two passes (the overall maximum, then the
+// weighted sums), each with eight ranges' loads in flight.
+template <int DH>
+__device__ __forceinline__ float merge_ranges(const float* __restrict__ pp, int nsplit, int c) {
+    float mtot = -INFINITY;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float mx[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mx[u] = s0 + u < nsplit ? pp[(size_t)(s0 + u) * (DH + 2)] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mtot = fmaxf(mtot, mx[u]);
+    }
+    float num = 0.f, den = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float mx[8], sm[8], ac[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float* ps = pp + (size_t)(s0 + u) * (DH + 2);
+            const bool in = s0 + u < nsplit;
+            mx[u] = in ? ps[0] : -INFINITY;
+            sm[u] = in ? ps[1] : 0.f;
+            ac[u] = in ? ps[2 + c] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = mx[u] > -INFINITY ? exp2f(mx[u] - mtot) : 0.f;
+            num += w * ac[u];
+            den += w * sm[u];
+        }
+    }
+    return den > 0.f ? num / den : 0.f;
+}
+
 template <typename T, int DH, int NW, bool FINAL>
 __global__ __launch_bounds__(NW * 64)
 void attn_stream_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
                         int H, int L, const int32_t* __restrict__ heads, int kh,
-                        int span, float* __restrict__ part, T* __restrict__ out) {
+                        int span, int nsplit, float* __restrict__ part, T* __restrict__ out) {
     constexpr int LPP = DH / 8;              // lanes per position
     constexpr int PPW = 64 / LPP;            // positions per wavefront step
     constexpr int STEP = PPW * NW;           // positions per workgroup step
     __shared__ float sm[NW][DH + 2];
 
-    const int split = blockIdx.x, h = blockIdx.y, seq = blockIdx.z;
-    const int nsplit = gridDim.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPP, grp = lane / LPP;
-    int slot = -1;
-    for (int j0 = 0; j0 < kh; j0 += 64) {                // one load per lane, match found by ballot
-        const int j = j0 + lane;
-        const int hv = j < kh ? heads[seq * kh + j] : -1;
-        const unsigned long long bal = __ballot(hv == h);
-        if (bal) slot = j0 + __ffsll((long long)bal) - 1;
-    }
-    if (slot < 0) {                          // pruned head: zeros, written once
-        if (split == 0)
+    int split, seq, slot, h;
+    if (FINAL) {
+        // grid (1, H, B): all heads, the pruned ones write their zeros here
+        split = 0; h = blockIdx.y; seq = blockIdx.z;
+        slot = -1;
+        for (int j0 = 0; j0 < kh; j0 += 64) {            // one load per lane, match found by ballot
+            const int j = j0 + lane;
+            const int hv = j < kh ? heads[seq * kh + j] : -1;
+            const unsigned long long bal = __ballot(hv == h);
+            if (bal) slot = j0 + __ffsll((long long)bal) - 1;
+        }
+        if (slot < 0) {
             for (int c = threadIdx.x; c < DH; c += NW * 64) store1(out + ((size_t)seq * H + h) * DH + c, 0.f);
-        return;
+            return;
+        }
+    } else {
+        // grid (B * kh * nsplit): kept heads only, in the order [seq][slot][range].  There are more
+        // workgroups than fit on the chip at once, so the dispatcher hands the later ones to whichever
+        // compute unit is free: units that get a smaller share of the memory bandwidth process fewer ranges.
+        const int item = blockIdx.x;
+        split = item % nsplit;
+        slot = (item / nsplit) % kh;
+        seq = item / (nsplit * kh);
+        h = heads[seq * kh + slot];
+        if (h < 0 || h >= H) return;                     // uniform; the merge kernel skips the entry too
     }
     const size_t head_off = ((size_t)seq * H + h);
     const T* Kh = K + head_off * (size_t)L * DH + sub * 8;
@@ -195,67 +244,73 @@ void attn_stream_kernel(const T* __restrict__ q, const T* __restrict__ K, const 
     if (threadIdx.x == 0) { dst[0] = mtot; dst[1] = den; }
 }
 
-// One thread per output element: merge the position ranges of a kept head (pruned
-// heads were zeroed by the streaming kernel).  All loads are issued before any is used.
+// Merge kernel, grid (kh, B), one thread per output element: workgroup `slot` merges the position
+// ranges of the head listed there and writes the zeros of those of the heads slot, slot + kh,
+// slot + 2 kh, ... that are pruned (between them the kh workgroups of a sequence cover all H heads).
+// A head listed twice is merged by both workgroups, with equal results.
 template <typename T, int DH>
 __global__ void attn_combine_kernel(const float* __restrict__ part, int H, const int32_t* __restrict__ heads,
                                     int kh, int nsplit, T* __restrict__ out) {
     const int slot = blockIdx.x, seq = blockIdx.y;
-    const int c = threadIdx.x;
+    const int c = threadIdx.x, lane = c & 63;
     const int h = heads[seq * kh + slot];
-    const float* pp = part + ((size_t)seq * kh + slot) * nsplit * (DH + 2);
-    float mx[AT_MAX_SPLIT], sm[AT_MAX_SPLIT], ac[AT_MAX_SPLIT];
-#pragma unroll
-    for (int s = 0; s < AT_MAX_SPLIT; ++s) {
-        const float* ps = pp + (size_t)s * (DH + 2);
-        mx[s] = s < nsplit ? ps[0] : -INFINITY;
-        sm[s] = s < nsplit ? ps[1] : 0.f;
-        ac[s] = s < nsplit ? ps[2 + c] : 0.f;
+    for (int hp = slot; hp < H; hp += kh) {
+        bool listed = false;
+        for (int j0 = 0; j0 < kh; j0 += 64) {
+            const int j = j0 + lane;
+            listed |= __ballot(j < kh && heads[seq * kh + j] == hp) != 0ull;
+        }
+        if (!listed) store1(out + ((size_t)seq * H + hp) * DH + c, 0.f);
     }
     if (h < 0 || h >= H) return;
-    float mtot = -INFINITY;
-#pragma unroll
-    for (int s = 0; s < AT_MAX_SPLIT; ++s) mtot = fmaxf(mtot, mx[s]);
-    float num = 0.f, den = 0.f;
-#pragma unroll
-    for (int s = 0; s < AT_MAX_SPLIT; ++s) {
-        const float w = mx[s] > -INFINITY ? exp2f(mx[s] - mtot) : 0.f;
-        num += w * ac[s];
-        den += w * sm[s];
-    }
-    store1(out + ((size_t)seq * H + h) * DH + c, den > 0.f ? num / den : 0.f);
+    const float* pp = part + ((size_t)seq * kh + slot) * nsplit * (DH + 2);
+    store1(out + ((size_t)seq * H + h) * DH + c, merge_ranges<DH>(pp, nsplit, c));
 }
 
-// Number of position ranges per head and their length.  One range (the result is
-// written directly) only when the cache is short.
-static void attn_split(const AttnArgs& a, int& nsplit, int& span) {
+// Workgroup shape, number of position ranges per head and their length.  One range (the result
+// is written directly) only when the cache is short.  A range is a whole number of unrolled passes
+// of a workgroup.
+struct AttnShape { int nw, nsplit, span; };
+
+static AttnShape attn_shape_for(const AttnArgs& a, int nw, long target) {
     const long pairs = (long)a.B * a.kh;
-    long want = pairs > 0 ? (AT_TARGET_WGS + pairs - 1) / pairs : 1;
+    long want = pairs > 0 ? (target + pairs - 1) / pairs : 1;
     if (want > AT_MAX_SPLIT) want = AT_MAX_SPLIT;
     long sp = (a.L + want - 1) / want;
-    sp = ((sp + 63) / 64) * 64;
-    span = (int)sp;
-    nsplit = (a.L + span - 1) / span;
-    if (nsplit == 1) span = a.L;
+    const long unit = (long)(64 / (a.dh / 8)) * nw * AT_UNROLL;
+    sp = ((sp + unit - 1) / unit) * unit;
+    AttnShape r;
+    r.nw = nw;
+    r.span = (int)sp;
+    r.nsplit = (int)((a.L + sp - 1) / sp);
+    if (r.nsplit == 1) r.span = a.L;
+    return r;
+}
+
+static AttnShape attn_shape(const AttnArgs& a) {
+    const AttnShape wide = attn_shape_for(a, AT_WAVES_WIDE, AT_WGS_WIDE);
+    if ((long)a.B * a.kh * wide.nsplit >= 512) return wide;
+    return attn_shape_for(a, AT_WAVES_NARROW, AT_WGS_NARROW);
 }
 
 size_t attn_scratch_bytes(const AttnArgs& a) {
-    int nsplit, span;
-    attn_split(a, nsplit, span);
-    return nsplit == 1 ? 0 : (size_t)a.B * a.kh * nsplit * (a.dh + 2) * sizeof(float);
+    const AttnShape sh = attn_shape(a);
+    return sh.nsplit == 1 ? 0 : (size_t)a.B * a.kh * sh.nsplit * (a.dh + 2) * sizeof(float);
 }
 
-template <typename T, int DH>
-static hipError_t run_attn(const AttnArgs& a, hipStream_t s) {
-    int nsplit, span;
-    attn_split(a, nsplit, span);
+template <typename T, int DH, int NW>
+static hipError_t run_attn(const AttnArgs& a, const AttnShape& sh, hipStream_t s) {
+    const int nsplit = sh.nsplit, span = sh.span;
     float* part = reinterpret_cast<float*>(a.scratch);
     if (nsplit == 1) {
-        hipLaunchKernelGGL((attn_stream_kernel<T, DH, AT_WAVES, true>), dim3(1, a.H, a.B), dim3(AT_WAVES * 64), 0, s,
-                           (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, part, (T*)a.out);
+        hipLaunchKernelGGL((attn_stream_kernel<T, DH, NW, true>), dim3(1, a.H, a.B), dim3(NW * 64), 0, s,
+                           (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, 1, part, (T*)a.out);
     } else {
-        hipLaunchKernelGGL((attn_stream_kernel<T, DH, AT_WAVES, false>), dim3(nsplit, a.H, a.B), dim3(AT_WAVES * 64), 0, s,
-                           (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, part, (T*)a.out);
+        const long nitems = (long)a.B * a.kh * nsplit;
+        if (nitems > 0x7fffffffL) return hipErrorInvalidValue;
+        if (nitems > 0)
+            hipLaunchKernelGGL((attn_stream_kernel<T, DH, NW, false>), dim3((unsigned)nitems), dim3(NW * 64), 0, s,
+                               (const T*)a.q, (const T*)a.K, (const T*)a.V, a.H, a.L, a.heads, a.kh, span, nsplit, part, (T*)a.out);
         if (a.kh > 0)
             hipLaunchKernelGGL((attn_combine_kernel<T, DH>), dim3(a.kh, a.B), dim3(DH), 0, s,
                                part, a.H, a.heads, a.kh, nsplit, (T*)a.out);
@@ -265,7 +320,8 @@ static hipError_t run_attn(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_head_attn(const AttnArgs& a, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
-#define CS_ATTN_CASE(TYPE, DHV) if (a.dh == DHV) return run_attn<TYPE, DHV>(a, s)
+    const AttnShape sh = attn_shape(a);
+#define CS_ATTN_CASE(TYPE, DHV) if (a.dh == DHV) return sh.nw == AT_WAVES_WIDE ? run_attn<TYPE, DHV, AT_WAVES_WIDE>(a, sh, s) : run_attn<TYPE, DHV, AT_WAVES_NARROW>(a, sh, s)
     if (a.dtype == 0) { CS_ATTN_CASE(float, 64); CS_ATTN_CASE(float, 128); CS_ATTN_CASE(float, 256); }
     else { CS_ATTN_CASE(uint16_t, 64); CS_ATTN_CASE(uint16_t, 128); CS_ATTN_CASE(uint16_t, 256); }
 #undef CS_ATTN_CASE
