@@ -2,12 +2,13 @@
 // operator generated on the fly: no entry of Phi is ever written to memory.
 //
 // Rademacher ensemble.  A workgroup owns RR rows of Phi and TB tokens; its 16
-// wavefronts split the columns in tiles of 256.  Per tile, lane L < 2*RR draws the
-// 128 sign bits of (row L % RR, call L / RR) with one Philox call; the words are
-// handed to the other lanes with scalar lane reads.  Lane l owns columns
-// l, l+64, l+128, l+192 of the tile, so the loads of z are coalesced and each value
-// of z is reused for all RR rows from a register.  The RR*TB running sums per lane
-// are reduced across the wavefront once at the end, then across wavefronts in LDS.
+// wavefronts split the columns in tiles of 256 (wave w takes tiles w, w+16, ...).  One Philox
+// pass of a wave draws the sign bits of all its tiles at once: 2*RR lanes per tile, lane = (tile,
+// call, row), 128 bits each; the words are handed to the other lanes with scalar lane reads.
+// Lane l owns columns l, l+64, l+128, l+192 of a tile, so the loads of z are coalesced and each
+// value of z is reused for all RR rows from a register; an entry costs one multiply-add with
+// +-1.0.  The RR*TB running sums per lane are reduced across the wavefront once at the end, then
+// across wavefronts in LDS.
 //
 // Gaussian ensemble.  One wavefront per row and token chunk; a lane draws four
 // normals per Philox call (Box-Muller) and applies them to one float4 of z.
@@ -24,62 +25,74 @@ namespace csk {
 constexpr int SK_TB = 8;          // tokens per wavefront pass
 constexpr int SK_WAVES = 4;       // rows per workgroup (Gaussian kernel)
 
-constexpr int SR_RR = 4;          // rows per workgroup (Rademacher kernel)
-constexpr int SR_TB = 8;          // tokens per workgroup
 constexpr int SR_WAVES = 16;
 
+// RR rows of Phi and TB tokens per workgroup.  The kernel is a short latency chain (one Philox
+// call, one round trip for z, the reductions), so the launcher picks the smallest RR that still
+// gives every compute unit a workgroup.
+template <int RR, int TB>
 __global__ __launch_bounds__(SR_WAVES * 64)
 void sketch_rademacher_kernel(OpDesc op, const float* __restrict__ z, int B, float* __restrict__ y) {
-    __shared__ float part[SR_WAVES][SR_RR * SR_TB];
+    __shared__ float part[SR_WAVES][RR * TB];
+    constexpr int PER = 2 * RR;              // lanes that draw the bits of one 256-column tile
+    constexpr int CH = 64 / PER;             // tiles covered by one Philox pass of the wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row0 = blockIdx.x * SR_RR;
-    const int t0 = blockIdx.y * SR_TB;
-    const int nt = min(SR_TB, B - t0);
+    const int row0 = blockIdx.x * RR;
+    const int t0 = blockIdx.y * TB;
+    const int nt = min(TB, B - t0);
     const int n = op.n;
-    float acc[SR_RR][SR_TB];
+    float acc[RR][TB];
 #pragma unroll
-    for (int r = 0; r < SR_RR; ++r)
+    for (int r = 0; r < RR; ++r)
 #pragma unroll
-        for (int t = 0; t < SR_TB; ++t) acc[r][t] = 0.f;
+        for (int t = 0; t < TB; ++t) acc[r][t] = 0.f;
 
     const int ntiles = (n + 255) >> 8;
     const uint32_t hi = (uint32_t)(lane >> 5);           // which half of the wave: selects the word pair
     const uint32_t sh = 31u - (uint32_t)(lane & 31);     // shift that moves this lane's bit to the sign position
-    for (int tile = wave; tile < ntiles; tile += SR_WAVES) {
-        // lane L < 2*RR: bits of row (row0 + L % RR), columns 128*(2*tile + L / RR) .. +127
+    // this wave's tiles are wave, wave + 16, wave + 32, ...; one Philox pass draws the bits of CH of them:
+    // lane L holds row (row0 + L % RR), call (L / RR) % 2 of tile number L / PER of the pass
+    for (int j0 = 0; wave + j0 * SR_WAVES < ntiles; j0 += CH) {
         u32x4 bits;
         {
-            const uint32_t r = (uint32_t)(lane % SR_RR), c = (uint32_t)(lane / SR_RR) & 1u;
-            bits = rademacher_bits(op, (uint32_t)row0 + r, (uint32_t)(2 * tile) + c);
+            const uint32_t l = (uint32_t)(lane % PER);
+            const uint32_t tl = (uint32_t)(wave + (j0 + lane / PER) * SR_WAVES);
+            bits = rademacher_bits(op, (uint32_t)row0 + l % RR, 2u * tl + l / RR);
         }
+#pragma unroll 1
+        for (int jj = 0; jj < CH; ++jj) {
+            const int tile = wave + (j0 + jj) * SR_WAVES;
+            if (tile >= ntiles) break;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int col = (tile << 8) + 64 * q + lane;
-            float zv[SR_TB];
+            for (int q = 0; q < 4; ++q) {
+                const int col = (tile << 8) + 64 * q + lane;
+                float zv[TB];
 #pragma unroll
-            for (int t = 0; t < SR_TB; ++t) zv[t] = (col < n && t < nt) ? z[(size_t)(t0 + t) * n + col] : 0.f;
+                for (int t = 0; t < TB; ++t) zv[t] = (col < n && t < nt) ? z[(size_t)(t0 + t) * n + col] : 0.f;
 #pragma unroll
-            for (int r = 0; r < SR_RR; ++r) {
-                // column 64q + lane of the tile: call q/2, word 2*(q%2) + lane/32, bit lane%32
-                const int src = (q >> 1) * SR_RR + r;
-                const uint32_t wlo = __builtin_amdgcn_readlane(bits.w[2 * (q & 1)], src);
-                const uint32_t whi = __builtin_amdgcn_readlane(bits.w[2 * (q & 1) + 1], src);
-                const uint32_t sgn = ((hi ? whi : wlo) << sh) & 0x80000000u;
+                for (int r = 0; r < RR; ++r) {
+                    // column 64q + lane of the tile: call q/2, word 2*(q%2) + lane/32, bit lane%32
+                    const int src = jj * PER + (q >> 1) * RR + r;
+                    const uint32_t wlo = __builtin_amdgcn_readlane(bits.w[2 * (q & 1)], src);
+                    const uint32_t whi = __builtin_amdgcn_readlane(bits.w[2 * (q & 1) + 1], src);
+                    // +-1.0 built from the sign bit; one multiply-add per entry (the product is exact)
+                    const float pm = __uint_as_float((((hi ? whi : wlo) << sh) & 0x80000000u) | 0x3F800000u);
 #pragma unroll
-                for (int t = 0; t < SR_TB; ++t) acc[r][t] += __uint_as_float(__float_as_uint(zv[t]) ^ sgn);
+                    for (int t = 0; t < TB; ++t) acc[r][t] = fmaf(pm, zv[t], acc[r][t]);
+                }
             }
         }
     }
 #pragma unroll
-    for (int r = 0; r < SR_RR; ++r)
+    for (int r = 0; r < RR; ++r)
 #pragma unroll
-        for (int t = 0; t < SR_TB; ++t) {
+        for (int t = 0; t < TB; ++t) {
             const float s = wave_sum(acc[r][t]);
-            if (lane == 0) part[wave][r * SR_TB + t] = s;
+            if (lane == 0) part[wave][r * TB + t] = s;
         }
     __syncthreads();
-    if (threadIdx.x < SR_RR * SR_TB) {
-        const int r = threadIdx.x / SR_TB, t = threadIdx.x % SR_TB;
+    if (threadIdx.x < RR * TB) {
+        const int r = threadIdx.x / TB, t = threadIdx.x % TB;
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < SR_WAVES; ++w) s += part[w][threadIdx.x];
@@ -234,8 +247,12 @@ hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipS
         nthreads = nthreads < 64 ? 64 : (nthreads > 1024 ? 1024 : nthreads);
         hipLaunchKernelGGL(sketch_srht_kernel, dim3(B), dim3(nthreads), bytes, s, op, z, y);
     } else if (op.ens == 1) {
-        dim3 grid((op.m + SR_RR - 1) / SR_RR, (B + SR_TB - 1) / SR_TB);
-        hipLaunchKernelGGL(sketch_rademacher_kernel, grid, dim3(SR_WAVES * 64), 0, s, op, z, B, y);
+        const int tgroups = (B + 7) / 8;
+        if ((long)((op.m + 3) / 4) * tgroups >= 256) {
+            hipLaunchKernelGGL((sketch_rademacher_kernel<4, 8>), dim3((op.m + 3) / 4, tgroups), dim3(SR_WAVES * 64), 0, s, op, z, B, y);
+        } else {
+            hipLaunchKernelGGL((sketch_rademacher_kernel<2, 8>), dim3((op.m + 1) / 2, tgroups), dim3(SR_WAVES * 64), 0, s, op, z, B, y);
+        }
     } else {
         dim3 grid((op.m + SK_WAVES - 1) / SK_WAVES, (B + SK_TB - 1) / SK_TB);
         const bool vec = (op.n & 3) == 0;   // float4 loads need 16-byte aligned rows of z
