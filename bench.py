@@ -45,6 +45,9 @@ def parse():
                     help="next-step: the sketches of step t give the supports step t+1 executes, and the recoveries of "
                          "all layers are solved in batched launches; same-step: every layer's support is recovered "
                          "just ahead of that layer's execution in the same step")
+    ap.add_argument("--sketch", choices=["per-group", "per-layer"], default="per-group",
+                    help="next-step mode: sketch the layers of a group with one launch per kind once the group's last "
+                         "layer has been issued (per-group), or every layer with its own two launches (per-layer)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     return ap.parse_args()
 
@@ -97,8 +100,10 @@ class DecodeState:
                 u = hs.bg * torch.randn((B, hs.H), generator=gen, device=dev)
                 u.scatter_add_(1, hperm, torch.randn((B, hs.kh), generator=gen, device=dev))
                 us.append(u.contiguous())
-            self.z.append(zs)
-            self.u.append(us)
+            # one tensor per step, [layers][B][n]: a layer's usage vectors are a row block of it, and the
+            # vectors of a group of layers can be sketched with one launch
+            self.z.append(torch.stack(zs))
+            self.u.append(torch.stack(us))
             self.x.append(randn((layers, B, c.d)))
             self.q.append(randn((layers, B, hs.H, hs.dh)))
         # outputs and intermediates, allocated once
@@ -141,6 +146,7 @@ class DecodeState:
 
 
 SOLVER = {"name": "omp", "iters": 12}
+SKETCH = {"per_group": True}     # next-step mode: sketch a group of layers with one launch per kind
 NEXT_GROUPS = 2     # batched recovery launches per step and kind (a group starts once its layers are sketched)
 # Layers per ordering point "layer l issued -> sketch of layer l" between the two streams; 0 = none.
 # The usage vectors of this workload are synthetic and resident, so nothing has to be waited for; an
@@ -221,6 +227,14 @@ def decode_step_pipelined(ctx, rctx, st, i, s_exec, s_rec, chunk=None, ahead=Non
     s_exec.wait_stream(s_rec)
 
 
+def sketch_group(cx, st, grp, i):
+    """The sketches of one group of layers at step i, one launch per kind (the layers' usage vectors are
+    kept until the group's last layer has been issued)."""
+    l0, l1 = grp["layers"][0], grp["layers"][-1] + 1
+    cx.cs_sketch_multi(grp["head_ops"], st.u[i][l0:l1], st.Yh_all[l0:l1])
+    cx.cs_sketch_multi(grp["ffn_ops"], st.z[i][l0:l1], st.Y_all[l0:l1])
+
+
 def recover_group(cx, st, grp, gen):
     """Batched recovery of one group of layers into support generation `gen`."""
     c, hs = st.c, st.hs
@@ -251,19 +265,22 @@ def decode_step_next(ctx, rctx, st, i, s_exec, s_rec):
         with torch.cuda.stream(s_rec):
             if sync_here:
                 s_rec.wait_event(issued)
-            rctx.cs_sketch(st.head_op[l], st.u[i][l], st.Yh_all[l])
-            rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.Y_all[l])
-            if l in last_of_group:
-                recover_group(rctx, st, last_of_group[l], nxt)
+            if SKETCH["per_group"]:
+                if l in last_of_group:
+                    sketch_group(rctx, st, last_of_group[l], i)
+                    recover_group(rctx, st, last_of_group[l], nxt)
+            else:
+                rctx.cs_sketch(st.head_op[l], st.u[i][l], st.Yh_all[l])
+                rctx.cs_sketch(st.ffn_op[l], st.z[i][l], st.Y_all[l])
+                if l in last_of_group:
+                    recover_group(rctx, st, last_of_group[l], nxt)
     s_exec.wait_stream(s_rec)
 
 
 def prime_supports(ctx, st):
     """Generation 0 of the supports, from the sketches of step 0 (before the timed region)."""
-    for l in range(st.layers):
-        ctx.cs_sketch(st.head_op[l], st.u[0][l], st.Yh_all[l])
-        ctx.cs_sketch(st.ffn_op[l], st.z[0][l], st.Y_all[l])
     for grp in st.groups:
+        sketch_group(ctx, st, grp, 0)
         recover_group(ctx, st, grp, 0)
 
 
@@ -300,7 +317,11 @@ def call_loops(ctx, st, stream):
     fn = lambda i: [recover_group(ctx, st, grp, 1) for grp in st.groups]
     time_loop(fn, 2, stream)
     raw["recover_step_batched"] = time_loop(fn, 8, stream)
+    fn = lambda i: [sketch_group(ctx, st, grp, 0) for grp in st.groups]
+    time_loop(fn, 2, stream)
+    raw["sketch_step_batched"] = time_loop(fn, 8, stream)
     per = {"attn": raw["attn"], "ffn": raw["ffn"], "recover_step_batched": raw["recover_step_batched"],
+           "sketch_step_batched": raw["sketch_step_batched"],
            "recover": 0.5 * (raw["recover_ffn"] + raw["recover_heads"]),
            "sketch": 0.5 * (raw["sketch_ffn"] + raw["sketch_heads"])}
     per.update({k: raw[k] for k in ("recover_ffn", "recover_heads", "sketch_ffn", "sketch_heads")})
@@ -465,6 +486,7 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU and the HIP library; there is no CPU fallback")
     SOLVER["name"], SOLVER["iters"] = args.solver, args.iht_iters
+    SKETCH["per_group"] = args.sketch == "per-group"
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
     rstream = torch.cuda.Stream()
@@ -547,8 +569,11 @@ def main():
     calls_per_step = {"sketch": 2 * args.layers, "recover": 2 * args.layers, "attn": args.layers, "ffn": args.layers}
     step_share = {k: per[k] * calls_per_step[k] for k in calls_per_step}
     per_layer_recover_ms = step_share["recover"]
+    per_layer_sketch_ms = step_share["sketch"]
     if args.recovery == "next-step":
         step_share["recover"] = per["recover_step_batched"]
+        if SKETCH["per_group"]:
+            step_share["sketch"] = per["sketch_step_batched"]
     kernels = {
         "attn": {"us_per_call": per["attn"] * 1e3, "active_MB": attn_bytes / 1e6,
                  "GBs": attn_bytes / (per["attn"] * 1e-3) / 1e9,
@@ -587,9 +612,11 @@ def main():
                      "frac_of_serial_step": rec_frac,
                      "frac_of_step_with_sketches": (step_share["recover"] + step_share["sketch"]) / sum(step_share.values()),
                      "ms_per_step_one_call_per_layer": per_layer_recover_ms,
+                     "sketch_ms_per_step": step_share["sketch"],
+                     "sketch_ms_per_step_one_call_per_layer": per_layer_sketch_ms,
                      "margin_pass_rate": margin_pass,
-                     "note": ("the sketches of step t give the supports step t+1 executes; a second stream sketches the "
-                              "layers and recovers %d groups of layers with one launch per group and kind; the "
+                     "note": ("the sketches of step t give the supports step t+1 executes; a second stream sketches and "
+                              "recovers %d groups of layers with one launch per group and kind; the "
                               "synthetic usage vectors are resident, so that stream is not ordered against the "
                               "execution of the same step" % len(st.groups)) if args.recovery == "next-step" else
                              "measurement and recovery run on a second stream up to 4 layers ahead of execution in the same step"},

@@ -114,6 +114,15 @@ cs_status cs_plan(cs_ctx* ctx, const cs_op* op, const cs_dict* dict);
 cs_status cs_sketch(cs_ctx* ctx, const cs_op* op, const float* z, int B, float* y);
 
 /*
+ * cs_sketch for several operators in one launch: y[j] = Phi_j z[j] (Sec. 3 / Sec. 8; Sec. 5: the
+ * sketches of a step are only needed by the next step, so the usage vectors of several layers can be
+ * kept and measured together).  z: float[n_ops][B][n] in, y: float[n_ops][B][m] out.  All operators
+ * must agree in ensemble, m and n; they differ in seed and stream_id.  ops is a host array of n_ops
+ * entries, n_ops >= 1.  The arithmetic per sketch is exactly that of cs_sketch; nothing is allocated.
+ */
+cs_status cs_sketch_multi(cs_ctx* ctx, int n_ops, const cs_op* ops, const float* z, int B, float* y);
+
+/*
  * Structured sparse recovery by block orthogonal matching pursuit over the
  * dictionary's units (Sec. 8, "orthogonal matching pursuit over a constrained
  * support dictionary"; support projection of Sec. 3 and Sec. 7 with the

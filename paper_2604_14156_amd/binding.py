@@ -16,7 +16,7 @@ CS_OK, CS_EINVAL, CS_EALIGN, CS_EILLPOSED, CS_ENOMEM, CS_EHIP = 0, -1, -2, -3, -
 CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
-EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch",
+EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch", "cs_sketch_multi",
            "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
            "cs_softmax_entropy", "cs_uds_budget")
 
@@ -49,6 +49,7 @@ def load_library(path=LIB_PATH):
     lib.cs_set_stream.argtypes = [vp, vp]
     lib.cs_plan.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict)]
     lib.cs_sketch.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, vp]
+    lib.cs_sketch_multi.argtypes = [vp, i32, ctypes.POINTER(CsOp), vp, i32, vp]
     lib.cs_recover_support.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
     lib.cs_recover_support_multi.argtypes = [vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
     lib.cs_recover_support_iht.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, i32, vp, i32, vp, vp, vp, vp]
@@ -125,6 +126,16 @@ class Context:
         if y is None:
             y = torch.empty((B, op.m), dtype=torch.float32, device=z.device)
         self._check(self.lib.cs_sketch(self._h, ctypes.byref(op), _ptr(z), B, _ptr(y)))
+        return y
+
+    def cs_sketch_multi(self, ops, z, y=None):
+        """ops: sequence of CsOp (or a ctypes array of them); z [n_ops][B][n] -> y [n_ops][B][m]."""
+        n_ops = len(ops)
+        arr = ops if isinstance(ops, ctypes.Array) else (CsOp * n_ops)(*ops)
+        B = z.shape[1]
+        if y is None:
+            y = torch.empty((n_ops, B, arr[0].m), dtype=torch.float32, device=z.device)
+        self._check(self.lib.cs_sketch_multi(self._h, n_ops, arr, _ptr(z), B, _ptr(y)))
         return y
 
     def cs_recover_support(self, op, dct, k, y, support=None, coef=None, resid=None, margin=None,

@@ -263,6 +263,30 @@ cs_status cs_sketch(cs_ctx* c, const cs_op* op, const float* z, int B, float* y)
     return CS_OK;
 }
 
+cs_status cs_sketch_multi(cs_ctx* c, int n_ops, const cs_op* ops, const float* z, int B, float* y) {
+    if (!c) return CS_EINVAL;
+    if (n_ops < 1 || n_ops > 65535) return fail(c, CS_EINVAL, "cs_sketch_multi: n_ops=%d out of range [1, 65535]", n_ops);
+    if (!ops) return fail(c, CS_EINVAL, "cs_sketch_multi: NULL operator list");
+    cs_status st;
+    for (int j = 0; j < n_ops; ++j) {
+        if ((st = check_op(c, &ops[j], "cs_sketch_multi")) != CS_OK) return st;
+        if (ops[j].ens != ops[0].ens || ops[j].m != ops[0].m || ops[j].n != ops[0].n)
+            return fail(c, CS_EINVAL, "cs_sketch_multi: operator %d differs in ensemble or shape from operator 0", j);
+    }
+    if (B < 0) return fail(c, CS_EINVAL, "cs_sketch_multi: B < 0");
+    if (B == 0) return CS_OK;
+    if (!z || !y) return fail(c, CS_EINVAL, "cs_sketch_multi: NULL buffer");
+    if (!aligned16(z) || !aligned16(y)) return fail(c, CS_EALIGN, "cs_sketch_multi: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    std::vector<OpDesc> descs((size_t)n_ops);
+    for (int j = 0; j < n_ops; ++j) descs[(size_t)j] = make_desc(ops[j]);
+    if (ops[0].ens == CS_SRHT && !sketch_srht_supported(descs[0]))
+        return fail(c, CS_EINVAL, "cs_sketch_multi: the Hadamard ensemble is limited to n <= 32768 (n=%d)", ops[0].n);
+    hipError_t e = launch_sketch_multi(descs.data(), n_ops, z, B, y, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_sketch_multi");
+    return CS_OK;
+}
+
 cs_status cs_recover_support(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k,
                              const float* y, int B,
                              int32_t* support, float* coef, float* resid_norm, float* margin) {

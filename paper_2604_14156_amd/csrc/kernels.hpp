@@ -8,6 +8,7 @@ namespace csk {
 
 // y[B][m] = Phi z[B][n]
 hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s);
+hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int B, float* y, hipStream_t s);
 // the fast transform of the Hadamard ensemble keeps the padded vector in LDS
 bool sketch_srht_supported(const OpDesc& op);
 

@@ -27,13 +27,27 @@ constexpr int SK_WAVES = 4;       // rows per workgroup (Gaussian kernel)
 
 constexpr int SR_WAVES = 16;
 
+// Several operators of one shape in a launch: blockIdx.z picks the operator, whose Philox key and
+// stream come from this table (passed by value); its vectors and sketches follow those of the
+// previous operator in z and y.
+constexpr int SK_MAX_OPS = 32;
+struct OpKeys { uint32_t k0[SK_MAX_OPS], k1[SK_MAX_OPS], stream[SK_MAX_OPS]; };
+
+__device__ __forceinline__ void pick_operator(OpDesc& op, const OpKeys& keys) {
+    const int j = blockIdx.z;
+    op.k0 = keys.k0[j]; op.k1 = keys.k1[j]; op.stream = keys.stream[j];
+}
+
 // RR rows of Phi and TB tokens per workgroup.  The kernel is a short latency chain (one Philox
 // call, one round trip for z, the reductions), so the launcher picks the smallest RR that still
 // gives every compute unit a workgroup.
 template <int RR, int TB>
 __global__ __launch_bounds__(SR_WAVES * 64)
-void sketch_rademacher_kernel(OpDesc op, const float* __restrict__ z, int B, float* __restrict__ y) {
+void sketch_rademacher_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ y) {
     __shared__ float part[SR_WAVES][RR * TB];
+    pick_operator(op, keys);
+    z += (size_t)blockIdx.z * B * op.n;
+    y += (size_t)blockIdx.z * B * op.m;
     constexpr int PER = 2 * RR;              // lanes that draw the bits of one 256-column tile
     constexpr int CH = 64 / PER;             // tiles covered by one Philox pass of the wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -102,7 +116,10 @@ void sketch_rademacher_kernel(OpDesc op, const float* __restrict__ z, int B, flo
 
 template <int TB, bool VEC>
 __global__ __launch_bounds__(SK_WAVES * 64)
-void sketch_gauss_kernel(OpDesc op, const float* __restrict__ z, int B, float* __restrict__ y) {
+void sketch_gauss_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ y) {
+    pick_operator(op, keys);
+    z += (size_t)blockIdx.z * B * op.n;
+    y += (size_t)blockIdx.z * B * op.m;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * SK_WAVES + (threadIdx.x >> 6);
     const int t0 = blockIdx.y * TB;
@@ -169,8 +186,11 @@ __device__ __forceinline__ void wht_pass(float* x, int nbits, int sh) {
 }
 
 __global__ __launch_bounds__(1024)
-void sketch_srht_kernel(OpDesc op, const float* __restrict__ z, float* __restrict__ y) {
+void sketch_srht_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ y) {
     extern __shared__ float xs[];                       // 2^nbits values at their padded positions
+    pick_operator(op, keys);
+    z += (size_t)blockIdx.z * B * op.n;
+    y += (size_t)blockIdx.z * B * op.m;
     const int npad = 1 << op.nbits;
     const int tok = blockIdx.x, tid = threadIdx.x, NT = blockDim.x;
     const float* zt = z + (size_t)tok * op.n;
@@ -230,36 +250,52 @@ constexpr int SRHT_MAX_BITS = 15;                       // 128 KB of LDS for the
 
 bool sketch_srht_supported(const OpDesc& op) { return op.nbits <= SRHT_MAX_BITS; }
 
-hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s) {
-    if (B <= 0) return hipSuccess;
-    if (op.ens == 2) {
-        if (!sketch_srht_supported(op)) return hipErrorInvalidValue;
-        const int npad = 1 << op.nbits;
-        const size_t bytes = (size_t)(npad + (npad >> 5) + 4) * 4;
-        static size_t allowed = 0;
-        if (bytes > allowed) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_srht_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-            if (e != hipSuccess) return e;
-            allowed = bytes;
+// ops[0..n_ops): operators of one ensemble and shape; z [n_ops][B][n], y [n_ops][B][m].
+hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int B, float* y, hipStream_t s) {
+    if (B <= 0 || n_ops <= 0) return hipSuccess;
+    const OpDesc& op = ops[0];
+    if (op.ens == 2 && !sketch_srht_supported(op)) return hipErrorInvalidValue;
+    for (int j0 = 0; j0 < n_ops; j0 += SK_MAX_OPS) {
+        const int nz = n_ops - j0 < SK_MAX_OPS ? n_ops - j0 : SK_MAX_OPS;
+        OpKeys keys;
+        for (int j = 0; j < SK_MAX_OPS; ++j) {
+            const OpDesc& o = ops[j0 + (j < nz ? j : 0)];
+            keys.k0[j] = o.k0; keys.k1[j] = o.k1; keys.stream[j] = o.stream;
         }
-        int nthreads = npad / 16;
-        nthreads = nthreads < 64 ? 64 : (nthreads > 1024 ? 1024 : nthreads);
-        hipLaunchKernelGGL(sketch_srht_kernel, dim3(B), dim3(nthreads), bytes, s, op, z, y);
-    } else if (op.ens == 1) {
-        const int tgroups = (B + 7) / 8;
-        if ((long)((op.m + 3) / 4) * tgroups >= 256) {
-            hipLaunchKernelGGL((sketch_rademacher_kernel<4, 8>), dim3((op.m + 3) / 4, tgroups), dim3(SR_WAVES * 64), 0, s, op, z, B, y);
+        const float* zj = z + (size_t)j0 * B * op.n;
+        float* yj = y + (size_t)j0 * B * op.m;
+        if (op.ens == 2) {
+            const int npad = 1 << op.nbits;
+            const size_t bytes = (size_t)(npad + (npad >> 5) + 4) * 4;
+            static size_t allowed = 0;
+            if (bytes > allowed) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_srht_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+                if (e != hipSuccess) return e;
+                allowed = bytes;
+            }
+            int nthreads = npad / 16;
+            nthreads = nthreads < 64 ? 64 : (nthreads > 1024 ? 1024 : nthreads);
+            hipLaunchKernelGGL(sketch_srht_kernel, dim3(B, 1, nz), dim3(nthreads), bytes, s, op, keys, zj, B, yj);
+        } else if (op.ens == 1) {
+            const int tgroups = (B + 7) / 8;
+            if ((long)((op.m + 3) / 4) * tgroups * nz >= 256) {
+                hipLaunchKernelGGL((sketch_rademacher_kernel<4, 8>), dim3((op.m + 3) / 4, tgroups, nz), dim3(SR_WAVES * 64), 0, s, op, keys, zj, B, yj);
+            } else {
+                hipLaunchKernelGGL((sketch_rademacher_kernel<2, 8>), dim3((op.m + 1) / 2, tgroups, nz), dim3(SR_WAVES * 64), 0, s, op, keys, zj, B, yj);
+            }
         } else {
-            hipLaunchKernelGGL((sketch_rademacher_kernel<2, 8>), dim3((op.m + 1) / 2, tgroups), dim3(SR_WAVES * 64), 0, s, op, z, B, y);
+            dim3 grid((op.m + SK_WAVES - 1) / SK_WAVES, (B + SK_TB - 1) / SK_TB, nz);
+            const bool vec = (op.n & 3) == 0;   // float4 loads need 16-byte aligned rows of z
+            if (vec) hipLaunchKernelGGL((sketch_gauss_kernel<SK_TB, true>), grid, dim3(SK_WAVES * 64), 0, s, op, keys, zj, B, yj);
+            else hipLaunchKernelGGL((sketch_gauss_kernel<SK_TB, false>), grid, dim3(SK_WAVES * 64), 0, s, op, keys, zj, B, yj);
         }
-    } else {
-        dim3 grid((op.m + SK_WAVES - 1) / SK_WAVES, (B + SK_TB - 1) / SK_TB);
-        const bool vec = (op.n & 3) == 0;   // float4 loads need 16-byte aligned rows of z
-        if (vec) hipLaunchKernelGGL((sketch_gauss_kernel<SK_TB, true>), grid, dim3(SK_WAVES * 64), 0, s, op, z, B, y);
-        else hipLaunchKernelGGL((sketch_gauss_kernel<SK_TB, false>), grid, dim3(SK_WAVES * 64), 0, s, op, z, B, y);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s) {
+    return launch_sketch_multi(&op, 1, z, B, y, s);
 }
 
 }  // namespace csk

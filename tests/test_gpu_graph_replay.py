@@ -102,7 +102,7 @@ def test_pipelined_step_graph_replays_match_eager():
 
 def test_next_step_graph_with_batched_recovery_replays_match_eager():
     """The other step shape: execution reads one generation of supports while the second stream sketches
-    all layers and recovers them with one launch per kind into the other generation."""
+    all layers with one launch per kind and recovers them with one launch per kind into the other generation."""
     dev = "cuda:0"
     c = wl.scaled(wl.CFG2, d=512, G=24, k=6, m=64)
     hs = wl.scaled(wl.CFG3_HEADS, L=200)
@@ -157,10 +157,9 @@ def test_next_step_graph_with_batched_recovery_replays_match_eager():
                 with torch.cuda.stream(s_exec):
                     ctx.cs_head_attn(q[l], K[l], V[l], Hh[0][l], o[l])
                     ctx.cs_block_ffn(Wg[l], Wu[l], Wd[l], x[l], S[0][l], False, out[l])
-                with torch.cuda.stream(s_rec):
-                    rctx.cs_sketch(hop[l], u[l], Yh[l])
-                    rctx.cs_sketch(fop[l], z[l], Y[l])
             with torch.cuda.stream(s_rec):
+                rctx.cs_sketch_multi(hop, u, Yh)
+                rctx.cs_sketch_multi(fop, z, Y)
                 recover_all(rctx, 1)
             s_exec.wait_stream(s_rec)
 

@@ -422,3 +422,34 @@ def test_multi_operator_heads_generic_sizes_and_errors(cs):
     with pytest.raises(binding.CsError) as e:
         cs.cs_recover_support_multi(bad, dcts[:2], hs.kh, Y[:2])
     assert e.value.status == binding.CS_EINVAL
+
+
+@pytest.mark.parametrize("ens", [wl.GAUSS, wl.RADEMACHER, wl.SRHT])
+@pytest.mark.parametrize("m,n,B,n_ops", [(256, 11008, 16, 3), (16, 32, 16, 16), (33, 1001, 9, 35), (5, 130, 1, 2)])
+def test_multi_operator_sketch_equals_separate_calls(cs, ens, m, n, B, n_ops):
+    """One launch for the operators of several layers (more than one launch's worth at 35): the same
+    bits as one cs_sketch call per operator, and the oracle's values for the last operator."""
+    rng = wl.rng_for(77 + m + n_ops)
+    z = rng.standard_normal((n_ops, B, n)).astype(np.float32)
+    ops = [binding.make_op(ens, 900 + 13 * j, 5 + j, m, n) for j in range(n_ops)]
+    zd = dev_f32(z)
+    Y = cs.cs_sketch_multi(ops, zd)
+    assert Y.shape == (n_ops, B, m)
+    for j in range(n_ops):
+        assert torch.equal(Y[j], cs.cs_sketch(ops[j], zd[j].clone()))     # a copy: rows of an odd-sized stack are not 16-byte aligned
+    want = oracle.sketch(ens, 900 + 13 * (n_ops - 1), 5 + n_ops - 1, m, z[-1])
+    got = host(Y[-1])
+    for t in range(B):
+        assert rel_err(got[t], want[t]) <= 1e-5
+
+
+def test_multi_operator_sketch_errors(cs):
+    ops = [binding.make_op(wl.RADEMACHER, 1, j, 16, 64) for j in range(2)]
+    z = dev_f32(np.zeros((2, 1, 64), dtype=np.float32))
+    bad = [ops[0], binding.make_op(wl.RADEMACHER, 1, 1, 16, 128)]
+    with pytest.raises(binding.CsError):
+        cs.cs_sketch_multi(bad, z)
+    mixed = [ops[0], binding.make_op(wl.GAUSS, 1, 1, 16, 64)]
+    with pytest.raises(binding.CsError):
+        cs.cs_sketch_multi(mixed, z)
+    assert cs.cs_sketch_multi(ops, dev_f32(np.zeros((2, 0, 64), dtype=np.float32))).shape == (2, 0, 16)
