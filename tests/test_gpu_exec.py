@@ -185,6 +185,28 @@ def test_attention_decode_shape_full_size(cs):
         assert np.all(out[b, pruned] == 0.0)
 
 
+@pytest.mark.parametrize("B,H,L,dh,kh", [(8, 32, 2500, 128, 16), (16, 16, 5001, 64, 8), (24, 8, 1030, 256, 6)])
+def test_attention_wide_workgroups_ragged_cache(cs, B, H, L, dh, kh):
+    """Batches large enough for the 16-wave workgroup shape, cache lengths that are not a multiple of a
+    workgroup's pass; oracle on sampled (sequence, head) pairs, zeros on every pruned head."""
+    gen = torch.Generator(device="cuda:0").manual_seed(L + dh)
+    q = torch.randn((B, H, dh), generator=gen, device="cuda:0").to(torch.bfloat16)
+    K = torch.randn((B, H, L, dh), generator=gen, device="cuda:0").to(torch.bfloat16)
+    V = torch.randn((B, H, L, dh), generator=gen, device="cuda:0").to(torch.bfloat16)
+    heads = wl.random_supports(wl.rng_for(L), H, kh, B)
+    out = host(cs.cs_head_attn(q, K, V, dev_i32(heads)))
+    hq = host(q)
+    for b in (0, B // 2, B - 1):
+        for h in (int(heads[b][0]), int(heads[b][kh // 2]), int(heads[b][-1])):
+            want = oracle.head_attn(hq[b:b + 1, h:h + 1], host(K[b:b + 1, h:h + 1]), host(V[b:b + 1, h:h + 1]),
+                                    np.array([[0]]))[0, 0]
+            assert rel_err(out[b, h], want) <= 2e-2, (b, h)
+    for b in range(B):
+        pruned = sorted(set(range(H)) - set(heads[b].tolist()))
+        assert np.all(out[b, pruned] == 0.0)
+        assert np.all(np.abs(out[b, heads[b]]).max(axis=1) > 0.0)
+
+
 def test_attention_sharp_scores_do_not_overflow(cs):
     rng = wl.rng_for(3500)
     q, K, V = wl.make_kv(rng, 1, 2, 200, 128)
