@@ -480,7 +480,7 @@ def extra_measurements(ctx, st, wl, stream, binding_mod):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: this library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
     from paper_2604_14156_amd import binding, workloads as wl
     if not torch.cuda.is_available():

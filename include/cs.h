@@ -124,9 +124,9 @@ cs_status cs_sketch_multi(cs_ctx* ctx, int n_ops, const cs_op* ops, const float*
 
 /*
  * Structured sparse recovery by block orthogonal matching pursuit over the
- * dictionary's units (Sec. 8, "orthogonal matching pursuit over a constrained
- * support dictionary"; support projection of Sec. 3 and Sec. 7 with the
- * admissible family "exactly k units").  For each of the B sketches:
+ * dictionary's units (Sec. 8 lists greedy pursuit restricted to a dictionary of
+ * admissible supports among the per-token solvers; support projection of Sec. 3
+ * and Sec. 7 with the admissible family "exactly k units").  For each of the B sketches:
  *   k rounds of { score every unselected unit; take the best (ties -> smaller
  *   index); least-squares refit of all selected coefficients; new residual }.
  * Score of unit g: with a dictionary, the energy of the residual in the unit's
@@ -164,8 +164,8 @@ cs_status cs_recover_support_multi(cs_ctx* ctx, int n_ops, const cs_op* ops, con
 
 /*
  * Structured sparse recovery by block iterative hard thresholding: the second cheap
- * solver the paper names (Sec. 8, "projected proximal methods with a small fixed
- * number of iterations"), with the projection onto exactly k units (Sec. 7).
+ * solver the paper names (Sec. 8: proximal steps followed by a projection, run for a
+ * small fixed number of iterations), with the projection onto exactly k units (Sec. 7).
  * `iters` rounds of { g = M^T (y - M alpha); mu = ||g_S||^2 / ||M g_S||^2 on the
  * current support S (first round: the k units with most gradient energy);
  * p = alpha + mu g; S = the k units with the largest energy of p (ties -> smaller

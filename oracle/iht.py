@@ -1,8 +1,8 @@
 """Structured sparse recovery by projected gradient steps: block iterative hard
 thresholding (oracle, fp64).
 
-The paper names "projected proximal methods with a small fixed number of
-iterations" as the second cheap solver next to greedy pursuit (Sec. 8), with the
+The paper names proximal steps followed by a projection, run for a small fixed
+number of iterations, as the second cheap solver next to greedy pursuit (Sec. 8), with the
 projection onto the admissible supports of Sec. 7 (here: exactly k units).  The
 iteration is the classical normalised hard-thresholding scheme:
 

@@ -1,8 +1,8 @@
 """Warm-started (incremental) structured recovery (oracle, fp64).
 
 The paper's token-adaptive loop (Sec. 5) regularises the per-token recovery towards
-the previous token's solution, Omega_temp = gamma ||alpha_t - alpha_{t-1}||^2 "or a
-support-change penalty", and argues (Sec. 10, proposition on incremental
+the previous token's solution, Omega_temp = gamma ||alpha_t - alpha_{t-1}||^2 (a penalty
+on the change of support is allowed instead), and argues (Sec. 10, proposition on incremental
 token-adaptive recovery) that when the support drifts by Delta_t = |S_t ^ S_{t-1}|
 units only the changed part has to be identified, from about
 Delta_t log(e G / Delta_t) measurements.  It prints no procedure.  The one taken

@@ -2,8 +2,8 @@
 
 The paper models the usage vector as u ~ Psi alpha with one group of
 coefficients per structured unit (Sec. 3), senses it with M = A Psi (Sec. 9),
-and names "orthogonal matching pursuit over a constrained support dictionary"
-as the per-token solver (Sec. 8); the support is then projected onto the
+and lists greedy pursuit restricted to a dictionary of admissible supports
+among the per-token solvers (Sec. 8); the support is then projected onto the
 admissible family (Sec. 3, Sec. 7).  Here the admissible family is "exactly k
 units", and the greedy rule is the classical one:
 

@@ -1,5 +1,5 @@
 // Structured sparse recovery by block iterative hard thresholding (paper Sec. 8:
-// "projected proximal methods with a small fixed number of iterations", projection
+// proximal steps followed by a projection, a small fixed number of iterations; projection
 // onto exactly k units, Sec. 7).  One workgroup per sketch, one atom per unit.
 //
 // Everything runs in the Gram domain (G = M^T M in LDS, c0 = M^T y): the gradient is
