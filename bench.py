@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--counter-pass", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (calibration), then every call once per "
                          "layer on one stream, no graphs, no timing")
+    ap.add_argument("--prefill-pass", action="store_true",
+                    help="run only the shared-support FFN at the two prompt shapes (configs 4 and 5) and print their "
+                         "timings; the command the prefill profiles under profiles/ are taken from")
     ap.add_argument("--solver", choices=["omp", "iht"], default="omp",
                     help="recovery of the FFN block supports: block-OMP (default) or block iterative hard thresholding")
     ap.add_argument("--iht-iters", type=int, default=12)
@@ -399,6 +402,33 @@ def time_loop(fn, iters, stream):
     return a.elapsed_time(b) / iters          # ms per iteration
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def prefill_measurements(ctx, wl, stream, iters=10):
+    """Shared-support FFN (one support for all rows) at the two prompt shapes: config 4 (T = 2048 rows,
+    d = 8192, 112 of 448 blocks) and config 5 (2048 kept tokens, d = 4096, 43 of 172 blocks).  The call is a
+    dense contraction over the gathered blocks, 6 T |S| b d flop, priced against the bf16 matrix peak."""
+    dev = "cuda:0"
+    res = {}
+    for name, c, T in (("cfg4", wl.CFG4, 2048), ("cfg5", wl.CFG2, wl.CFG5_TOK["k_tok"])):
+        gen = torch.Generator(device=dev).manual_seed(4000 if name == "cfg4" else 5000)
+        Wg, Wu = (torch.randn((c.G, c.b, c.d), generator=gen, device=dev).mul_(c.wstd).to(torch.bfloat16) for _ in range(2))
+        Wd = torch.randn((c.G, c.d, c.b), generator=gen, device=dev).mul_(c.wstd).to(torch.bfloat16)
+        x = torch.randn((T, c.d), generator=gen, device=dev).to(torch.bfloat16)
+        sup = torch.rand((c.G,), generator=gen, device=dev).argsort()[:c.k].sort().values.to(torch.int32).contiguous()
+        out = torch.empty_like(x)
+        fn = lambda i: ctx.cs_block_ffn(Wg, Wu, Wd, x, sup, True, out)
+        time_loop(fn, 3, stream)
+        ms = time_loop(fn, iters, stream)
+        flop = 6.0 * T * c.k * c.b * c.d
+        res["prefill_ffn_" + name] = {"us": ms * 1e3, "rows": T, "d": c.d, "blocks": "%d/%d" % (c.k, c.G),
+                                      "TFLOP": flop / 1e12, "TFLOPs": flop / (ms * 1e-3) / 1e12,
+                                      "mfma_frac": flop / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        del Wg, Wu, Wd, x, out
+    return res
+
+
 def extra_measurements(ctx, st, wl, stream, binding_mod):
     """Single-layer side figures: FFN at batch 1/8/64 on rotating layers, recovery and sketch per call."""
     c, hs = st.c, st.hs
@@ -493,6 +523,12 @@ def main():
     ctx = binding.Context(device=0, stream=stream)
     rctx = binding.Context(device=0, stream=rstream)
     nsteps = args.steps + args.warmup
+    if args.prefill_pass:
+        with torch.cuda.stream(stream):
+            res = prefill_measurements(ctx, wl, stream)
+        res["prefill_pass"] = True
+        print(json.dumps(res))
+        return
     with torch.cuda.stream(stream):
         st = DecodeState(ctx, wl, binding, args.layers, args.batch, nsteps)
         for l in range(args.layers):               # the recovery context keeps its own plans
@@ -562,6 +598,8 @@ def main():
         margin_pass = float((st.margin > 1e-3).float().mean())
         ffn_bytes = union_mean * 3 * c.b * c.d * 2
         extra = None if args.no_extra else extra_measurements(ctx, st, wl, stream, binding)
+        if extra is not None:
+            extra.update(prefill_measurements(ctx, wl, stream))
         torch.cuda.synchronize()
 
     ms_per_step = wall * 1e3 / args.steps
