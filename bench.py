@@ -504,6 +504,15 @@ def extra_measurements(ctx, st, wl, stream, binding_mod):
     fn = lambda i: ctx.cs_joint_select_coupled(tok_op, y_tok, t["k_tok"], st.ffn_op[i % nl], st.ffn_dict[i % nl], Y_ch, c.k)
     time_loop(fn, 4, stream)
     res["joint_select_coupled_us_per_call"] = time_loop(fn, 16, stream) * 1e3
+    # what plain streaming reaches on this device, for context beside the published peak: a 1 GiB
+    # device-to-device copy (bytes read + bytes written)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    fn = lambda i: dst.copy_(src)
+    time_loop(fn, 2, stream)
+    ms = time_loop(fn, 10, stream)
+    res["plain_copy_1GiB"] = {"us": ms * 1e3, "GBs_read_plus_write": 2 * (1 << 30) / (ms * 1e-3) / 1e9}
+    del src, dst
     return res
 
 
