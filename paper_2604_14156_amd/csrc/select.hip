@@ -5,8 +5,8 @@
 
 namespace csk {
 
-// One thread per column (Rademacher) or per group of four columns (Gaussian);
-// rows are visited in ascending order.
+// Hadamard ensemble: one thread per column; Gaussian ensemble: one thread per group of four columns
+// (one Philox call); rows are visited in ascending order.
 __global__ void backproject_kernel(OpDesc op, const float* __restrict__ y, float* __restrict__ p) {
     extern __shared__ float ys[];
     for (int i = threadIdx.x; i < op.m; i += blockDim.x) ys[i] = y[i];
@@ -20,16 +20,6 @@ __global__ void backproject_kernel(OpDesc op, const float* __restrict__ y, float
         float acc = 0.f;
         for (int i = 0; i < op.m; ++i) {
             const uint32_t sgn = ((__popc(srht_row(key, (uint32_t)i) & (uint32_t)t) ^ d) & 1u) << 31;
-            acc += __uint_as_float(__float_as_uint(ys[i]) ^ sgn);
-        }
-        p[t] = acc * op.scale;
-    } else if (op.ens == 1) {
-        if (t >= op.n) return;
-        const uint32_t cg = (uint32_t)t >> 7, word = ((uint32_t)t & 127u) >> 5, bit = (uint32_t)t & 31u;
-        float acc = 0.f;
-        for (int i = 0; i < op.m; ++i) {
-            const u32x4 b = rademacher_bits(op, (uint32_t)i, cg);
-            const uint32_t sgn = ((b.w[word] >> bit) & 1u) << 31;
             acc += __uint_as_float(__float_as_uint(ys[i]) ^ sgn);
         }
         p[t] = acc * op.scale;
@@ -47,7 +37,48 @@ __global__ void backproject_kernel(OpDesc op, const float* __restrict__ y, float
     }
 }
 
+// Rademacher ensemble: one Philox call gives the signs of 128 columns of a row, so a workgroup owns a
+// group of 128 columns and draws every (row, group) word once into LDS; thread (q, c) then sums the
+// rows of quarter q of each row block for column c in ascending order, and the four quarter sums are
+// added in a fixed order.
+constexpr int BP_THREADS = 512;
+constexpr int BP_ROWS = 1024;                 // rows per block: 16 KB of sign words + 4 KB of y
+__global__ __launch_bounds__(BP_THREADS)
+void backproject_rademacher_kernel(OpDesc op, const float* __restrict__ y, float* __restrict__ p) {
+    __shared__ uint32_t bits[BP_ROWS][4];
+    __shared__ float ys[BP_ROWS];
+    __shared__ float quarter[4][128];
+    const int tid = threadIdx.x, c = tid & 127, q = tid >> 7;
+    const uint32_t cg = blockIdx.x;
+    const int word = c >> 5, bit = c & 31;
+    float acc = 0.f;
+    for (int r0 = 0; r0 < op.m; r0 += BP_ROWS) {
+        const int nr = min(BP_ROWS, op.m - r0);
+        for (int i = tid; i < nr; i += BP_THREADS) {
+            const u32x4 b = rademacher_bits(op, (uint32_t)(r0 + i), cg);
+            bits[i][0] = b.w[0]; bits[i][1] = b.w[1]; bits[i][2] = b.w[2]; bits[i][3] = b.w[3];
+            ys[i] = y[r0 + i];
+        }
+        __syncthreads();
+        const int per = (nr + 3) >> 2;
+        const int i1 = min(nr, (q + 1) * per);
+        for (int i = q * per; i < i1; ++i) {
+            const uint32_t sgn = ((bits[i][word] >> bit) & 1u) << 31;
+            acc += __uint_as_float(__float_as_uint(ys[i]) ^ sgn);
+        }
+        __syncthreads();
+    }
+    quarter[q][c] = acc;
+    __syncthreads();
+    const int col = (int)cg * 128 + c;
+    if (q == 0 && col < op.n) p[col] = (((quarter[0][c] + quarter[1][c]) + quarter[2][c]) + quarter[3][c]) * op.scale;
+}
+
 hipError_t launch_backproject(const OpDesc& op, const float* y, float* p, hipStream_t s) {
+    if (op.ens == 1) {
+        hipLaunchKernelGGL(backproject_rademacher_kernel, dim3((op.n + 127) / 128), dim3(BP_THREADS), 0, s, op, y, p);
+        return hipGetLastError();
+    }
     const int items = op.ens != 0 ? op.n : (op.n + 3) / 4;
     const int block = 64;                    // many small workgroups: the row loop is long
     hipLaunchKernelGGL(backproject_kernel, dim3((items + block - 1) / block), dim3(block),
@@ -71,6 +102,7 @@ __global__ __launch_bounds__(TK_THREADS)
 void topk_kernel(const float* __restrict__ scores, int n, int k, int32_t* __restrict__ out) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh_prefix, sh_need;
+    __shared__ uint32_t wtot[4];
     __shared__ uint32_t wsum_gt[TK_THREADS / 64], wsum_eq[TK_THREADS / 64];
     __shared__ uint32_t base_gt, base_eq;
     const int tid = threadIdx.x;
@@ -85,15 +117,29 @@ void topk_kernel(const float* __restrict__ scores, int n, int k, int32_t* __rest
             if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (tid == 0) {
-            uint32_t left = need;
-            int bin = 255;
-            for (; bin > 0; --bin) {
-                if (hist[bin] >= left) break;
-                left -= hist[bin];
+        // the bin that holds the need-th largest of the candidates: bins are scanned from the top by a
+        // suffix sum over the 256 counts (4 waves), exactly one bin has "at least need at or above it,
+        // fewer than need above it"
+        uint32_t h = 0, sfx = 0;
+        if (tid < 256) {
+            h = hist[tid];
+            sfx = h;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t o = __shfl_down(sfx, off, 64);
+                if ((tid & 63) + off < 64) sfx += o;
             }
-            sh_prefix = prefix | ((uint32_t)bin << shift);
-            sh_need = left;                 // how many are still wanted inside this bin
+            if ((tid & 63) == 0) wtot[tid >> 6] = sfx;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t above = 0;
+            for (int w = (tid >> 6) + 1; w < 4; ++w) above += wtot[w];
+            const uint32_t at_or_above = sfx + above, strictly_above = at_or_above - h;
+            if (at_or_above >= need && strictly_above < need) {
+                sh_prefix = prefix | ((uint32_t)tid << shift);
+                sh_need = need - strictly_above;      // how many are still wanted inside this bin
+            }
         }
         __syncthreads();
         prefix = sh_prefix;
