@@ -198,6 +198,10 @@ void ffn_gemm_kernel(GemmArgs a) {
 // Fragment reads for the next k-step are spread between the multiplies of the current one.
 // ---------------------------------------------------------------------------
 constexpr int GW_BM = 256, GW_BN = 256, GW_BK = 32;
+#ifndef CS_GW_MIN_WGS
+#define CS_GW_MIN_WGS 150
+#endif
+constexpr int GW_MIN_WGS = CS_GW_MIN_WGS;              // fewer wide workgroups than this: use the 128 x 128 tiles
 constexpr int GW_STAGE = (GW_BM + GW_BN) * 4;          // 16-byte entries per stage
 constexpr int GW_MAX_BLOCKS = 4096;                    // longest gathered list the down product keeps in LDS
 
@@ -492,9 +496,13 @@ hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s) {
         hipLaunchKernelGGL(ffn_splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                            g.partial, GM_SPLITS, n, g.out);
     } else if (a.T >= 512 && (a.d % GW_BK) == 0 && nb_max <= GW_MAX_BLOCKS) {
-        const int mt = (a.T + GW_BM - 1) / GW_BM;
-        hipLaunchKernelGGL((ffn_gemm_wide_kernel<0>), dim3((nb_max + 1) / 2, mt), dim3(GM_THREADS), 0, s, g);
-        hipLaunchKernelGGL((ffn_gemm_wide_kernel<1>), dim3((a.d + GW_BN - 1) / GW_BN, mt), dim3(GM_THREADS), 0, s, g);
+        // per product: the wide tiles only when they give the chip enough workgroups, else the 128 x 128 ones
+        const int mt = (a.T + GW_BM - 1) / GW_BM, mtn = (a.T + GM_BM - 1) / GM_BM;
+        const int w0 = (nb_max + 1) / 2, w1 = (a.d + GW_BN - 1) / GW_BN;
+        if (w0 * mt >= GW_MIN_WGS) hipLaunchKernelGGL((ffn_gemm_wide_kernel<0>), dim3(w0, mt), dim3(GM_THREADS), 0, s, g);
+        else hipLaunchKernelGGL((ffn_gemm_kernel<0, GM_BM, false>), dim3(nb_max, mtn), dim3(GM_THREADS), 0, s, g);
+        if (w1 * mt >= GW_MIN_WGS) hipLaunchKernelGGL((ffn_gemm_wide_kernel<1>), dim3(w1, mt), dim3(GM_THREADS), 0, s, g);
+        else hipLaunchKernelGGL((ffn_gemm_kernel<1, GM_BM, false>), dim3(nt, mtn), dim3(GM_THREADS), 0, s, g);
     } else {
         const int mt = (a.T + GM_BM - 1) / GM_BM;
         hipLaunchKernelGGL((ffn_gemm_kernel<0, GM_BM, false>), dim3(nb_max, mt), dim3(GM_THREADS), 0, s, g);

@@ -74,6 +74,28 @@ def test_ffn_prefill_shape_full_size(cs):
         assert rel_err(got[i], want[i]) <= 2e-2, (rows[i], rel_err(got[i], want[i]))
 
 
+@pytest.mark.parametrize("T,shared,G,k,d", [(2100, True, 40, 35, 4160), (2052, False, 40, 9, 4128), (1300, True, 64, 63, 2080)])
+def test_ffn_wide_tiles_ragged_shapes(cs, T, shared, G, k, d):
+    """Shapes large enough for the 256 x 256 tiles on at least one of the two products, with a ragged last
+    row tile, an odd number of blocks, an output width that is no multiple of the tile, and (second case)
+    per-row supports; oracle on sampled rows, among them the last ones."""
+    gen = torch.Generator(device="cuda:0").manual_seed(T + d)
+    b = 64
+    Wg, Wu = (torch.randn((G, b, d), generator=gen, device="cuda:0").mul_(0.03).to(torch.bfloat16) for _ in range(2))
+    Wd = torch.randn((G, d, b), generator=gen, device="cuda:0").mul_(0.03).to(torch.bfloat16)
+    x = torch.randn((T, d), generator=gen, device="cuda:0").to(torch.bfloat16)
+    rng = wl.rng_for(T + d)
+    sup = wl.random_supports(rng, G, k, 1)[0] if shared else wl.random_supports(rng, G, k, T)
+    out = cs.cs_block_ffn(Wg, Wu, Wd, x, dev_i32(sup), shared)
+    torch.cuda.synchronize()
+    rows = [0, 255, 256, T // 2, T - 37, T - 2, T - 1]
+    hWg, hWu, hWd = host(Wg), host(Wu), host(Wd)
+    got = host(out[rows])
+    for i, r in enumerate(rows):
+        want = oracle.block_ffn(hWg, hWu, hWd, host(x[r:r + 1]), sup if shared else sup[r])[0]
+        assert rel_err(got[i], want) <= 2e-2, (r, rel_err(got[i], want))
+
+
 def test_joint_prompt_shape_gather_and_ffn(cs):
     """Kept-token gather followed by the shared-support FFN (joint selection workload), sampled rows."""
     c = wl.CFG2
