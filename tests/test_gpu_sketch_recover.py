@@ -453,3 +453,40 @@ def test_multi_operator_sketch_errors(cs):
     with pytest.raises(binding.CsError):
         cs.cs_sketch_multi(mixed, z)
     assert cs.cs_sketch_multi(ops, dev_f32(np.zeros((2, 0, 64), dtype=np.float32))).shape == (2, 0, 16)
+
+
+def test_group_of_layers_full_size_sketch_and_recovery(cs):
+    """The launch configuration of the decode benchmark: 16 layers x 16 tokens per launch at the FFN shape.
+    Sketches and supports equal those of one call per layer; oracle on sampled (layer, token) pairs."""
+    c = wl.CFG2
+    seed = 8300
+    rng = wl.rng_for(seed)
+    n_ops, B = 16, 16
+    ops, dcts, psis, zs = [], [], [], []
+    for j in range(n_ops):
+        pi, psi = wl.make_profiles(rng, c.G, c.b)
+        z, _ = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
+        psi_dev = dev_f32(psi)
+        psis.append(psi_dev)
+        zs.append(z.astype(np.float32))
+        ops.append(binding.make_op(c.ens, seed, 2 * j, c.m, c.n))
+        dcts.append(binding.make_dict(psi_dev, c.G, c.b, 1))
+        cs.cs_plan(ops[j], dcts[j], psi_dev)
+    Z = dev_f32(np.stack(zs))
+    Y = cs.cs_sketch_multi(ops, Z)
+    sup, _, _, margin = cs.cs_recover_support_multi(ops, dcts, c.k, Y, want_coef=False, want_resid=False)
+    for j in (0, 7, 15):
+        yj = cs.cs_sketch(ops[j], Z[j])
+        assert torch.equal(Y[j], yj)
+        s1 = cs.cs_recover_support(ops[j], dcts[j], c.k, yj, want_coef=False, want_resid=False)[0]
+        assert torch.equal(sup[j], s1)
+    hs_, exact = host(sup), 0
+    for j, t in ((0, 0), (7, 5), (15, 15)):
+        want_y = oracle.sketch(c.ens, seed, 2 * j, c.m, zs[j][t:t + 1])[0]
+        assert rel_err(host(Y[j, t]), want_y) <= 1e-5
+        M = oracle.effective_matrix(c.ens, seed, 2 * j, c.m, c.n, c.G, c.b, 1, host(psis[j]).reshape(c.G, c.b, 1))
+        rec = oracle.block_omp(M, want_y, c.G, 1, c.k, True)
+        if rec["margin"] > MARGIN:
+            assert list(hs_[j, t]) == list(rec["support"])
+            exact += 1
+    assert exact >= 1
