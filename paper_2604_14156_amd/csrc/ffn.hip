@@ -177,7 +177,7 @@ template <int NS>
 __global__ __launch_bounds__(FD_THREADS)
 void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
                      const uint16_t* __restrict__ x, int T, const int32_t* __restrict__ support, int k, int shared,
-                     uint16_t* __restrict__ hbuf, int* __restrict__ sync) {
+                     uint16_t* __restrict__ hbuf, uint16_t* __restrict__ list_out, int* __restrict__ sync) {
     __shared__ uint32_t mask[FD_MAXG];
     __shared__ uint16_t ulist[FD_MAXG];
     __shared__ int wcount[FD_WAVES];
@@ -202,6 +202,11 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     int t_first = 0;
     if (tid == 0) t_first = atomicAdd(&sync[0], 1);   // result not needed before the list is built
     const int nblocks = build_block_list<FD_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
+    // the down kernel takes the list from here instead of building it again: [0] = count, then the blocks
+    if (blockIdx.x == 0) {
+        if (tid == 0) list_out[0] = (uint16_t)nblocks;
+        for (int i = tid; i < nblocks; i += FD_THREADS) list_out[1 + i] = ulist[i];
+    }
     const int cpb = b >> 3;                           // 8-channel chunks per block
     const int nitems = nblocks * cpb;
     if (tid == 0) { ticket[0] = blockIdx.x; ticket[1] = (int)gridDim.x + t_first; }
@@ -273,17 +278,18 @@ constexpr int DN_UB = 6;                              // blocks in flight per wa
 
 __global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
-                   int T, const int32_t* __restrict__ support, int k, int shared, uint16_t* __restrict__ out,
+                   int T, const uint16_t* __restrict__ list_in, uint16_t* __restrict__ out,
                    int* __restrict__ sync) {
-    __shared__ uint32_t mask[FD_MAXG];
     __shared__ uint16_t ulist[FD_MAXG];
-    __shared__ int wcount[DN_WAVES];
     __shared__ float red[DN_WAVES][256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ int ticket[2];
     int t_first = 0;
     if (tid == 0) t_first = atomicAdd(&sync[2], 1);
-    const int nblocks = build_block_list<DN_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
+    // the list of used blocks, written by the gate/up kernel of the same call
+    // (G entries are fetched whatever the count says, so that both loads are in flight together)
+    for (int i = tid; i < G; i += DN_WAVES * 64) ulist[i] = list_in[1 + i];
+    const int nblocks = min((int)list_in[0], G);
     const int ln = lane & 15, kg = lane >> 4;
     const bool tok_ok = ln < T;                       // rows of the hidden-value operand beyond T are zero
     const int ksteps = b >> 5;                        // 32 channels per matrix instruction
@@ -352,6 +358,7 @@ static bool mfma_decode_ok(const FfnArgs& a) {
 
 static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(a.scratch);
+    uint16_t* list = hbuf + (size_t)a.G * 16 * a.b;   // count + used blocks, handed from the first kernel to the second
     const int ns = gateup_steps(a.d);
     const int cpb = a.b / 8;
     const int union_max = a.shared ? a.k : (a.T * a.k < a.G ? a.T * a.k : a.G);
@@ -359,14 +366,14 @@ static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     if (grid > 256) grid = 256;                       // one workgroup of 16 waves per compute unit
     if (grid < 1) grid = 1;
 #define CS_GU(NSV) hipLaunchKernelGGL((ffn_gateup_mfma<NSV>), dim3(grid), dim3(FD_THREADS), 0, s, \
-        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf, \
+        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf, list, \
         reinterpret_cast<int*>(a.sync))
     if (ns <= 2) CS_GU(2); else if (ns <= 4) CS_GU(4); else if (ns <= 8) CS_GU(8); else CS_GU(16);
 #undef CS_GU
     int dgrid = (a.d + 15) / 16;
     if (dgrid > 256) dgrid = 256;
     hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), 0, s,
-                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, a.support, a.k, a.shared, (uint16_t*)a.out,
+                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, list, (uint16_t*)a.out,
                        reinterpret_cast<int*>(a.sync));
     return hipGetLastError();
 }
@@ -385,7 +392,7 @@ hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s) {
 }
 
 size_t ffn_scratch_bytes(const FfnArgs& a) {
-    if (mfma_decode_ok(a)) return (size_t)a.G * 16 * a.b * sizeof(uint16_t);
+    if (mfma_decode_ok(a)) return ((size_t)a.G * 16 * a.b + FD_MAXG + 8) * sizeof(uint16_t);
     if (ffn_gemm_ok(a)) return ffn_gemm_scratch_bytes(a);
     return (size_t)a.T * a.k * a.b * sizeof(float);
 }
