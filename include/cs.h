@@ -118,7 +118,9 @@ cs_status cs_sketch(cs_ctx* ctx, const cs_op* op, const float* z, int B, float* 
  * sketches of a step are only needed by the next step, so the usage vectors of several layers can be
  * kept and measured together).  z: float[n_ops][B][n] in, y: float[n_ops][B][m] out.  All operators
  * must agree in ensemble, m and n; they differ in seed and stream_id.  ops is a host array of n_ops
- * entries, n_ops >= 1.  The arithmetic per sketch is exactly that of cs_sketch; nothing is allocated.
+ * entries, n_ops >= 1.  Each sketch is the same sum of the same exactly representable products as in
+ * cs_sketch; large Rademacher launches add them in another order (matrix cores), so the two calls
+ * agree to fp32 rounding, bit for bit only on the smaller launches.  Nothing is allocated.
  */
 cs_status cs_sketch_multi(cs_ctx* ctx, int n_ops, const cs_op* ops, const float* z, int B, float* y);
 

@@ -114,6 +114,66 @@ void sketch_rademacher_kernel(OpDesc op, OpKeys keys, const float* __restrict__ 
     }
 }
 
+// Rademacher ensemble on the matrix cores, for launches that sketch many operators at once.
+// y = Phi z is a dense contraction once 16 tokens share the rows: a workgroup owns 16 rows of Phi and 16
+// tokens, its 16 waves split the columns in chunks of 128 (one Philox call per row and chunk), and every
+// `v_mfma_f32_16x16x4_f32` multiplies a 16 x 4 tile of signs (+-1.0, built from the bits) with a 4 x 16 tile
+// of z.  Operands are fp32, so the products are exact and only the order of the additions differs from the
+// vector kernel.  A lane (t, kg) holds sign row / token t and loads z[t][16 s + 4 kg .. + 4) of the chunk
+// as one 16-byte load for s = 0..7; component jj of load s is the B operand of multiply (s, jj), whose k
+// index kg therefore stands for column 16 s + 4 kg + jj.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float sk_f32x4;
+constexpr int SM_WAVES = 16;
+
+__global__ __launch_bounds__(SM_WAVES * 64)
+void sketch_rademacher_mfma_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ y) {
+    __shared__ float red[SM_WAVES][256];
+    pick_operator(op, keys);
+    z += (size_t)blockIdx.z * B * op.n;
+    y += (size_t)blockIdx.z * B * op.m;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tl = lane & 15, kg = lane >> 4;
+    const int row0 = blockIdx.x * 16, t0 = blockIdx.y * 16;
+    const int n = op.n;
+    const bool tok_ok = t0 + tl < B;
+    const float* zt = z + (size_t)(tok_ok ? t0 + tl : 0) * n + kg * 4;
+    const int nchunks = (n + 127) >> 7;
+    sk_f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};      // two chains, so that a multiply need not wait for the one before
+    for (int cc = wave; cc < nchunks; cc += SM_WAVES) {
+        const int c0 = cc << 7;
+        float4 zv[8];
+#pragma unroll
+        for (int sgrp = 0; sgrp < 8; ++sgrp) {
+            const int col = c0 + sgrp * 16 + kg * 4;                   // n is a multiple of 4: a load is all in or all out
+            zv[sgrp] = (tok_ok && col < n) ? *reinterpret_cast<const float4*>(zt + c0 + sgrp * 16) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        const u32x4 bits = rademacher_bits(op, (uint32_t)(row0 + tl), (uint32_t)cc);
+#pragma unroll
+        for (int sgrp = 0; sgrp < 8; ++sgrp) {
+            // bit 16 (sgrp % 2) + 4 kg + jj of word sgrp / 2
+            const uint32_t wl = bits.w[sgrp >> 1] >> (kg * 4);
+            const float zc[4] = {zv[sgrp].x, zv[sgrp].y, zv[sgrp].z, zv[sgrp].w};
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int bpos = (sgrp & 1) * 16 + jj;
+                const float pm = __uint_as_float(((wl << (31 - bpos)) & 0x80000000u) | 0x3F800000u);
+                acc[jj & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(pm, zc[jj], acc[jj & 1], 0, 0, 0);
+            }
+        }
+    }
+    const sk_f32x4 tot = acc[0] + acc[1];
+    *reinterpret_cast<sk_f32x4*>(&red[wave][lane * 4]) = tot;
+    __syncthreads();
+    // element e = lane * 4 + v of a tile is (row 4 (lane / 16) + v, token lane % 16)
+    if (tid < 256) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < SM_WAVES; ++w) sum += red[w][tid];
+        const int row = row0 + 4 * (tid >> 6) + (tid & 3), tok = t0 + ((tid >> 2) & 15);
+        if (row < op.m && tok < B) y[(size_t)tok * op.m + row] = sum * op.scale;
+    }
+}
+
 template <int TB, bool VEC>
 __global__ __launch_bounds__(SK_WAVES * 64)
 void sketch_gauss_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ y) {
@@ -279,7 +339,12 @@ hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int
             hipLaunchKernelGGL(sketch_srht_kernel, dim3(B, 1, nz), dim3(nthreads), bytes, s, op, keys, zj, B, yj);
         } else if (op.ens == 1) {
             const int tgroups = (B + 7) / 8;
-            if ((long)((op.m + 3) / 4) * tgroups * nz >= 256) {
+            const long mfma_wgs = (long)((op.m + 15) / 16) * ((B + 15) / 16) * nz;
+            if ((op.n & 3) == 0 && mfma_wgs >= 128) {
+                // enough 16 x 16 tiles to fill the chip (several operators per launch): matrix cores
+                hipLaunchKernelGGL(sketch_rademacher_mfma_kernel, dim3((op.m + 15) / 16, (B + 15) / 16, nz), dim3(SM_WAVES * 64), 0, s,
+                                   op, keys, zj, B, yj);
+            } else if ((long)((op.m + 3) / 4) * tgroups * nz >= 256) {
                 hipLaunchKernelGGL((sketch_rademacher_kernel<4, 8>), dim3((op.m + 3) / 4, tgroups, nz), dim3(SR_WAVES * 64), 0, s, op, keys, zj, B, yj);
             } else {
                 hipLaunchKernelGGL((sketch_rademacher_kernel<2, 8>), dim3((op.m + 1) / 2, tgroups, nz), dim3(SR_WAVES * 64), 0, s, op, keys, zj, B, yj);
