@@ -594,6 +594,35 @@ def main():
             run(args.warmup + i)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        # --- after the timed region: the same steps once more with an event between them (spread of
+        # the step time), and the execution stream alone (attention + FFN of every layer, no sketches and
+        # no recoveries) replayed the same way: net against kernel-only time of a step
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        marks[0].record(stream)
+        for i in range(args.steps):
+            run(args.warmup + i)
+            marks[i + 1].record(stream)
+        torch.cuda.synchronize()
+        step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+        pick = lambda q: step_ms[min(len(step_ms) - 1, int(q * len(step_ms)))]
+        step_spread = {"p10": pick(0.1), "p50": pick(0.5), "p90": pick(0.9), "note": "one event per step; the timed region has none"}
+        exec_only_ms = None
+        if graphs is not None and args.recovery == "next-step":
+            def exec_only(i):
+                cur = i % 2
+                for l in range(st.layers):
+                    ctx.cs_head_attn(st.q[i][l], st.K[l], st.V[l], st.H_gen[cur][l], st.o)
+                    ctx.cs_block_ffn(st.Wg[l], st.Wu[l], st.Wd[l], st.x[i][l], st.S_gen[cur][l], False, st.out)
+            eg = []
+            for i in range(min(4, nsteps)):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream, capture_error_mode="thread_local"):
+                    exec_only(i)
+                eg.append(g)
+            for g in eg:
+                g.replay()
+            exec_only_ms = time_loop(lambda i: eg[i % len(eg)].replay(), 3 * len(eg), stream)
+            del eg
         # --- per-call durations: each call type launched back to back over all layers (fresh
         # weights and supports per layer), HIP events on the launching stream around each loop
         per, union_mean = call_loops(ctx, st, stream)
@@ -667,6 +696,9 @@ def main():
                               "synthetic usage vectors are resident, so that stream is not ordered against the "
                               "execution of the same step" % len(st.groups)) if args.recovery == "next-step" else
                              "measurement and recovery run on a second stream up to 4 layers ahead of execution in the same step"},
+        "step_ms_spread": step_spread,
+        "ms_per_step_execution_only": exec_only_ms,
+        "measurement_and_recovery_overhead": None if exec_only_ms is None else (ms_per_step - exec_only_ms) / ms_per_step,
         "serial_step_breakdown_ms": step_share,
         "ms_per_step_serial_sum": sum(step_share.values()),
         "launch_mode": "hip_graph" if graphs is not None else "eager",
