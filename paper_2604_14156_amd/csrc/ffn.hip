@@ -108,6 +108,14 @@ static hipError_t run_generic(const FfnArgs& a, hipStream_t s) {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
+// Items (gate/up) and column tiles (down) go to workgroups round-robin by default.  With CS_FD_TICKETS=1
+// they are handed out by a device-wide counter instead, which pays when another stream's kernels hold some
+// compute units for long (a workgroup that starts late simply takes fewer items) and costs about 1.5 us per
+// kernel otherwise.
+#ifndef CS_FD_TICKETS
+#define CS_FD_TICKETS 0
+#endif
+constexpr bool FD_TICKETS = CS_FD_TICKETS != 0;
 constexpr int FD_WAVES = 16;
 constexpr int FD_THREADS = FD_WAVES * 64;
 constexpr int FD_MAXG = 1024;
@@ -195,12 +203,11 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
         const int kk = kcol(s);
         xa[s] = (kk < d && ln < T) ? load_frag(x + (size_t)ln * d + kk + kg * 8) : zero_frag();
     }
-    // work items are handed out by a device-wide counter (sync[0]); a workgroup that starts late, or
-    // not at all while its compute unit is busy with another kernel, simply takes fewer items.
-        // Tickets are drawn two items ahead so that the atomic's latency never sits on the critical path.
-    // The first item of a workgroup is its own index; the rest are tickets gridDim.x + n.
+    // The first item of a workgroup is its own index; the following ones are index + n gridDim.x, or, with
+    // tickets, gridDim.x + the value of a device-wide counter (sync[0]), drawn two items ahead so that the
+    // atomic's latency never sits on the critical path.
     int t_first = 0;
-    if (tid == 0) t_first = atomicAdd(&sync[0], 1);   // result not needed before the list is built
+    if (FD_TICKETS && tid == 0) t_first = atomicAdd(&sync[0], 1);   // result not needed before the list is built
     const int nblocks = build_block_list<FD_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
     // the down kernel takes the list from here instead of building it again: [0] = count, then the blocks
     if (blockIdx.x == 0) {
@@ -209,7 +216,7 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     }
     const int cpb = b >> 3;                           // 8-channel chunks per block
     const int nitems = nblocks * cpb;
-    if (tid == 0) { ticket[0] = blockIdx.x; ticket[1] = (int)gridDim.x + t_first; }
+    if (tid == 0) { ticket[0] = blockIdx.x; ticket[1] = (int)gridDim.x + (FD_TICKETS ? t_first : (int)blockIdx.x); }
     __syncthreads();
     auto row_ptr = [&](int item) -> const uint16_t* {
         const int g = ulist[item / cpb], cc = item % cpb;
@@ -236,7 +243,8 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
                 wn[s] = kk < d ? load_frag(rp + kk) : zero_frag();
             }
         }
-        if (tid == 0) ticket[(it & 1) + 2] = (int)gridDim.x + atomicAdd(&sync[0], 1);   // the item after next
+        if (tid == 0) ticket[(it & 1) + 2] = FD_TICKETS ? (int)gridDim.x + atomicAdd(&sync[0], 1)   // the item after next
+                                                        : (int)blockIdx.x + (it + 2) * (int)gridDim.x;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[s], wb[s], acc, 0, 0, 0);
@@ -265,7 +273,7 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     }
     // the last workgroup to leave puts the counters back to zero for the next launch
     __syncthreads();
-    if (tid == 0) {
+    if (FD_TICKETS && tid == 0) {
         const int gone = atomicAdd(&sync[1], 1);
         if (gone == (int)gridDim.x - 1) { sync[0] = 0; sync[1] = 0; }
     }
@@ -285,7 +293,7 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ int ticket[2];
     int t_first = 0;
-    if (tid == 0) t_first = atomicAdd(&sync[2], 1);
+    if (FD_TICKETS && tid == 0) t_first = atomicAdd(&sync[2], 1);
     // the list of used blocks, written by the gate/up kernel of the same call
     // (G entries are fetched whatever the count says, so that both loads are in flight together)
     for (int i = tid; i < G; i += DN_WAVES * 64) ulist[i] = list_in[1 + i];
@@ -296,12 +304,13 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     const int ntiles = (d + 15) >> 4;
     // column tiles are handed out like the items of the gate/up kernel: own index first, then tickets
     int tile = blockIdx.x, it = 0;
-    if (tid == 0) ticket[0] = (int)gridDim.x + t_first;
+    if (tid == 0) ticket[0] = (int)gridDim.x + (FD_TICKETS ? t_first : (int)blockIdx.x);
     __syncthreads();
     while (tile < ntiles) {
     const int col0 = tile * 16;
     const bool row_ok = col0 + ln < d;
-    if (tid == 0 && it > 0) ticket[it & 1] = (int)gridDim.x + atomicAdd(&sync[2], 1);
+    if (tid == 0 && it > 0) ticket[it & 1] = FD_TICKETS ? (int)gridDim.x + atomicAdd(&sync[2], 1)
+                                                        : (int)blockIdx.x + (it + 1) * (int)gridDim.x;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     for (int u0 = wave; u0 < nblocks; u0 += DN_WAVES * DN_UB) {
         for (int ks = 0; ks < ksteps; ks += 2) {
@@ -339,7 +348,7 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     ++it;
     __syncthreads();                                  // red[] and the ticket slot are reused
     }
-    if (tid == 0) {
+    if (FD_TICKETS && tid == 0) {
         const int gone = atomicAdd(&sync[3], 1);
         if (gone == (int)gridDim.x - 1) { sync[2] = 0; sync[3] = 0; }
     }
