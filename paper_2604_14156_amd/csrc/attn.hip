@@ -94,6 +94,29 @@ template <> struct Frag8<uint16_t> {
 // weighted sums), each with eight ranges' loads in flight.
 template <int DH>
 __device__ __forceinline__ float merge_ranges(const float* __restrict__ pp, int nsplit, int c) {
+    if (nsplit <= 8) {
+        // the usual case: everything is fetched in one round trip, then the same two passes on registers
+        float mx[8], sm[8], ac[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float* ps = pp + (size_t)u * (DH + 2);
+            const bool in = u < nsplit;
+            mx[u] = in ? ps[0] : -INFINITY;
+            sm[u] = in ? ps[1] : 0.f;
+            ac[u] = in ? ps[2 + c] : 0.f;
+        }
+        float mtot = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mtot = fmaxf(mtot, mx[u]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = mx[u] > -INFINITY ? exp2f(mx[u] - mtot) : 0.f;
+            num += w * ac[u];
+            den += w * sm[u];
+        }
+        return den > 0.f ? num / den : 0.f;
+    }
     float mtot = -INFINITY;
     for (int s0 = 0; s0 < nsplit; s0 += 8) {
         float mx[8];
@@ -254,6 +277,9 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, const
     const int slot = blockIdx.x, seq = blockIdx.y;
     const int c = threadIdx.x, lane = c & 63;
     const int h = heads[seq * kh + slot];
+    // the loads of the merge do not depend on the head list: they are issued first
+    const float* pp = part + ((size_t)seq * kh + slot) * nsplit * (DH + 2);
+    const float merged = merge_ranges<DH>(pp, nsplit, c);
     for (int hp = slot; hp < H; hp += kh) {
         bool listed = false;
         for (int j0 = 0; j0 < kh; j0 += 64) {
@@ -263,8 +289,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int H, const
         if (!listed) store1(out + ((size_t)seq * H + hp) * DH + c, 0.f);
     }
     if (h < 0 || h >= H) return;
-    const float* pp = part + ((size_t)seq * kh + slot) * nsplit * (DH + 2);
-    store1(out + ((size_t)seq * H + h) * DH + c, merge_ranges<DH>(pp, nsplit, c));
+    store1(out + ((size_t)seq * H + h) * DH + c, merged);
 }
 
 // Workgroup shape, number of position ranges per head and their length.  One range (the result
