@@ -185,7 +185,7 @@ template <int NS>
 __global__ __launch_bounds__(FD_THREADS)
 void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
                      const uint16_t* __restrict__ x, int T, const int32_t* __restrict__ support, int k, int shared,
-                     uint16_t* __restrict__ hbuf, uint16_t* __restrict__ list_out, int* __restrict__ sync) {
+                     uint16_t* __restrict__ hbuf, uint32_t* __restrict__ list_out, int* __restrict__ sync) {
     __shared__ uint32_t mask[FD_MAXG];
     __shared__ uint16_t ulist[FD_MAXG];
     __shared__ int wcount[FD_WAVES];
@@ -211,8 +211,14 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     const int nblocks = build_block_list<FD_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
     // the down kernel takes the list from here instead of building it again: [0] = count, then the blocks
     if (blockIdx.x == 0) {
-        if (tid == 0) list_out[0] = (uint16_t)nblocks;
-        for (int i = tid; i < nblocks; i += FD_THREADS) list_out[1 + i] = ulist[i];
+        // layout: [0] count, [1 + i] = block of slot i in the low half, nothing else; [1 + FD_MAXG + i] = the
+        // block's token mask (the down kernel does not fetch hidden values of tokens that do not use a block)
+        if (tid == 0) list_out[0] = (uint32_t)nblocks;
+        for (int i = tid; i < nblocks; i += FD_THREADS) {
+            const uint32_t g = ulist[i];
+            list_out[1 + i] = g;
+            list_out[1 + FD_MAXG + i] = mask[g];
+        }
     }
     const int cpb = b >> 3;                           // 8-channel chunks per block
     const int nitems = nblocks * cpb;
@@ -286,9 +292,10 @@ constexpr int DN_UB = 6;                              // blocks in flight per wa
 
 __global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
-                   int T, const uint16_t* __restrict__ list_in, uint16_t* __restrict__ out,
+                   int T, const uint32_t* __restrict__ list_in, uint16_t* __restrict__ out,
                    int* __restrict__ sync) {
     __shared__ uint16_t ulist[FD_MAXG];
+    __shared__ uint32_t umask[FD_MAXG];
     __shared__ float red[DN_WAVES][256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ int ticket[2];
@@ -296,7 +303,10 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     if (FD_TICKETS && tid == 0) t_first = atomicAdd(&sync[2], 1);
     // the list of used blocks, written by the gate/up kernel of the same call
     // (G entries are fetched whatever the count says, so that both loads are in flight together)
-    for (int i = tid; i < G; i += DN_WAVES * 64) ulist[i] = list_in[1 + i];
+    for (int i = tid; i < G; i += DN_WAVES * 64) {
+        ulist[i] = (uint16_t)list_in[1 + i];
+        umask[i] = list_in[1 + FD_MAXG + i];
+    }
     const int nblocks = min((int)list_in[0], G);
     const int ln = lane & 15, kg = lane >> 4;
     const bool tok_ok = ln < T;                       // rows of the hidden-value operand beyond T are zero
@@ -322,9 +332,10 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
                 for (int e = 0; e < 2; ++e) {
                     const bool ok = u < nblocks && ks + e < ksteps;
                     const int g = ok ? ulist[u] : 0;
+                    const bool tok_uses = ok && ((umask[ok ? u : 0] >> ln) & 1u);      // token ln lists block g
                     const int ch = (ks + e) * 32 + kg * 8;
                     wa[q][e] = (ok && row_ok) ? load_frag(Wd + ((size_t)g * d + col0 + ln) * b + ch) : zero_frag();
-                    hb[q][e] = (ok && tok_ok) ? load_frag(hbuf + ((size_t)g * 16 + ln) * b + ch) : zero_frag();
+                    hb[q][e] = (tok_uses && tok_ok) ? load_frag(hbuf + ((size_t)g * 16 + ln) * b + ch) : zero_frag();
                 }
             }
 #pragma unroll
@@ -367,7 +378,8 @@ static bool mfma_decode_ok(const FfnArgs& a) {
 
 static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(a.scratch);
-    uint16_t* list = hbuf + (size_t)a.G * 16 * a.b;   // count + used blocks, handed from the first kernel to the second
+    // count, used blocks and their token masks, handed from the first kernel to the second
+    uint32_t* list = reinterpret_cast<uint32_t*>(hbuf + (size_t)a.G * 16 * a.b);
     const int ns = gateup_steps(a.d);
     const int cpb = a.b / 8;
     const int union_max = a.shared ? a.k : (a.T * a.k < a.G ? a.T * a.k : a.G);
@@ -401,7 +413,7 @@ hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s) {
 }
 
 size_t ffn_scratch_bytes(const FfnArgs& a) {
-    if (mfma_decode_ok(a)) return ((size_t)a.G * 16 * a.b + FD_MAXG + 8) * sizeof(uint16_t);
+    if (mfma_decode_ok(a)) return (size_t)a.G * 16 * a.b * sizeof(uint16_t) + (2 * FD_MAXG + 4) * sizeof(uint32_t);
     if (ffn_gemm_ok(a)) return ffn_gemm_scratch_bytes(a);
     return (size_t)a.T * a.k * a.b * sizeof(float);
 }
