@@ -130,8 +130,10 @@ __device__ __forceinline__ bf16x8_t zero_frag() {
 
 // Token masks per block and the compacted list of blocks used by at least one token.
 // mask[g] bit t = token t lists block g.  Returns the number of listed blocks.
+// `pre` is support[threadIdx.x] (or -1 past the end), fetched by the caller ahead of its other loads:
+// loads return in order, so a support entry requested after them would wait for all of them.
 template <int NWAVES>
-__device__ __forceinline__ int build_block_list(const int32_t* __restrict__ support, int T, int k, int shared, int G,
+__device__ __forceinline__ int build_block_list(const int32_t* __restrict__ support, int pre, int T, int k, int shared, int G,
                                                 uint32_t* mask, uint16_t* ulist, int* wcount) {
     constexpr int NTH = NWAVES * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -142,7 +144,7 @@ __device__ __forceinline__ int build_block_list(const int32_t* __restrict__ supp
         int base = 0;
         for (int i0 = 0; i0 < k; i0 += NTH) {
             const int i = i0 + tid;
-            const int g = i < k ? support[i] : -1;
+            const int g = i < k ? (i0 == 0 ? pre : support[i]) : -1;
             const bool used = g >= 0 && g < G;
             const unsigned long long bal = __ballot(used);
             if (lane == 0) wcount[wave] = __popcll(bal);
@@ -160,7 +162,7 @@ __device__ __forceinline__ int build_block_list(const int32_t* __restrict__ supp
     const int total = shared ? k : T * k;
     const uint32_t allbits = T >= 32 ? 0xFFFFFFFFu : ((1u << T) - 1u);
     for (int i = tid; i < total; i += NTH) {
-        const int g = support[i];
+        const int g = i == tid ? pre : support[i];
         if (g >= 0 && g < G) atomicOr(&mask[g], shared ? allbits : (1u << (i / k)));
     }
     __syncthreads();
@@ -196,7 +198,10 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     // k-steps of this wave: pairs of adjacent 32-column steps, so that a wave reads whole 128-byte lines
     auto kcol = [&](int s) { return (((s >> 1) * FD_WAVES + wave) * 2 + (s & 1)) * 32; };
 
-    // this wave's slice of the token rows, kept in registers (issued before the block list is built)
+    // the first support entries, then this wave's slice of the token rows, kept in registers (both
+    // requested before the block list is built)
+    const int nsup = (shared || T == 1) ? k : T * k;
+    const int pre = tid < nsup ? support[tid] : -1;
     bf16x8_t xa[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -208,7 +213,7 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     // atomic's latency never sits on the critical path.
     int t_first = 0;
     if (FD_TICKETS && tid == 0) t_first = atomicAdd(&sync[0], 1);   // result not needed before the list is built
-    const int nblocks = build_block_list<FD_WAVES>(support, T, k, shared, G, mask, ulist, wcount);
+    const int nblocks = build_block_list<FD_WAVES>(support, pre, T, k, shared, G, mask, ulist, wcount);
     // the down kernel takes the list from here instead of building it again: [0] = count, then the blocks
     if (blockIdx.x == 0) {
         // layout: [0] count, [1 + i] = block of slot i in the low half, nothing else; [1 + FD_MAXG + i] = the
