@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--sketch", choices=["per-group", "per-layer"], default="per-group",
                     help="next-step mode: sketch the layers of a group with one launch per kind once the group's last "
                          "layer has been issued (per-group), or every layer with its own two launches (per-layer)")
+    ap.add_argument("--groups", type=int, default=None,
+                    help="next-step mode: number of layer groups per step (each is sketched and recovered with one launch per kind)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     return ap.parse_args()
 
@@ -526,6 +528,9 @@ def main():
         raise SystemExit("bench.py needs a GPU and the HIP library; there is no CPU fallback")
     SOLVER["name"], SOLVER["iters"] = args.solver, args.iht_iters
     SKETCH["per_group"] = args.sketch == "per-group"
+    if args.groups is not None:
+        global NEXT_GROUPS
+        NEXT_GROUPS = max(1, args.groups)
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
     rstream = torch.cuda.Stream()
