@@ -108,14 +108,6 @@ static hipError_t run_generic(const FfnArgs& a, hipStream_t s) {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
-// Items (gate/up) and column tiles (down) go to workgroups round-robin by default.  With CS_FD_TICKETS=1
-// they are handed out by a device-wide counter instead, which pays when another stream's kernels hold some
-// compute units for long (a workgroup that starts late simply takes fewer items) and costs about 1.5 us per
-// kernel otherwise.
-#ifndef CS_FD_TICKETS
-#define CS_FD_TICKETS 0
-#endif
-constexpr bool FD_TICKETS = CS_FD_TICKETS != 0;
 constexpr int FD_WAVES = 16;
 constexpr int FD_THREADS = FD_WAVES * 64;
 constexpr int FD_MAXG = 1024;
@@ -187,37 +179,59 @@ template <int NS>
 __global__ __launch_bounds__(FD_THREADS)
 void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
                      const uint16_t* __restrict__ x, int T, const int32_t* __restrict__ support, int k, int shared,
-                     uint16_t* __restrict__ hbuf, uint32_t* __restrict__ list_out, int* __restrict__ sync) {
+                     int direct, uint16_t* __restrict__ hbuf, uint32_t* __restrict__ list_out) {
     __shared__ uint32_t mask[FD_MAXG];
     __shared__ uint16_t ulist[FD_MAXG];
     __shared__ int wcount[FD_WAVES];
     __shared__ float red[2][FD_WAVES][256];
-    __shared__ int ticket[4];
+    __shared__ int n_direct;                          // listed blocks that are handled as direct items
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, kg = lane >> 4;         // tile column / row index, k-group
     // k-steps of this wave: pairs of adjacent 32-column steps, so that a wave reads whole 128-byte lines
     auto kcol = [&](int s) { return (((s >> 1) * FD_WAVES + wave) * 2 + (s & 1)) * 32; };
+    const int cpb = b >> 3;                           // 8-channel chunks per block
+    auto rows_of = [&](int g, int cc) -> const uint16_t* {
+        const uint16_t* base = ln < 8 ? Wg : Wu;
+        return base + ((size_t)g * b + cc * 8 + (ln & 7)) * d + kg * 8;
+    };
+    if (tid == 0) n_direct = 0;
 
-    // the first support entries, then this wave's slice of the token rows, kept in registers (both
-    // requested before the block list is built)
+    // Items are (used block, 8-channel chunk).  Which blocks are used is known only after the supports have
+    // come in, a full memory round trip after the kernel started.  When the union of the supports is
+    // expected to be dense (`direct`), the first item of workgroup w is therefore fixed beforehand as block
+    // w / cpb, chunk w % cpb, and its weights are requested at once; should no token list that block, the
+    // loads are dropped (they are in bounds whatever the supports say).  The items of all other used blocks
+    // are dealt round-robin from the compacted list.
+    const int nd_blocks = direct ? min(G, (int)gridDim.x / cpb) : 0;
+    const bool has_direct = (int)blockIdx.x < nd_blocks * cpb;
+    const int g_dir = blockIdx.x / cpb, cc_dir = blockIdx.x % cpb;
+
+    // requested in this order: the first support entries, the direct item, this wave's slice of the token
+    // rows (kept in registers for the whole kernel); loads return in order
     const int nsup = (shared || T == 1) ? k : T * k;
     const int pre = tid < nsup ? support[tid] : -1;
+    bf16x8_t wb[NS], wn[NS];
+    if (has_direct) {
+        const uint16_t* rp = rows_of(g_dir, cc_dir);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int kk = kcol(s);
+            wb[s] = kk < d ? load_frag(rp + kk) : zero_frag();
+        }
+    }
     bf16x8_t xa[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const int kk = kcol(s);
         xa[s] = (kk < d && ln < T) ? load_frag(x + (size_t)ln * d + kk + kg * 8) : zero_frag();
     }
-    // The first item of a workgroup is its own index; the following ones are index + n gridDim.x, or, with
-    // tickets, gridDim.x + the value of a device-wide counter (sync[0]), drawn two items ahead so that the
-    // atomic's latency never sits on the critical path.
-    int t_first = 0;
-    if (FD_TICKETS && tid == 0) t_first = atomicAdd(&sync[0], 1);   // result not needed before the list is built
     const int nblocks = build_block_list<FD_WAVES>(support, pre, T, k, shared, G, mask, ulist, wcount);
-    // the down kernel takes the list from here instead of building it again: [0] = count, then the blocks
+    // the list is ascending when it was compacted from the masks: its first entries are the direct blocks
+    for (int i = tid; i < nblocks; i += FD_THREADS)
+        if ((int)ulist[i] < nd_blocks && (i + 1 == nblocks || (int)ulist[i + 1] >= nd_blocks)) n_direct = i + 1;
+    // the down kernel takes the list and the token masks from here: [0] count, [1 + i] block of slot i,
+    // [1 + FD_MAXG + i] its token mask
     if (blockIdx.x == 0) {
-        // layout: [0] count, [1 + i] = block of slot i in the low half, nothing else; [1 + FD_MAXG + i] = the
-        // block's token mask (the down kernel does not fetch hidden values of tokens that do not use a block)
         if (tid == 0) list_out[0] = (uint32_t)nblocks;
         for (int i = tid; i < nblocks; i += FD_THREADS) {
             const uint32_t g = ulist[i];
@@ -225,68 +239,69 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
             list_out[1 + FD_MAXG + i] = mask[g];
         }
     }
-    const int cpb = b >> 3;                           // 8-channel chunks per block
-    const int nitems = nblocks * cpb;
-    if (tid == 0) { ticket[0] = blockIdx.x; ticket[1] = (int)gridDim.x + (FD_TICKETS ? t_first : (int)blockIdx.x); }
     __syncthreads();
-    auto row_ptr = [&](int item) -> const uint16_t* {
-        const int g = ulist[item / cpb], cc = item % cpb;
-        const uint16_t* base = ln < 8 ? Wg : Wu;
-        return base + ((size_t)g * b + cc * 8 + (ln & 7)) * d + kg * 8;
-    };
-    bf16x8_t wb[NS], wn[NS];
-    int item = ticket[0], next = ticket[1];
-    if (item < nitems) {
-        const uint16_t* rp = row_ptr(item);
+    const int nlisted = (nblocks - n_direct) * cpb;   // items dealt from the list
+    const int first_listed = n_direct;
+    int g_cur = 0, cc_cur = 0, j_next;
+    bool v_cur;
+    if (has_direct) {
+        g_cur = g_dir; cc_cur = cc_dir;
+        v_cur = mask[g_dir] != 0u;
+        j_next = blockIdx.x;
+    } else {
+        const int j = blockIdx.x;
+        v_cur = j < nlisted;
+        if (v_cur) {
+            g_cur = ulist[first_listed + j / cpb]; cc_cur = j % cpb;
+            const uint16_t* rp = rows_of(g_cur, cc_cur);
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const int kk = kcol(s);
-            wb[s] = kk < d ? load_frag(rp + kk) : zero_frag();
+            for (int s = 0; s < NS; ++s) {
+                const int kk = kcol(s);
+                wb[s] = kk < d ? load_frag(rp + kk) : zero_frag();
+            }
         }
+        j_next = j + (int)gridDim.x;
     }
-    int buf = 0, it = 0;
-    while (item < nitems) {
-        if (next < nitems) {
-            const uint16_t* rp = row_ptr(next);
+    int buf = 0;
+    bool direct_pass = has_direct;                    // a direct item that turns out unused is skipped, the listed ones follow
+    while (v_cur || direct_pass) {
+        direct_pass = false;
+        const bool v_next = j_next < nlisted;
+        int g_next = 0, cc_next = 0;
+        if (v_next) {                                 // the next item's loads go out before the current one is used
+            g_next = ulist[first_listed + j_next / cpb]; cc_next = j_next % cpb;
+            const uint16_t* rp = rows_of(g_next, cc_next);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int kk = kcol(s);
                 wn[s] = kk < d ? load_frag(rp + kk) : zero_frag();
             }
         }
-        if (tid == 0) ticket[(it & 1) + 2] = FD_TICKETS ? (int)gridDim.x + atomicAdd(&sync[0], 1)   // the item after next
-                                                        : (int)blockIdx.x + (it + 2) * (int)gridDim.x;
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        if (v_cur) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[s], wb[s], acc, 0, 0, 0);
-        *reinterpret_cast<f32x4_t*>(&red[buf][wave][lane * 4]) = acc;
+            for (int s = 0; s < NS; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[s], wb[s], acc, 0, 0, 0);
+            *reinterpret_cast<f32x4_t*>(&red[buf][wave][lane * 4]) = acc;
+        }
         __syncthreads();
         // element e = lane*4 + i of a tile is (token 4*(lane/16)+i, column lane%16);
         // columns 0-7 are gate channels, 8-15 the matching up channels (32 elements further)
-        if (tid < 256) {
+        if (v_cur && tid < 256) {
             const int col = (tid >> 2) & 15;
             if (col < 8) {
                 float sg = 0.f, su = 0.f;
 #pragma unroll
                 for (int w = 0; w < FD_WAVES; ++w) { sg += red[buf][w][tid]; su += red[buf][w][tid + 32]; }
                 const int tok = 4 * (tid >> 6) + (tid & 3);
-                const int g = ulist[item / cpb], cc = item % cpb;
-                const float hv = ((mask[g] >> tok) & 1u) ? sg / (1.0f + __expf(-sg)) * su : 0.f;
-                hbuf[((size_t)g * 16 + tok) * b + cc * 8 + col] = f32_to_bf16(hv);
+                const float hv = ((mask[g_cur] >> tok) & 1u) ? sg / (1.0f + __expf(-sg)) * su : 0.f;
+                hbuf[((size_t)g_cur * 16 + tok) * b + cc_cur * 8 + col] = f32_to_bf16(hv);
             }
         }
         buf ^= 1;
-        item = next;
-        next = ticket[(it & 1) + 2];          // written before the barrier above
-        ++it;
+        g_cur = g_next; cc_cur = cc_next; v_cur = v_next;
+        j_next += (int)gridDim.x;
 #pragma unroll
         for (int s = 0; s < NS; ++s) wb[s] = wn[s];
-    }
-    // the last workgroup to leave puts the counters back to zero for the next launch
-    __syncthreads();
-    if (FD_TICKETS && tid == 0) {
-        const int gone = atomicAdd(&sync[1], 1);
-        if (gone == (int)gridDim.x - 1) { sync[0] = 0; sync[1] = 0; }
     }
 }
 
@@ -297,15 +312,11 @@ constexpr int DN_UB = 6;                              // blocks in flight per wa
 
 __global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
-                   int T, const uint32_t* __restrict__ list_in, uint16_t* __restrict__ out,
-                   int* __restrict__ sync) {
+                   int T, const uint32_t* __restrict__ list_in, uint16_t* __restrict__ out) {
     __shared__ uint16_t ulist[FD_MAXG];
     __shared__ uint32_t umask[FD_MAXG];
     __shared__ float red[DN_WAVES][256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ int ticket[2];
-    int t_first = 0;
-    if (FD_TICKETS && tid == 0) t_first = atomicAdd(&sync[2], 1);
     // the list of used blocks, written by the gate/up kernel of the same call
     // (G entries are fetched whatever the count says, so that both loads are in flight together)
     for (int i = tid; i < G; i += DN_WAVES * 64) {
@@ -317,15 +328,11 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     const bool tok_ok = ln < T;                       // rows of the hidden-value operand beyond T are zero
     const int ksteps = b >> 5;                        // 32 channels per matrix instruction
     const int ntiles = (d + 15) >> 4;
-    // column tiles are handed out like the items of the gate/up kernel: own index first, then tickets
-    int tile = blockIdx.x, it = 0;
-    if (tid == 0) ticket[0] = (int)gridDim.x + (FD_TICKETS ? t_first : (int)blockIdx.x);
     __syncthreads();
-    while (tile < ntiles) {
+    // column tiles are dealt round-robin
+    for (int tile = blockIdx.x; tile < ntiles; tile += (int)gridDim.x) {
     const int col0 = tile * 16;
     const bool row_ok = col0 + ln < d;
-    if (tid == 0 && it > 0) ticket[it & 1] = FD_TICKETS ? (int)gridDim.x + atomicAdd(&sync[2], 1)
-                                                        : (int)blockIdx.x + (it + 1) * (int)gridDim.x;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     for (int u0 = wave; u0 < nblocks; u0 += DN_WAVES * DN_UB) {
         for (int ks = 0; ks < ksteps; ks += 2) {
@@ -360,13 +367,7 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
         const int col = col0 + 4 * (tid >> 6) + (tid & 3), tok = (tid >> 2) & 15;
         if (tok < T && col < d) out[(size_t)tok * d + col] = f32_to_bf16(s);
     }
-    tile = ticket[it & 1];                            // drawn at the top of this round (or before the loop)
-    ++it;
-    __syncthreads();                                  // red[] and the ticket slot are reused
-    }
-    if (FD_TICKETS && tid == 0) {
-        const int gone = atomicAdd(&sync[3], 1);
-        if (gone == (int)gridDim.x - 1) { sync[2] = 0; sync[3] = 0; }
+    __syncthreads();                                  // red[] is reused by the next tile
     }
 }
 
@@ -391,16 +392,16 @@ static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     int grid = union_max * cpb;
     if (grid > 256) grid = 256;                       // one workgroup of 16 waves per compute unit
     if (grid < 1) grid = 1;
+    // a dense union is expected when the tokens list at least twice as many entries as there are blocks
+    const int direct = (!a.shared && a.T > 1 && (long)a.T * a.k >= 2L * a.G) ? 1 : 0;
 #define CS_GU(NSV) hipLaunchKernelGGL((ffn_gateup_mfma<NSV>), dim3(grid), dim3(FD_THREADS), 0, s, \
-        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf, list, \
-        reinterpret_cast<int*>(a.sync))
+        (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, direct, hbuf, list)
     if (ns <= 2) CS_GU(2); else if (ns <= 4) CS_GU(4); else if (ns <= 8) CS_GU(8); else CS_GU(16);
 #undef CS_GU
     int dgrid = (a.d + 15) / 16;
     if (dgrid > 256) dgrid = 256;
     hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), 0, s,
-                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, list, (uint16_t*)a.out,
-                       reinterpret_cast<int*>(a.sync));
+                       (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, list, (uint16_t*)a.out);
     return hipGetLastError();
 }
 
