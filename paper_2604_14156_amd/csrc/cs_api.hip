@@ -24,8 +24,6 @@ struct cs_ctx {
     hipStream_t stream;
     void* scratch;
     size_t scratch_bytes;
-    void* sync;               // small zeroed area for device-side counters; kernels restore the zeros
-    size_t sync_bytes;
     int lds_limit;
     std::vector<PlanEntry> plans;
     // device arrays of plans for calls that serve several operators at once, keyed by the plans' atom
@@ -196,15 +194,6 @@ cs_status cs_create(cs_ctx** out, int device, void* hip_stream, size_t scratch_b
         delete c;
         return CS_ENOMEM;
     }
-    c->sync_bytes = 64 * 1024;
-    c->sync = nullptr;
-    if (hipMalloc(&c->sync, c->sync_bytes) != hipSuccess || hipMemset(c->sync, 0, c->sync_bytes) != hipSuccess) {
-        (void)hipGetLastError();
-        if (c->sync) (void)hipFree(c->sync);
-        (void)hipFree(c->scratch);
-        delete c;
-        return CS_ENOMEM;
-    }
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess || lds <= 0)
         lds = 64 * 1024;
@@ -225,7 +214,6 @@ void cs_destroy(cs_ctx* c) {
     for (cs_ctx::PlanGroup& g : c->groups)
         if (g.d_plans) (void)hipFree(g.d_plans);
     if (c->scratch) (void)hipFree(c->scratch);
-    if (c->sync) (void)hipFree(c->sync);
     delete c;
 }
 
@@ -435,7 +423,7 @@ cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, con
     FfnArgs a;
     a.dtype = dtype; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.d = d; a.G = G; a.b = b;
     a.x = x; a.T = T; a.support = support; a.k = k; a.shared = shared ? 1 : 0; a.out = out;
-    a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes; a.sync = c->sync;
+    a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes;
     const size_t need = ffn_scratch_bytes(a);
     if (need > c->scratch_bytes)
         return fail(c, CS_ENOMEM, "cs_block_ffn: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);
@@ -461,7 +449,6 @@ cs_status cs_head_attn(cs_ctx* c, int dtype, const void* q, const void* K, const
     AttnArgs a;
     a.dtype = dtype; a.q = q; a.K = K; a.V = V; a.B = B; a.H = H; a.L = L; a.dh = dh;
     a.heads = heads; a.kh = kh; a.out = out; a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes;
-    a.sync = c->sync; a.sync_bytes = c->sync_bytes;
     const size_t need = attn_scratch_bytes(a);
     if (need > c->scratch_bytes)
         return fail(c, CS_ENOMEM, "cs_head_attn: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);

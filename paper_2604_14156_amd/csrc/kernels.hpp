@@ -79,7 +79,6 @@ struct FfnArgs {
     const void* x; int T; const int32_t* support; int k; int shared;
     void* out;
     void* scratch; size_t scratch_bytes;
-    void* sync;           // zero-initialised device counters; every kernel leaves them at zero
 };
 size_t ffn_scratch_bytes(const FfnArgs& a);
 // many-row path on the matrix cores (ffn_gemm.hip)
@@ -93,7 +92,6 @@ struct AttnArgs {
     const void *q, *K, *V; int B, H, L, dh;
     const int32_t* heads; int kh; void* out;
     void* scratch; size_t scratch_bytes;
-    void* sync; size_t sync_bytes;      // zero-initialised counters; every kernel leaves them at zero
 };
 size_t attn_scratch_bytes(const AttnArgs& a);
 hipError_t launch_head_attn(const AttnArgs& a, hipStream_t s);
