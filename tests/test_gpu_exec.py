@@ -147,6 +147,30 @@ def test_ffn_empty_cases(cs):
     assert e.value.status == binding.CS_EINVAL
 
 
+@pytest.mark.parametrize("case", ["high_blocks_only", "shared_by_all_tokens", "low_blocks_only", "independent"])
+def test_ffn_decode_dense_union_guess(cs, case):
+    """16 tokens x 6 of 40 blocks: enough listed entries for the decode kernel to fix its first items by
+    workgroup index before it knows the supports (blocks 0..31).  The guess is wrong for every such item
+    when the tokens only use blocks 32..39, for most when all tokens share one support, right for most when
+    only low blocks are used."""
+    G, b, d, k, T = 40, 64, 512, 6, 16
+    rng = wl.rng_for(1700 + len(case))
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, G, b, d, 0.05, "bf16")
+    x = wl.make_tokens(rng, T, d, "bf16")
+    if case == "high_blocks_only":
+        sup = np.stack([rng.permutation(np.arange(32, 40))[:k] for _ in range(T)]).astype(np.int32)
+    elif case == "shared_by_all_tokens":
+        sup = np.tile(wl.random_supports(rng, G, k, 1)[0], (T, 1)).astype(np.int32)
+    elif case == "low_blocks_only":
+        sup = np.stack([rng.permutation(np.arange(0, 12))[:k] for _ in range(T)]).astype(np.int32)
+    else:
+        sup = wl.random_supports(rng, G, k, T)
+    out = host(cs.cs_block_ffn(dev_bf16(Wg), dev_bf16(Wu), dev_bf16(Wd), dev_bf16(x), dev_i32(sup), False))
+    want = oracle.block_ffn(Wg, Wu, Wd, x, sup)
+    for t in range(T):
+        assert rel_err(out[t], want[t]) <= 2e-2, (case, t, rel_err(out[t], want[t]))
+
+
 def _full_size_ffn(cs, B, seed):
     """Decode shape at full size: weights drawn on the device, oracle on sampled tokens."""
     c = wl.CFG2
