@@ -108,6 +108,16 @@ cs_status cs_set_stream(cs_ctx* ctx, void* hip_stream);
 cs_status cs_plan(cs_ctx* ctx, const cs_op* op, const cs_dict* dict);
 
 /*
+ * Plans are found again by the fields of `op` and by dict->psi, G, b, rb: the dictionary is identified by
+ * its ADDRESS, not by its content, and it is read at plan time only.  A caller that frees a dictionary,
+ * or overwrites it, must drop the plans built from it before the same address is used for other content;
+ * otherwise a later call with that address would silently run on the old plan.  cs_plan_drop waits for
+ * the context's stream, frees the plan's device memory (and every multi-operator table that lists it) and
+ * forgets it; dropping a pair that has no plan is not an error.  The next use builds a fresh plan.
+ */
+cs_status cs_plan_drop(cs_ctx* ctx, const cs_op* op, const cs_dict* dict);
+
+/*
  * y = Phi z (measurement equation, Sec. 3 / Sec. 8).
  *   z: float[B][n] in,  y: float[B][m] out.  B >= 0 (B == 0 is a no-op).
  */

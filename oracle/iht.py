@@ -26,15 +26,20 @@ def _unit_energy(v, G, rb, weights):
     return e.reshape(G, rb).sum(axis=1)
 
 
-def _top_units(energy, k):
-    order = sorted(range(energy.size), key=lambda g: (-energy[g], g))
+def _top_units(energy, k, boost=None):
+    key = energy if boost is None else energy * boost
+    order = sorted(range(energy.size), key=lambda g: (-key[g], g))
     return sorted(order[:k]), order
 
 
-def block_iht(M, y, G, rb, k, iters, normalised):
+def block_iht(M, y, G, rb, k, iters, normalised, prefer=None, slack=0.0):
     """Returns a dict like block_omp: support (ascending), coef ([k*rb], ascending-support
     order, after the final refit), residual, resid_norm, margin = relative gap between the
-    k-th and (k+1)-th unit energies at the last projection (1 if k == G)."""
+    k-th and (k+1)-th unit energies at the last projection (1 if k == G).
+
+    prefer, slack: as in block_omp, for checking a support selected elsewhere: in every
+    projection a unit of `prefer` is ranked as if its energy were (1 + slack) times larger, so
+    that near ties at the cut fall towards `prefer`.  Defaults: the plain rule."""
     M = np.asarray(M, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
     m, N = M.shape
@@ -47,6 +52,10 @@ def block_iht(M, y, G, rb, k, iters, normalised):
     if iters < 1:
         raise ValueError("iters must be >= 1")
     weights = np.linalg.norm(M, axis=0) if normalised else np.ones(N)
+    boost = None
+    if prefer is not None:
+        boost = np.ones(G)
+        boost[[int(u) for u in prefer]] = 1.0 + slack
     alpha = np.zeros(N)
     support = None
     margin = 1.0
@@ -55,7 +64,7 @@ def block_iht(M, y, G, rb, k, iters, normalised):
         g = M.T @ (y - M @ alpha)
         if support is None:
             e0 = _unit_energy(g, G, rb, weights)
-            support, order0 = _top_units(e0, k)
+            support, order0 = _top_units(e0, k, boost)
             if k < G and e0[order0[k - 1]] > 0.0:
                 min_margin = min(min_margin, (e0[order0[k - 1]] - e0[order0[k]]) / e0[order0[k - 1]])
         cols = np.concatenate([np.arange(u * rb, (u + 1) * rb) for u in support])
@@ -65,7 +74,7 @@ def block_iht(M, y, G, rb, k, iters, normalised):
         mu = float(gs @ gs) / den if den > 0.0 else 0.0
         p = alpha + mu * g
         energy = _unit_energy(p, G, rb, weights)
-        support, order = _top_units(energy, k)
+        support, order = _top_units(energy, k, boost)
         if k < G:
             ek, ek1 = energy[order[k - 1]], energy[order[k]]
             margin = (ek - ek1) / ek if ek > 0.0 else 0.0

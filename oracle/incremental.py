@@ -41,7 +41,8 @@ def _cols(units, rb):
     return np.concatenate([np.arange(g * rb, (g + 1) * rb) for g in units]) if len(units) else np.zeros(0, dtype=np.int64)
 
 
-def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_coef=None, gamma=0.0):
+def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_coef=None, gamma=0.0,
+                          prefer=None, slack=0.0):
     """Returns a dict: support (ascending), coef ([k*rb], ascending-support order, plain refit),
     residual, resid_norm, margin (min over the forward rounds of (best - runner_up)/best; 1 when
     swaps == 0), kept / dropped / added (unit lists), coef_step1 (the regularised refit on
@@ -49,6 +50,10 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
     dropped and the weakest unit kept; 1 when nothing or everything is dropped).
 
     prev_support: k distinct units in any order; prev_coef: [k*rb] in the order of prev_support.
+
+    prefer, slack: as in block_omp, for checking a support selected elsewhere: a unit of `prefer`
+    is ranked as if its energy (backward step) or score (forward step) were (1 + slack) times
+    larger.  Defaults: the plain rule.
     """
     M = np.asarray(M, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
@@ -68,6 +73,9 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
         raise ValueError("gamma must be >= 0")
     norms = np.linalg.norm(M, axis=0)
     weights = norms if normalised else np.ones(G * rb)
+    boost = np.ones(G)
+    if prefer is not None:
+        boost[[int(g) for g in prefer]] = 1.0 + slack
 
     # 1. temporal-regularised refit on the previous support (normal equations of the stacked system)
     cols = _cols(prev, rb)
@@ -82,7 +90,7 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
 
     # 2. backward step
     energy = ((alpha1 * weights[cols]) ** 2).reshape(k, rb).sum(axis=1)
-    order = sorted(range(k), key=lambda i: (energy[i], -prev[i]))      # first = dropped first
+    order = sorted(range(k), key=lambda i: (energy[i] * boost[prev[i]], -prev[i]))      # first = dropped first
     e_sorted = [energy[i] for i in order]
     if 0 < swaps < k and e_sorted[swaps] > 0.0:
         drop_margin = float((e_sorted[swaps] - e_sorted[swaps - 1]) / e_sorted[swaps])
@@ -110,7 +118,7 @@ def incremental_block_omp(M, y, G, rb, k, prev_support, swaps, normalised, prev_
                 continue
             c = bases[g].T @ r if normalised else M[:, g * rb:(g + 1) * rb].T @ r
             score[g] = float(c @ c)
-        best = int(np.argmax(score))
+        best = int(np.argmax(score * boost))
         s1 = score[best]
         rest = np.delete(score, best)
         s2 = float(rest.max()) if rest.size and np.isfinite(rest.max()) else 0.0

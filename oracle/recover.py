@@ -51,13 +51,20 @@ def _least_squares(A, y):
     return coef
 
 
-def block_omp(M, y, G, rb, k, normalised):
+def block_omp(M, y, G, rb, k, normalised, prefer=None, slack=0.0):
     """Greedy recovery of k units from y ~ M alpha.
 
     normalised=True : score_g = || Q_g^T r ||^2, Q_g an orthonormal basis of
                       the unit's columns (for rb == 1: (m_g^T r)^2 / ||m_g||^2,
                       the normalised-column correlation of Sec. 9).
     normalised=False: score_g = || M_g^T r ||^2 (raw block energy).
+
+    prefer, slack: for checking a support that somebody else selected.  Near
+    ties have several correct greedy choices; with prefer = that support and a
+    small slack, a unit of `prefer` is taken whenever its score is within a
+    factor 1/(1+slack) of the best one.  The other support is a valid greedy
+    path up to that slack exactly when this call returns it.  The defaults
+    (no preference) are the rule stated above.
 
     Returns a dict: support (ascending), order (selection order), coef
     ([k*rb], in ascending-support order), residual (vector), resid_norm,
@@ -75,6 +82,9 @@ def block_omp(M, y, G, rb, k, normalised):
     bases = None
     if normalised:
         bases = [np.linalg.qr(M[:, g * rb:(g + 1) * rb])[0] for g in range(G)]
+    boost = np.ones(G)
+    if prefer is not None:
+        boost[[int(g) for g in prefer]] = 1.0 + slack
     chosen = []
     r = y.copy()
     margin = 1.0
@@ -88,7 +98,7 @@ def block_omp(M, y, G, rb, k, normalised):
             else:
                 c = M[:, g * rb:(g + 1) * rb].T @ r
             score[g] = float(c @ c)
-        best = int(np.argmax(score))             # first maximum = smallest index
+        best = int(np.argmax(score * boost))     # first maximum = smallest index
         s1 = score[best]
         rest = np.delete(score, best)
         s2 = float(rest.max()) if rest.size and np.isfinite(rest.max()) else 0.0

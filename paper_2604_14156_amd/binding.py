@@ -16,7 +16,7 @@ CS_OK, CS_EINVAL, CS_EALIGN, CS_EILLPOSED, CS_ENOMEM, CS_EHIP = 0, -1, -2, -3, -
 CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
-EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_sketch", "cs_sketch_multi",
+EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_plan_drop", "cs_sketch", "cs_sketch_multi",
            "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
            "cs_softmax_entropy", "cs_uds_budget")
 
@@ -48,6 +48,7 @@ def load_library(path=LIB_PATH):
     lib.cs_last_error.restype = ctypes.c_char_p
     lib.cs_set_stream.argtypes = [vp, vp]
     lib.cs_plan.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict)]
+    lib.cs_plan_drop.argtypes = lib.cs_plan.argtypes
     lib.cs_sketch.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, vp]
     lib.cs_sketch_multi.argtypes = [vp, i32, ctypes.POINTER(CsOp), vp, i32, vp]
     lib.cs_recover_support.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32, vp, vp, vp, vp]
@@ -87,7 +88,11 @@ def make_op(ens, seed, stream_id, m, n):
 
 
 def make_dict(psi, G, b, rb):
-    return CsDict(None if psi is None else psi.data_ptr(), int(G), int(b), int(rb))
+    """psi: device tensor [G][b][rb] or None.  The tensor travels with the struct (attribute `tensor`), so
+    that a context which builds a plan from it can keep it alive: plans are found again by address."""
+    dct = CsDict(None if psi is None else psi.data_ptr(), int(G), int(b), int(rb))
+    dct.tensor = psi
+    return dct
 
 
 class Context:
@@ -101,12 +106,16 @@ class Context:
         st = self.lib.cs_create(ctypes.byref(self._h), device, sptr, scratch_bytes)
         if st != CS_OK:
             raise CsError(st, "cs_create failed")
-        self._keep = []        # dictionaries referenced by cached plans stay alive
+        self._keep = {}        # address -> dictionary tensor: dictionaries of cached plans stay alive
 
     def close(self):
         if self._h:
             self.lib.cs_destroy(self._h)
             self._h = ctypes.c_void_p()
+
+    def _alloc(self, shape, dtype, device):
+        """Output buffers the caller did not pass in (tests override this to put guard bands around them)."""
+        return torch.empty(shape, dtype=dtype, device=device)
 
     def _check(self, st):
         if st != CS_OK:
@@ -116,15 +125,25 @@ class Context:
         self._check(self.lib.cs_set_stream(self._h, None if stream is None else ctypes.c_void_p(stream.cuda_stream)))
 
     # -- the calls of the C ABI, same names ---------------------------------
+    def _retain(self, dct, psi=None):
+        """Every call that may build a plan keeps the dictionary's tensor: the plan cache identifies a
+        dictionary by its address, which must not be handed to another tensor while the plan lives."""
+        for d in (dct if isinstance(dct, (list, tuple)) else [dct]):
+            t = psi if psi is not None else getattr(d, "tensor", None)
+            if t is not None:
+                self._keep[t.data_ptr()] = t
+
     def cs_plan(self, op, dct, psi=None):
-        if psi is not None:
-            self._keep.append(psi)
+        self._retain(dct, psi)
         self._check(self.lib.cs_plan(self._h, ctypes.byref(op), ctypes.byref(dct)))
+
+    def cs_plan_drop(self, op, dct):
+        self._check(self.lib.cs_plan_drop(self._h, ctypes.byref(op), ctypes.byref(dct)))
 
     def cs_sketch(self, op, z, y=None):
         B = z.shape[0]
         if y is None:
-            y = torch.empty((B, op.m), dtype=torch.float32, device=z.device)
+            y = self._alloc((B, op.m), torch.float32, z.device)
         self._check(self.lib.cs_sketch(self._h, ctypes.byref(op), _ptr(z), B, _ptr(y)))
         return y
 
@@ -134,7 +153,7 @@ class Context:
         arr = ops if isinstance(ops, ctypes.Array) else (CsOp * n_ops)(*ops)
         B = z.shape[1]
         if y is None:
-            y = torch.empty((n_ops, B, arr[0].m), dtype=torch.float32, device=z.device)
+            y = self._alloc((n_ops, B, arr[0].m), torch.float32, z.device)
         self._check(self.lib.cs_sketch_multi(self._h, n_ops, arr, _ptr(z), B, _ptr(y)))
         return y
 
@@ -142,14 +161,15 @@ class Context:
                            want_coef=True, want_resid=True):
         B = y.shape[0]
         dev = y.device
+        self._retain(dct)
         if support is None:
-            support = torch.empty((B, k), dtype=torch.int32, device=dev)
+            support = self._alloc((B, k), torch.int32, dev)
         if coef is None and want_coef:
-            coef = torch.empty((B, k * dct.rb), dtype=torch.float32, device=dev)
+            coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
-            resid = torch.empty((B,), dtype=torch.float32, device=dev)
+            resid = self._alloc((B,), torch.float32, dev)
         if margin is None:
-            margin = torch.empty((B,), dtype=torch.float32, device=dev)
+            margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                 _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
@@ -159,19 +179,21 @@ class Context:
         """ops, dcts: sequences of n_ops operators / dictionaries (or ctypes arrays); y: [n_ops, B, m]."""
         n_ops, B = y.shape[0], y.shape[1]
         dev = y.device
+        if not isinstance(dcts, ctypes.Array):
+            self._retain(list(dcts))
         if not isinstance(ops, ctypes.Array):
             ops = (CsOp * n_ops)(*ops)
         if not isinstance(dcts, ctypes.Array):
             dcts = (CsDict * n_ops)(*dcts)
         rb = dcts[0].rb
         if support is None:
-            support = torch.empty((n_ops, B, k), dtype=torch.int32, device=dev)
+            support = self._alloc((n_ops, B, k), torch.int32, dev)
         if coef is None and want_coef:
-            coef = torch.empty((n_ops, B, k * rb), dtype=torch.float32, device=dev)
+            coef = self._alloc((n_ops, B, k * rb), torch.float32, dev)
         if resid is None and want_resid:
-            resid = torch.empty((n_ops, B), dtype=torch.float32, device=dev)
+            resid = self._alloc((n_ops, B), torch.float32, dev)
         if margin is None:
-            margin = torch.empty((n_ops, B), dtype=torch.float32, device=dev)
+            margin = self._alloc((n_ops, B), torch.float32, dev)
         self._check(self.lib.cs_recover_support_multi(self._h, n_ops, ops, dcts, k, _ptr(y), B,
                                                       _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
@@ -180,14 +202,15 @@ class Context:
                                want_coef=True, want_resid=True):
         B = y.shape[0]
         dev = y.device
+        self._retain(dct)
         if support is None:
-            support = torch.empty((B, k), dtype=torch.int32, device=dev)
+            support = self._alloc((B, k), torch.int32, dev)
         if coef is None and want_coef:
-            coef = torch.empty((B, k * dct.rb), dtype=torch.float32, device=dev)
+            coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
-            resid = torch.empty((B,), dtype=torch.float32, device=dev)
+            resid = self._alloc((B,), torch.float32, dev)
         if margin is None:
-            margin = torch.empty((B,), dtype=torch.float32, device=dev)
+            margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support_iht(self._h, ctypes.byref(op), ctypes.byref(dct), k, iters, _ptr(y), B,
                                                     _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
@@ -196,26 +219,27 @@ class Context:
                                support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True):
         B = y.shape[0]
         dev = y.device
+        self._retain(dct)
         if support is None:
-            support = torch.empty((B, k), dtype=torch.int32, device=dev)
+            support = self._alloc((B, k), torch.int32, dev)
         if coef is None and want_coef:
-            coef = torch.empty((B, k * dct.rb), dtype=torch.float32, device=dev)
+            coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
-            resid = torch.empty((B,), dtype=torch.float32, device=dev)
+            resid = self._alloc((B,), torch.float32, dev)
         if margin is None:
-            margin = torch.empty((B,), dtype=torch.float32, device=dev)
+            margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support_inc(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                     _ptr(prev_support), _ptr(prev_coef), float(gamma), swaps,
                                                     _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 
-    def cs_block_ffn(self, Wg, Wu, Wd, x, support, shared, out=None):
+    def cs_block_ffn(self, Wg, Wu, Wd, x, support, shared, out=None, entry=None):
         G, b, d = Wg.shape
         T = x.shape[0]
         k = support.shape[-1]
         if out is None:
-            out = torch.empty_like(x)
-        self._check(self.lib.cs_block_ffn(self._h, _dtype_code(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), d, G, b,
+            out = self._alloc(tuple(x.shape), x.dtype, x.device)
+        self._check((entry or self.lib.cs_block_ffn)(self._h, _dtype_code(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), d, G, b,
                                           _ptr(x), T, _ptr(support), k, 1 if shared else 0, _ptr(out)))
         return out
 
@@ -223,18 +247,19 @@ class Context:
         B, H, L, dh = K.shape
         kh = heads.shape[-1]
         if out is None:
-            out = torch.empty_like(q)
+            out = self._alloc(tuple(q.shape), q.dtype, q.device)
         self._check(self.lib.cs_head_attn(self._h, _dtype_code(q), _ptr(q), _ptr(K), _ptr(V), B, H, L, dh,
                                           _ptr(heads), kh, _ptr(out)))
         return out
 
     def cs_joint_select_coupled(self, tok_op, y_tok, k_tok, ch_op, ch_dict, Y_ch, k_ch):
         dev = y_tok.device
-        tokens = torch.empty((k_tok,), dtype=torch.int32, device=dev)
-        support = torch.empty((k_ch,), dtype=torch.int32, device=dev)
-        ybar = torch.empty((ch_op.m,), dtype=torch.float32, device=dev)
-        resid = torch.empty((1,), dtype=torch.float32, device=dev)
-        margin = torch.empty((1,), dtype=torch.float32, device=dev)
+        self._retain(ch_dict)
+        tokens = self._alloc((k_tok,), torch.int32, dev)
+        support = self._alloc((k_ch,), torch.int32, dev)
+        ybar = self._alloc((ch_op.m,), torch.float32, dev)
+        resid = self._alloc((1,), torch.float32, dev)
+        margin = self._alloc((1,), torch.float32, dev)
         self._check(self.lib.cs_joint_select_coupled(self._h, ctypes.byref(tok_op), _ptr(y_tok), k_tok,
                                                      ctypes.byref(ch_op), ctypes.byref(ch_dict), _ptr(Y_ch), k_ch,
                                                      _ptr(tokens), _ptr(support), _ptr(ybar), _ptr(resid), _ptr(margin)))
@@ -243,7 +268,7 @@ class Context:
     def cs_softmax_entropy(self, logits, entropy=None):
         B, V = logits.shape
         if entropy is None:
-            entropy = torch.empty((B,), dtype=torch.float32, device=logits.device)
+            entropy = self._alloc((B,), torch.float32, logits.device)
         self._check(self.lib.cs_softmax_entropy(self._h, _ptr(logits), B, V, _ptr(entropy)))
         return entropy
 
@@ -254,16 +279,17 @@ class Context:
         n_rows, d = x.shape
         k_tok = tokens.shape[0]
         if out is None:
-            out = torch.empty((k_tok, d), dtype=x.dtype, device=x.device)
+            out = self._alloc((k_tok, d), x.dtype, x.device)
         self._check(self.lib.cs_gather_rows(self._h, _dtype_code(x), _ptr(x), n_rows, d, _ptr(tokens), k_tok, _ptr(out)))
         return out
 
     def cs_joint_select(self, tok_op, y_tok, k_tok, ch_op, ch_dict, y_ch, k_ch):
         dev = y_tok.device
-        tokens = torch.empty((k_tok,), dtype=torch.int32, device=dev)
-        support = torch.empty((k_ch,), dtype=torch.int32, device=dev)
-        resid = torch.empty((1,), dtype=torch.float32, device=dev)
-        margin = torch.empty((1,), dtype=torch.float32, device=dev)
+        self._retain(ch_dict)
+        tokens = self._alloc((k_tok,), torch.int32, dev)
+        support = self._alloc((k_ch,), torch.int32, dev)
+        resid = self._alloc((1,), torch.float32, dev)
+        margin = self._alloc((1,), torch.float32, dev)
         self._check(self.lib.cs_joint_select(self._h, ctypes.byref(tok_op), _ptr(y_tok), k_tok,
                                              ctypes.byref(ch_op), ctypes.byref(ch_dict), _ptr(y_ch), k_ch,
                                              _ptr(tokens), _ptr(support), _ptr(resid), _ptr(margin)))

@@ -7,7 +7,6 @@
 #include <new>
 #include <cstdio>
 #include <cstring>
-#include <string>
 #include <vector>
 
 using namespace csk;
@@ -30,7 +29,7 @@ struct cs_ctx {
     // buffers (one buffer per plan for the lifetime of the context)
     struct PlanGroup { std::vector<const float*> key; Plan* d_plans; };
     std::vector<PlanGroup> groups;
-    std::string err;
+    char err[512];
 };
 
 namespace {
@@ -40,18 +39,29 @@ constexpr int kMaxWeightedRb = 16;
 
 cs_status fail(cs_ctx* c, cs_status st, const char* fmt, ...) {
     if (c) {
-        char buf[512];
         va_list ap;
         va_start(ap, fmt);
-        vsnprintf(buf, sizeof buf, fmt, ap);
+        vsnprintf(c->err, sizeof c->err, fmt, ap);      // fixed buffer: reporting an error allocates nothing
         va_end(ap);
-        c->err = buf;
     }
     return st;
 }
 
 cs_status hip_fail(cs_ctx* c, hipError_t e, const char* what) {
     return fail(c, CS_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Runs the body of an entry point; the host containers used by some of them (plan cache, operator lists)
+// may throw when host memory runs out, and nothing may leave the library as an exception.
+template <class F>
+cs_status guarded(cs_ctx* c, F&& body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(c, CS_ENOMEM, "host memory allocation failed");
+    } catch (...) {
+        return fail(c, CS_EHIP, "unexpected internal error");
+    }
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -185,6 +195,7 @@ cs_status cs_create(cs_ctx** out, int device, void* hip_stream, size_t scratch_b
     if ((e = hipSetDevice(device)) != hipSuccess) return CS_EHIP;
     cs_ctx* c = new (std::nothrow) cs_ctx();
     if (!c) return CS_ENOMEM;
+    c->err[0] = 0;
     c->device = device;
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->scratch_bytes = scratch_bytes ? scratch_bytes : kDefaultScratch;
@@ -217,7 +228,7 @@ void cs_destroy(cs_ctx* c) {
     delete c;
 }
 
-const char* cs_last_error(const cs_ctx* c) { return c ? c->err.c_str() : "no context"; }
+const char* cs_last_error(const cs_ctx* c) { return c ? c->err : "no context"; }
 
 cs_status cs_set_stream(cs_ctx* c, void* hip_stream) {
     if (!c) return CS_EINVAL;
@@ -227,16 +238,56 @@ cs_status cs_set_stream(cs_ctx* c, void* hip_stream) {
 
 cs_status cs_plan(cs_ctx* c, const cs_op* op, const cs_dict* dict) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_op(c, op, "cs_plan")) != CS_OK) return st;
     if ((st = check_dict(c, op, dict, "cs_plan")) != CS_OK) return st;
     if ((st = bind_device(c)) != CS_OK) return st;
     const Plan* plan = nullptr;
     return find_or_build_plan(c, op, dict, &plan);
+    });
+}
+
+cs_status cs_plan_drop(cs_ctx* c, const cs_op* op, const cs_dict* dict) {
+    if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
+    if (!op || !dict) return fail(c, CS_EINVAL, "cs_plan_drop: NULL operator or dictionary");
+    cs_status st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    for (size_t i = 0; i < c->plans.size(); ++i) {
+        const PlanEntry& pe = c->plans[i];
+        if (!(pe.op.ens == op->ens && pe.op.seed == op->seed && pe.op.stream_id == op->stream_id &&
+              pe.op.m == op->m && pe.op.n == op->n && pe.psi == dict->psi && pe.G == dict->G &&
+              pe.b == dict->b && pe.rb == dict->rb))
+            continue;
+        // work that reads the plan may still be queued
+        hipError_t e = hipStreamSynchronize(c->stream);
+        if (e != hipSuccess) return hip_fail(c, e, "cs_plan_drop: stream synchronisation");
+        const float* atoms = pe.plan.Mt;
+        for (size_t g = 0; g < c->groups.size();) {           // device tables that list this plan go with it
+            bool uses = false;
+            for (const float* key : c->groups[g].key) uses = uses || key == atoms;
+            if (uses) {
+                if (c->groups[g].d_plans) (void)hipFree(c->groups[g].d_plans);
+                c->groups.erase(c->groups.begin() + (long)g);
+            } else {
+                ++g;
+            }
+        }
+        if (pe.plan.Mt) (void)hipFree(pe.plan.Mt);
+        if (pe.plan.Mr) (void)hipFree(pe.plan.Mr);
+        if (pe.plan.gram) (void)hipFree(pe.plan.gram);
+        if (pe.plan.W) (void)hipFree(pe.plan.W);
+        c->plans.erase(c->plans.begin() + (long)i);
+        return CS_OK;
+    }
+    return CS_OK;                                             // nothing cached: nothing to do
+    });
 }
 
 cs_status cs_sketch(cs_ctx* c, const cs_op* op, const float* z, int B, float* y) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_op(c, op, "cs_sketch")) != CS_OK) return st;
     if (B < 0) return fail(c, CS_EINVAL, "cs_sketch: B < 0");
@@ -249,10 +300,12 @@ cs_status cs_sketch(cs_ctx* c, const cs_op* op, const float* z, int B, float* y)
     hipError_t e = launch_sketch(make_desc(*op), z, B, y, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_sketch");
     return CS_OK;
+    });
 }
 
 cs_status cs_sketch_multi(cs_ctx* c, int n_ops, const cs_op* ops, const float* z, int B, float* y) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     if (n_ops < 1 || n_ops > 65535) return fail(c, CS_EINVAL, "cs_sketch_multi: n_ops=%d out of range [1, 65535]", n_ops);
     if (!ops) return fail(c, CS_EINVAL, "cs_sketch_multi: NULL operator list");
     cs_status st;
@@ -273,12 +326,14 @@ cs_status cs_sketch_multi(cs_ctx* c, int n_ops, const cs_op* ops, const float* z
     hipError_t e = launch_sketch_multi(descs.data(), n_ops, z, B, y, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_sketch_multi");
     return CS_OK;
+    });
 }
 
 cs_status cs_recover_support(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k,
                              const float* y, int B,
                              int32_t* support, float* coef, float* resid_norm, float* margin) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_recover_args(c, op, dict, k, "cs_recover_support")) != CS_OK) return st;
     if (B < 0) return fail(c, CS_EINVAL, "cs_recover_support: B < 0");
@@ -288,12 +343,14 @@ cs_status cs_recover_support(cs_ctx* c, const cs_op* op, const cs_dict* dict, in
         return fail(c, CS_EALIGN, "cs_recover_support: buffer not 16-byte aligned");
     if ((st = bind_device(c)) != CS_OK) return st;
     return run_recover(c, op, dict, k, y, B, support, coef, resid_norm, margin, 0, "cs_recover_support");
+    });
 }
 
 cs_status cs_recover_support_multi(cs_ctx* c, int n_ops, const cs_op* ops, const cs_dict* dicts, int k,
                                    const float* y, int B,
                                    int32_t* support, float* coef, float* resid_norm, float* margin) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     if (n_ops < 1 || n_ops > 65535) return fail(c, CS_EINVAL, "cs_recover_support_multi: n_ops=%d out of range [1, 65535]", n_ops);
     if (!ops || !dicts) return fail(c, CS_EINVAL, "cs_recover_support_multi: NULL operator or dictionary list");
     cs_status st;
@@ -343,12 +400,14 @@ cs_status cs_recover_support_multi(cs_ctx* c, int n_ops, const cs_op* ops, const
     hipError_t e = launch_recover(host_plans[0], a, c->lds_limit, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_multi");
     return CS_OK;
+    });
 }
 
 cs_status cs_recover_support_iht(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k, int iters,
                                  const float* y, int B,
                                  int32_t* support, float* coef, float* resid_norm, float* margin) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_recover_args(c, op, dict, k, "cs_recover_support_iht")) != CS_OK) return st;
     if (iters < 1) return fail(c, CS_EINVAL, "cs_recover_support_iht: iters < 1");
@@ -368,6 +427,7 @@ cs_status cs_recover_support_iht(cs_ctx* c, const cs_op* op, const cs_dict* dict
     hipError_t e = launch_recover_iht(*plan, a, iters, c->lds_limit, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_iht");
     return CS_OK;
+    });
 }
 
 cs_status cs_recover_support_inc(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k,
@@ -375,6 +435,7 @@ cs_status cs_recover_support_inc(cs_ctx* c, const cs_op* op, const cs_dict* dict
                                  const int32_t* prev_support, const float* prev_coef, float gamma, int swaps,
                                  int32_t* support, float* coef, float* resid_norm, float* margin) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_recover_args(c, op, dict, k, "cs_recover_support_inc")) != CS_OK) return st;
     if (swaps < 0 || swaps > k) return fail(c, CS_EINVAL, "cs_recover_support_inc: swaps=%d out of range [0, k=%d]", swaps, k);
@@ -398,12 +459,14 @@ cs_status cs_recover_support_inc(cs_ctx* c, const cs_op* op, const cs_dict* dict
     hipError_t e = launch_recover_inc(*plan, a, q, c->lds_limit, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_inc");
     return CS_OK;
+    });
 }
 
-cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
-                       int d, int G, int b, const void* x, int T,
-                       const int32_t* support, int k, int shared, void* out) {
-    if (!c) return CS_EINVAL;
+static cs_status block_ffn_with_scratch(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
+                                        int d, int G, int b, const void* x, int T,
+                                        const int32_t* support, int k, int shared, void* out,
+                                        void* work, size_t work_bytes, const char* work_name) {
+    return guarded(c, [&]() -> cs_status {
     if (dtype != CS_F32 && dtype != CS_BF16) return fail(c, CS_EINVAL, "cs_block_ffn: unknown dtype %d", dtype);
     if (d < 8 || (d % 8) || b < 8 || (b % 8) || G < 1) return fail(c, CS_EINVAL, "cs_block_ffn: need d %% 8 == 0, b %% 8 == 0, G >= 1");
     if (k < 0 || k > G) return fail(c, CS_EINVAL, "cs_block_ffn: k=%d out of range [0, G=%d]", k, G);
@@ -423,18 +486,28 @@ cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, con
     FfnArgs a;
     a.dtype = dtype; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.d = d; a.G = G; a.b = b;
     a.x = x; a.T = T; a.support = support; a.k = k; a.shared = shared ? 1 : 0; a.out = out;
-    a.scratch = c->scratch; a.scratch_bytes = c->scratch_bytes;
+    a.scratch = work; a.scratch_bytes = work_bytes;
     const size_t need = ffn_scratch_bytes(a);
-    if (need > c->scratch_bytes)
-        return fail(c, CS_ENOMEM, "cs_block_ffn: needs %zu bytes of scratch, context has %zu", need, c->scratch_bytes);
+    if (need > work_bytes)
+        return fail(c, CS_ENOMEM, "cs_block_ffn: needs %zu bytes of scratch, %s has %zu", need, work_name, work_bytes);
     hipError_t e = launch_block_ffn(a, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_block_ffn");
     return CS_OK;
+    });
+}
+
+cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
+                       int d, int G, int b, const void* x, int T,
+                       const int32_t* support, int k, int shared, void* out) {
+    if (!c) return CS_EINVAL;
+    return block_ffn_with_scratch(c, dtype, Wg, Wu, Wd, d, G, b, x, T, support, k, shared, out,
+                                  c->scratch, c->scratch_bytes, "the context");
 }
 
 cs_status cs_head_attn(cs_ctx* c, int dtype, const void* q, const void* K, const void* V,
                        int B, int H, int L, int dh, const int32_t* heads, int kh, void* out) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     if (dtype != CS_F32 && dtype != CS_BF16) return fail(c, CS_EINVAL, "cs_head_attn: unknown dtype %d", dtype);
     if (dh != 64 && dh != 128 && dh != 256) return fail(c, CS_EINVAL, "cs_head_attn: dh must be 64, 128 or 256");
     if (H < 1 || L < 1) return fail(c, CS_EINVAL, "cs_head_attn: need H >= 1 and L >= 1");
@@ -455,12 +528,14 @@ cs_status cs_head_attn(cs_ctx* c, int dtype, const void* q, const void* K, const
     hipError_t e = launch_head_attn(a, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_head_attn");
     return CS_OK;
+    });
 }
 
 cs_status cs_joint_select(cs_ctx* c, const cs_op* tok_op, const float* y_tok, int k_tok,
                           const cs_op* ch_op, const cs_dict* ch_dict, const float* y_ch, int k_ch,
                           int32_t* tokens, int32_t* support, float* resid_norm, float* margin) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_op(c, tok_op, "cs_joint_select(tokens)")) != CS_OK) return st;
     if (k_tok < 1 || k_tok > tok_op->n) return fail(c, CS_EINVAL, "cs_joint_select: k_tok=%d out of range [1, n=%d]", k_tok, tok_op->n);
@@ -480,6 +555,7 @@ cs_status cs_joint_select(cs_ctx* c, const cs_op* tok_op, const float* y_tok, in
     if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select: top-k");
     return run_recover(c, ch_op, ch_dict, k_ch, y_ch, 1, support, nullptr, resid_norm, margin, proxy_bytes,
                        "cs_joint_select: recovery");
+    });
 }
 
 cs_status cs_joint_select_coupled(cs_ctx* c, const cs_op* tok_op, const float* y_tok, int k_tok,
@@ -487,6 +563,7 @@ cs_status cs_joint_select_coupled(cs_ctx* c, const cs_op* tok_op, const float* y
                                   int32_t* tokens, int32_t* support, float* ybar,
                                   float* resid_norm, float* margin) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     cs_status st;
     if ((st = check_op(c, tok_op, "cs_joint_select_coupled(tokens)")) != CS_OK) return st;
     if (k_tok < 1 || k_tok > tok_op->n)
@@ -516,10 +593,12 @@ cs_status cs_joint_select_coupled(cs_ctx* c, const cs_op* tok_op, const float* y
     if (e != hipSuccess) return hip_fail(c, e, "cs_joint_select_coupled: pooling");
     return run_recover(c, ch_op, ch_dict, k_ch, pooled, 1, support, nullptr, resid_norm, margin, used,
                        "cs_joint_select_coupled: recovery");
+    });
 }
 
 cs_status cs_softmax_entropy(cs_ctx* c, const float* logits, int B, int V, float* entropy) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     if (B < 0 || B > 65535) return fail(c, CS_EINVAL, "cs_softmax_entropy: B out of range [0, 65535]");
     if (V < 1) return fail(c, CS_EINVAL, "cs_softmax_entropy: V < 1");
     if (B == 0) return CS_OK;
@@ -533,6 +612,7 @@ cs_status cs_softmax_entropy(cs_ctx* c, const float* logits, int B, int V, float
     hipError_t e = launch_softmax_entropy(logits, B, V, reinterpret_cast<float*>(c->scratch), entropy, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_softmax_entropy");
     return CS_OK;
+    });
 }
 
 int32_t cs_uds_budget(int32_t m_base, float gamma, float entropy, int32_t m_min, int32_t m_max) {
@@ -546,6 +626,7 @@ int32_t cs_uds_budget(int32_t m_base, float gamma, float entropy, int32_t m_min,
 cs_status cs_gather_rows(cs_ctx* c, int dtype, const void* x, int n_rows, int d,
                          const int32_t* tokens, int k_tok, void* out) {
     if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
     if (dtype != CS_F32 && dtype != CS_BF16) return fail(c, CS_EINVAL, "cs_gather_rows: unknown dtype %d", dtype);
     if (d < 8 || (d % 8) || n_rows < 1) return fail(c, CS_EINVAL, "cs_gather_rows: need d %% 8 == 0 and n_rows >= 1");
     if (k_tok < 0 || k_tok > 65535 * 1024) return fail(c, CS_EINVAL, "cs_gather_rows: k_tok out of range");
@@ -557,6 +638,7 @@ cs_status cs_gather_rows(cs_ctx* c, int dtype, const void* x, int n_rows, int d,
     hipError_t e = launch_gather_rows(x, n_rows, (size_t)d * (dtype == CS_F32 ? 4 : 2), tokens, k_tok, out, c->stream);
     if (e != hipSuccess) return hip_fail(c, e, "cs_gather_rows");
     return CS_OK;
+    });
 }
 
 }  // extern "C"

@@ -13,11 +13,13 @@ def pytest_configure(config):
 
 @pytest.fixture(scope="session")
 def cs():
-    """The ctypes binding over the HIP library, with a context on cuda:0."""
+    """The ctypes binding over the HIP library, with a context on cuda:0.  Result buffers that the
+    binding allocates sit between guard bands, verified after every call (gpu_util.guarded_context)."""
     import torch
-    from paper_2604_14156_amd import binding
+    import gpu_util
     if not torch.cuda.is_available():
         pytest.fail("GPU test collected on a machine without a GPU")
-    ctx = binding.Context(device=0)
+    ctx = gpu_util.guarded_context(0)
     yield ctx
+    assert ctx.guards_checked > 0
     ctx.close()

@@ -1,16 +1,24 @@
 """GPU parity: block-sparse FFN and head-pruned attention against the CPU oracle,
 through the C ABI.  Tolerances: fp32 layers 1e-5, bf16 layers 2e-2 (relative L2
-error of each output row against the unrounded fp64 oracle)."""
+error of each output row against the unrounded fp64 oracle), and for every single
+element |got - want| <= 4e-5 (fp32) or 2e-2 (bf16) times the root mean square of
+the oracle's row, so that one wrong element cannot hide in a row norm."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 from paper_2604_14156_amd import binding, workloads as wl
-from gpu_util import dev_w, dev_bf16, dev_i32, host, rel_err
+from gpu_util import dev_w, dev_bf16, dev_i32, host, rel_err, max_abs_over_rms, assert_greedy_support, dev_f32
 
 pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+ELT = {"f32": 4e-5, "bf16": 2e-2}
+
+
+def check_row(got, want, dtype="bf16", what=None):
+    e2, emax = rel_err(got, want), max_abs_over_rms(got, want)
+    assert e2 <= TOL[dtype] and emax <= ELT[dtype], (what, e2, emax)
 
 
 def _ffn_case(cs, seed, G, b, d, k, T, dtype, shared, std):
@@ -24,7 +32,7 @@ def _ffn_case(cs, seed, G, b, d, k, T, dtype, shared, std):
                                dev_i32(sup), shared))
     want = oracle.block_ffn(Wg, Wu, Wd, x, sup)
     for t in range(T):
-        assert rel_err(out[t], want[t]) <= TOL[dtype], (t, rel_err(out[t], want[t]))
+        check_row(out[t], want[t], dtype, t)
 
 
 def test_ffn_tiny_planted_config(cs):
@@ -53,17 +61,37 @@ def test_ffn_bf16_many_rows_matrix_core_path(cs, T, shared, G, k, d):
 
 
 def test_ffn_prefill_shape_full_size(cs):
-    """Task-conditioned prefill at full size: weights drawn on the device, oracle on sampled rows."""
+    """Task-conditioned prefill at full size, the whole chain: the prompt-level usage is sketched, one
+    support is recovered from the sketch (compared with the oracle's), and that support (still on the
+    device) drives the shared-support layer over 2048 rows.  Weights are drawn on the device; the oracle
+    computes 48 rows spread over all row tiles, among them the first and last of a tile."""
     c = wl.CFG4
     T = 2048
+    seed = 4001
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi, c.k, 2, c.amp, c.bg)
+    z, S = z[1:2], S[1:2]                                         # the second instance: oracle margin 2.3e-3
+    op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    cs.cs_plan(op, dct, psi_dev)
+    y = cs.cs_sketch(op, dev_f32(z))
+    sup_dev = cs.cs_recover_support(op, dct, c.k, y, want_coef=False, want_resid=False)[0]
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    y_or = oracle.sketch(c.ens, seed, 0, c.m, z[0])
+    rec = oracle.block_omp(M, y_or, c.G, 1, c.k, True)
+    sup = host(sup_dev)[0]
+    assert assert_greedy_support(M, y_or, c.G, 1, c.k, True, sup, rec)        # the exact comparison applies
+    assert list(sup) == list(S[0])
+
     gen = torch.Generator(device="cuda:0").manual_seed(41)
     Wg, Wu = (torch.randn((c.G, c.b, c.d), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16) for _ in range(2))
     Wd = torch.randn((c.G, c.d, c.b), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16)
     x = torch.randn((T, c.d), generator=gen, device="cuda:0").to(torch.bfloat16)
-    sup = wl.random_supports(wl.rng_for(41), c.G, c.k, 1)[0]
-    out = cs.cs_block_ffn(Wg, Wu, Wd, x, dev_i32(sup), True)
+    out = cs.cs_block_ffn(Wg, Wu, Wd, x, sup_dev[0], True)
     torch.cuda.synchronize()
-    rows = [0, 127, 128, 1000, 2047]
+    rows = sorted(set([0, 127, 128, 255, 256, 1000, 1023, 1024, 2046, 2047] + list(range(5, T, 53))))
     hx = host(x[rows])
     # the oracle needs only the kept blocks: gather them on the device, upcast on the host
     idx = torch.from_numpy(sup.astype(np.int64)).to("cuda:0")
@@ -71,7 +99,11 @@ def test_ffn_prefill_shape_full_size(cs):
     want = oracle.block_ffn(hWg, hWu, hWd, hx, np.arange(c.k))
     got = host(out[rows])
     for i in range(len(rows)):
-        assert rel_err(got[i], want[i]) <= 2e-2, (rows[i], rel_err(got[i], want[i]))
+        check_row(got[i], want[i], "bf16", rows[i])
+    # every row was written: no row of the output is far from the scale of the checked ones
+    norms = out.float().norm(dim=1)
+    ref = float(np.median(np.linalg.norm(want, axis=1)))
+    assert float(norms.min()) > 0.5 * ref and float(norms.max()) < 2.0 * ref
 
 
 @pytest.mark.parametrize("T,shared,G,k,d", [(2100, True, 40, 35, 4160), (2052, False, 40, 9, 4128), (1300, True, 64, 63, 2080)])
@@ -93,7 +125,7 @@ def test_ffn_wide_tiles_ragged_shapes(cs, T, shared, G, k, d):
     got = host(out[rows])
     for i, r in enumerate(rows):
         want = oracle.block_ffn(hWg, hWu, hWd, host(x[r:r + 1]), sup if shared else sup[r])[0]
-        assert rel_err(got[i], want) <= 2e-2, (r, rel_err(got[i], want))
+        check_row(got[i], want, "bf16", r)
 
 
 def test_joint_prompt_shape_gather_and_ffn(cs):
@@ -111,12 +143,12 @@ def test_joint_prompt_shape_gather_and_ffn(cs):
     torch.cuda.synchronize()
     assert torch.equal(Xk, X[torch.from_numpy(tokens.astype(np.int64)).to("cuda:0")])       # byte-exact copy
     out = cs.cs_block_ffn(Wg, Wu, Wd, Xk, dev_i32(sup), True)
-    rows = [0, 1, 1023, 2047]
+    rows = sorted(set([0, 1, 127, 128, 1023, 1024, 2046, 2047] + list(range(3, k_tok, 41))))
     idx = torch.from_numpy(sup.astype(np.int64)).to("cuda:0")
     want = oracle.block_ffn(host(Wg[idx]), host(Wu[idx]), host(Wd[idx]), host(X[tokens[rows].astype(np.int64)]), np.arange(c.k))
     got = host(out[rows])
     for i in range(len(rows)):
-        assert rel_err(got[i], want[i]) <= 2e-2
+        check_row(got[i], want[i], "bf16", rows[i])
     # an out-of-range token yields a zero row
     z = cs.cs_gather_rows(X, dev_i32(np.array([5, n_tok, -1, 7], dtype=np.int32)))
     torch.cuda.synchronize()
@@ -141,7 +173,7 @@ def test_ffn_empty_cases(cs):
     got = host(cs.cs_block_ffn(*dW, dev_bf16(x), dev_i32(sup), False))
     want = np.stack([oracle.block_ffn(Wg, Wu, Wd, x[t:t + 1], [g for g in sup[t] if 0 <= g < 4])[0] for t in range(3)])
     for t in range(3):
-        assert rel_err(got[t], want[t]) <= 2e-2
+        check_row(got[t], want[t], "bf16", t)
     with pytest.raises(binding.CsError) as e:
         cs.cs_block_ffn(*dW, dev_bf16(x), dev_i32(np.zeros((3, 5))), False)    # k > G
     assert e.value.status == binding.CS_EINVAL
@@ -168,11 +200,11 @@ def test_ffn_decode_dense_union_guess(cs, case):
     out = host(cs.cs_block_ffn(dev_bf16(Wg), dev_bf16(Wu), dev_bf16(Wd), dev_bf16(x), dev_i32(sup), False))
     want = oracle.block_ffn(Wg, Wu, Wd, x, sup)
     for t in range(T):
-        assert rel_err(out[t], want[t]) <= 2e-2, (case, t, rel_err(out[t], want[t]))
+        check_row(out[t], want[t], "bf16", (case, t))
 
 
 def _full_size_ffn(cs, B, seed):
-    """Decode shape at full size: weights drawn on the device, oracle on sampled tokens."""
+    """Decode shape at full size: weights drawn on the device, every token against the oracle."""
     c = wl.CFG2
     gen = torch.Generator(device="cuda:0").manual_seed(seed)
     Wg, Wu = (torch.randn((c.G, c.b, c.d), generator=gen, device="cuda:0").mul_(c.wstd).to(torch.bfloat16) for _ in range(2))
@@ -181,12 +213,12 @@ def _full_size_ffn(cs, B, seed):
     sup = wl.random_supports(wl.rng_for(seed), c.G, c.k, B)
     out = host(cs.cs_block_ffn(Wg, Wu, Wd, x, dev_i32(sup), False))
     hWg, hWu, hWd, hx = host(Wg), host(Wu), host(Wd), host(x)
-    for t in sorted(set([0, B // 2, B - 1])):
+    for t in range(B):
         want = oracle.block_ffn(hWg, hWu, hWd, hx[t:t + 1], sup[t])[0]
-        assert rel_err(out[t], want) <= 2e-2, (t, rel_err(out[t], want))
+        check_row(out[t], want, "bf16", t)
 
 
-@pytest.mark.parametrize("B", [1, 8, 16, 64])
+@pytest.mark.parametrize("B", [1, 8, 16, 17, 33, 64])
 def test_ffn_decode_shape_full_size(cs, B):
     _full_size_ffn(cs, B, 2000 + B)
 
@@ -201,7 +233,7 @@ def _attn_case(cs, seed, B, H, L, dh, kh):
         kept = set(heads[b].tolist())
         for h in range(H):
             if h in kept:
-                assert rel_err(out[b, h], want[b, h]) <= 2e-2, (b, h)
+                check_row(out[b, h], want[b, h], "bf16", (b, h))
             else:
                 assert np.all(out[b, h] == 0.0)
 
@@ -222,11 +254,12 @@ def test_attention_decode_shape_full_size(cs):
     heads = wl.random_supports(wl.rng_for(31), hs.H, hs.kh, B)
     out = host(cs.cs_head_attn(q, K, V, dev_i32(heads)))
     hq = host(q)
-    for b in (0, 7, 15):
-        for h in (int(heads[b][0]), int(heads[b][-1])):
+    for b in range(B):                                 # every kept (sequence, head) pair, every pruned head
+        for h in heads[b]:
+            h = int(h)
             want = oracle.head_attn(hq[b:b + 1, h:h + 1], host(K[b:b + 1, h:h + 1]), host(V[b:b + 1, h:h + 1]),
                                     np.array([[0]]))[0, 0]
-            assert rel_err(out[b, h], want) <= 2e-2
+            check_row(out[b, h], want, "bf16", (b, h))
         pruned = sorted(set(range(hs.H)) - set(heads[b].tolist()))
         assert np.all(out[b, pruned] == 0.0)
 
@@ -246,7 +279,7 @@ def test_attention_wide_workgroups_ragged_cache(cs, B, H, L, dh, kh):
         for h in (int(heads[b][0]), int(heads[b][kh // 2]), int(heads[b][-1])):
             want = oracle.head_attn(hq[b:b + 1, h:h + 1], host(K[b:b + 1, h:h + 1]), host(V[b:b + 1, h:h + 1]),
                                     np.array([[0]]))[0, 0]
-            assert rel_err(out[b, h], want) <= 2e-2, (b, h)
+            check_row(out[b, h], want, "bf16", (b, h))
     for b in range(B):
         pruned = sorted(set(range(H)) - set(heads[b].tolist()))
         assert np.all(out[b, pruned] == 0.0)
@@ -262,4 +295,4 @@ def test_attention_sharp_scores_do_not_overflow(cs):
     want = oracle.head_attn(q, K, V, heads)
     assert np.all(np.isfinite(out))
     for h in range(2):
-        assert rel_err(out[0, h], want[0, h]) <= 2e-2
+        check_row(out[0, h], want[0, h], "bf16", h)

@@ -1,6 +1,9 @@
 """GPU parity: sketch, recovery and joint selection against the CPU oracle,
 through the C ABI.  Tolerances: supports bit-exact when the oracle's selection
-margin exceeds 1e-3; ||r_gpu - r_oracle|| <= 1e-5 ||y||; sketches within 1e-5."""
+margin exceeds 1e-3; below that margin several supports are correct, and the
+GPU's must be one of them: the oracle, told to prefer the GPU's units wherever
+they score within a factor 1/(1+1e-3) of the best, has to reproduce it, with
+the same residual.  ||r_gpu - r_oracle|| <= 1e-5 ||y||; sketches within 1e-5."""
 import math
 import numpy as np
 import pytest
@@ -8,11 +11,12 @@ import torch
 
 import oracle
 from paper_2604_14156_amd import binding, workloads as wl
-from gpu_util import dev_f32, dev_i32, host, rel_err
+from gpu_util import dev_f32, dev_i32, host, rel_err, assert_greedy_support
 
 pytestmark = pytest.mark.gpu
 
 MARGIN = 1e-3
+SLACK = 1e-3
 RES_TOL = 1e-5
 
 
@@ -77,6 +81,12 @@ def _check_recovery(cs, op, dct, psi_dev, M, Y, G, rb, k, normalised):
             assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm
             assert abs(margin[t] - rec["margin"]) <= 1e-3
             exact += 1
+        else:
+            # a near tie somewhere on the way: the GPU's support must be a greedy path up to the slack
+            rep = oracle.block_omp(M, y, G, rb, k, normalised, prefer=s, slack=SLACK)
+            assert list(rep["support"]) == list(s), (t, rec["margin"], sorted(set(s) ^ set(rec["support"])))
+            assert abs(resid[t] - rep["resid_norm"]) <= RES_TOL * ynorm
+            assert margin[t] <= rec["margin"] + 1e-3
     return exact
 
 
@@ -113,14 +123,13 @@ def test_decode_shape_batch(cs):
     M = oracle.effective_matrix(c.ens, seed, 4, c.m, c.n, c.G, c.b, 1, psi)
     Y = oracle.sketch(c.ens, seed, 4, c.m, z).astype(np.float32)
     exact = _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True)
-    assert exact >= 3          # most instances clear the margin filter
+    assert exact == 6          # every instance of this seed clears the margin filter
     # end to end: the GPU's own sketch leads to the same supports where the margin allows
     y_gpu = cs.cs_sketch(op, dev_f32(z))
     sup = host(cs.cs_recover_support(op, dct, c.k, y_gpu)[0])
     for t in range(6):
         rec = oracle.block_omp(M, Y[t].astype(np.float64), c.G, 1, c.k, True)
-        if rec["margin"] > MARGIN:
-            assert list(sup[t]) == list(rec["support"])
+        assert_greedy_support(M, Y[t].astype(np.float64), c.G, 1, c.k, True, sup[t], rec)
 
 
 def test_literal_entrywise_usage_still_matches_oracle(cs):
@@ -134,7 +143,8 @@ def test_literal_entrywise_usage_still_matches_oracle(cs):
     dct = binding.make_dict(psi_dev, c.G, c.b, 1)
     M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
     Y = oracle.sketch(c.ens, seed, 0, c.m, z).astype(np.float32)
-    _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True)
+    # one of the three instances clears the margin filter, the other two go through the near-tie replay
+    assert _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True) == 1
 
 
 def test_head_selection_shape(cs):
@@ -147,21 +157,29 @@ def test_head_selection_shape(cs):
     M = oracle.effective_matrix(hs.ens, seed, 3, hs.m, hs.H, hs.H, 1, 1, None)
     Y = oracle.sketch(hs.ens, seed, 3, hs.m, u).astype(np.float32)
     exact = _check_recovery(cs, op, dct, None, M, Y, hs.H, 1, hs.kh, False)
-    assert exact >= 10
+    assert exact == 15         # of 16
 
 
 def test_prefill_shape_uses_the_spill_path(cs):
+    """One support per prompt at full size (k = 112 of 448 units, m = 512).  Six instances of seed 4001:
+    the oracle's margins are 1.7e-4, 2.3e-3, 2.1e-4, 3.3e-3, 1.2e-3, 2.2e-3, so four are compared bit for
+    bit and two go through the near-tie replay; the oracle recovers all 112 planted units in each."""
     c = wl.CFG4
-    seed = 4000
+    seed = 4001
+    B = 6
     rng = wl.rng_for(seed)
     pi, psi = wl.make_profiles(rng, c.G, c.b)
-    z, S = wl.plant_usage(rng, pi, c.k, 1, c.amp, c.bg)
+    z, S = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
     op = binding.make_op(c.ens, seed, 0, c.m, c.n)
     psi_dev = dev_f32(psi)
     dct = binding.make_dict(psi_dev, c.G, c.b, 1)
     M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
     Y = oracle.sketch(c.ens, seed, 0, c.m, z).astype(np.float32)
-    _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True)
+    assert _check_recovery(cs, op, dct, psi_dev, M, Y, c.G, 1, c.k, True) == 4
+    # the planted supports come back (from the GPU's own sketches as well)
+    sup = host(cs.cs_recover_support(op, dct, c.k, cs.cs_sketch(op, dev_f32(z)))[0])
+    for t in range(B):
+        assert list(sup[t]) == list(S[t])
 
 
 def test_textbook_block_mode_identity_dictionary(cs):
@@ -179,7 +197,7 @@ def test_textbook_block_mode_identity_dictionary(cs):
             z[g * b:(g + 1) * b] = rng.standard_normal(b) + 3.0
         Y.append(M @ z + 1e-3 * rng.standard_normal(m))
     Y = np.array(Y, dtype=np.float32)
-    assert _check_recovery(cs, op, dct, None, M, Y, G, b, k, False) >= 4
+    assert _check_recovery(cs, op, dct, None, M, Y, G, b, k, False) == 5
 
 
 def test_rank_two_units_with_dictionary(cs):
@@ -200,7 +218,7 @@ def test_rank_two_units_with_dictionary(cs):
             alpha[g * rb:(g + 1) * rb] = rng.standard_normal(rb) * 3.0
         Y.append(M @ alpha + 1e-2 * rng.standard_normal(m))
     Y = np.array(Y, dtype=np.float32)
-    assert _check_recovery(cs, op, dct, psi_dev, M, Y, G, rb, k, True) >= 3
+    assert _check_recovery(cs, op, dct, psi_dev, M, Y, G, rb, k, True) == 5
 
 
 def test_recovery_degenerate_and_error_paths(cs):
@@ -261,6 +279,12 @@ def _check_iht(cs, op, dct, psi_dev, M, Y, G, k, iters, normalised):
             assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm
             assert abs(margin[t] - rec["margin"]) <= 1e-3
             exact += 1
+        else:
+            # a near tie at some projection: the oracle, preferring the GPU's units within the slack, must
+            # arrive at the same support
+            rep = oracle.block_iht(M, y, G, 1, k, iters, normalised, prefer=s, slack=SLACK)
+            assert list(rep["support"]) == list(s), (t, rec["min_margin"], sorted(set(s) ^ set(rec["support"])))
+            assert abs(resid[t] - rep["resid_norm"]) <= RES_TOL * ynorm
     return exact
 
 
@@ -277,7 +301,24 @@ def test_iht_decode_shape(cs, iters):
     M = oracle.effective_matrix(c.ens, seed, 4, c.m, c.n, c.G, c.b, 1, psi)
     Y = oracle.sketch(c.ens, seed, 4, c.m, z).astype(np.float32)
     exact = _check_iht(cs, op, dct, psi_dev, M, Y, c.G, c.k, iters, True)
-    assert exact >= (4 if iters == 1 else 1)
+    assert exact == 6
+
+
+def test_iht_literal_entrywise_usage(cs):
+    """Usage drawn entry by entry lies outside the dictionary's span: small gaps at the cut, so this is
+    where the near-tie replay gets exercised for the thresholding solver (seed 2104, 12 iterations: the
+    smallest gaps of the four instances are 7.9e-3, 2.4e-5, 1.6e-3, 5.2e-5)."""
+    c = wl.CFG2
+    seed = 2104
+    rng = wl.rng_for(seed)
+    _, psi = wl.make_profiles(rng, c.G, c.b)
+    z, _ = wl.plant_usage_literal(rng, c.G, c.b, c.k, 4, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi)
+    Y = oracle.sketch(c.ens, seed, 0, c.m, z).astype(np.float32)
+    assert _check_iht(cs, op, dct, psi_dev, M, Y, c.G, c.k, 12, True) == 2
 
 
 def test_iht_heads_tiny_and_errors(cs):
@@ -289,7 +330,7 @@ def test_iht_heads_tiny_and_errors(cs):
     dct = binding.make_dict(None, hs.H, 1, 1)
     M = oracle.effective_matrix(hs.ens, seed, 3, hs.m, hs.H, hs.H, 1, 1, None)
     Y = oracle.sketch(hs.ens, seed, 3, hs.m, u).astype(np.float32)
-    assert _check_iht(cs, op, dct, None, M, Y, hs.H, hs.kh, 8, False) >= 4
+    assert _check_iht(cs, op, dct, None, M, Y, hs.H, hs.kh, 8, False) == 15         # of 16
     # tiny planted instance: recovered exactly
     c = wl.CFG1
     rng = wl.rng_for(1000)
@@ -342,8 +383,7 @@ def test_joint_selection_prompt_shape(cs):
     assert sure_in <= got and not (got & sure_out)
     if srt[t["k_tok"] - 1] - srt[t["k_tok"]] > 2 * tol:
         assert list(tokens) == list(otok)
-    if rec["margin"] > MARGIN:
-        assert list(support) == list(rec["support"])
+    if assert_greedy_support(M, yc, c.G, 1, c.k, True, support, rec):
         assert abs(host(resid)[0] - rec["resid_norm"]) <= RES_TOL * np.linalg.norm(yc)
 
 
@@ -388,9 +428,7 @@ def test_multi_operator_recovery_equals_separate_calls(cs):
     hs_, exact = host(sup[-1]), 0
     for t in range(B):
         rec = oracle.block_omp(M, Ys[-1][t].astype(np.float64), c.G, 1, c.k, True)
-        if rec["margin"] > MARGIN:
-            assert list(hs_[t]) == list(rec["support"])
-            exact += 1
+        exact += assert_greedy_support(M, Ys[-1][t].astype(np.float64), c.G, 1, c.k, True, hs_[t], rec)
     assert exact >= 1
     # a second call with the same list reuses the device table; without margins and refit outputs too
     sup2 = cs.cs_recover_support_multi(ops, dcts, c.k, Y, want_coef=False, want_resid=False)[0]
@@ -488,9 +526,7 @@ def test_group_of_layers_full_size_sketch_and_recovery(cs):
         assert rel_err(host(Y[j, t]), want_y) <= 1e-5
         M = oracle.effective_matrix(c.ens, seed, 2 * j, c.m, c.n, c.G, c.b, 1, host(psis[j]).reshape(c.G, c.b, 1))
         rec = oracle.block_omp(M, want_y, c.G, 1, c.k, True)
-        if rec["margin"] > MARGIN:
-            assert list(hs_[j, t]) == list(rec["support"])
-            exact += 1
+        exact += assert_greedy_support(M, want_y, c.G, 1, c.k, True, hs_[j, t], rec)
     assert exact >= 1
 
 
@@ -514,3 +550,40 @@ def test_multi_operator_sketch_matrix_core_path(cs, m, n, B, n_ops):
         want = oracle.sketch(wl.RADEMACHER, 700 + 3 * j, 2 * j, m, z[j])
         for t in range(B):
             assert rel_err(got[j, t], want[t]) <= 1e-5
+
+
+def test_plan_drop_makes_a_reused_dictionary_address_safe(cs):
+    """The plan cache identifies a dictionary by its address.  New content at the same address is seen
+    only after cs_plan_drop; dropping twice, or a pair that was never planned, is not an error."""
+    c = wl.CFG1
+    seed = 9300
+    rng = wl.rng_for(seed)
+    pi_a, psi_a = wl.make_profiles(rng, c.G, c.b)
+    pi_b, psi_b = wl.make_profiles(rng, c.G, c.b)
+    z, S = wl.plant_usage(rng, pi_b, c.k, 2, c.amp, c.bg)          # planted in the span of the second dictionary
+    op = binding.make_op(c.ens, seed, 0, c.m, c.n)
+    buf = dev_f32(psi_a)
+    dct = binding.make_dict(buf, c.G, c.b, 1)
+    y = cs.cs_sketch(op, dev_f32(z))
+    stale = host(cs.cs_recover_support(op, dct, c.k, y)[0])         # plan of the first dictionary
+    buf.copy_(dev_f32(psi_b))                                       # same address, other content
+    torch.cuda.synchronize()
+    assert np.array_equal(host(cs.cs_recover_support(op, dct, c.k, y)[0]), stale)      # still the old plan
+    cs.cs_plan_drop(op, dct)
+    fresh = host(cs.cs_recover_support(op, dct, c.k, y)[0])
+    M = oracle.effective_matrix(c.ens, seed, 0, c.m, c.n, c.G, c.b, 1, psi_b)
+    for t in range(2):
+        rec = oracle.block_omp(M, host(y)[t], c.G, 1, c.k, True)
+        assert_greedy_support(M, host(y)[t], c.G, 1, c.k, True, fresh[t], rec)
+        assert list(fresh[t]) == list(S[t])
+    assert not np.array_equal(fresh, stale)
+    cs.cs_plan_drop(op, dct)
+    cs.cs_plan_drop(op, dct)
+    cs.cs_plan_drop(binding.make_op(c.ens, seed + 1, 0, c.m, c.n), dct)
+    # a multi-operator table that listed the dropped plan is rebuilt on the next use
+    ops = [op, binding.make_op(c.ens, seed, 1, c.m, c.n)]
+    Y = torch.stack([y, y])
+    first = cs.cs_recover_support_multi(ops, [dct, dct], c.k, Y)[0]
+    cs.cs_plan_drop(op, dct)
+    again = cs.cs_recover_support_multi(ops, [dct, dct], c.k, Y)[0]
+    assert torch.equal(first, again) and np.array_equal(host(again[0]), fresh)
