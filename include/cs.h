@@ -241,6 +241,24 @@ cs_status cs_block_ffn(cs_ctx* ctx, int dtype, const void* Wg, const void* Wu, c
                        const int32_t* support, int k, int shared, void* out);
 
 /*
+ * cs_block_ffn for callers that cannot allocate device memory and must not depend on a buffer that was
+ * allocated for them: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and same results as cs_block_ffn; the only difference is the workspace
+ * for the values handed from the first product to the second, which is a fixed array of
+ * CS_STATIC_SCRATCH_BYTES bytes in the library's device image instead of the context's scratch buffer.
+ * Every GPU the library runs on holds one copy of that array until the process ends.  The call itself
+ * allocates and frees nothing.  Shapes whose workspace exceeds the array return CS_ENOMEM with a message
+ * (the decode shapes fit: T <= 16 rows of bf16, up to 1024 units of 64 channels; long prefill batches
+ * do not).  All calls on one GPU share the array, whatever their context or stream: two such calls that
+ * overlap in time on one GPU race.  Nothing in it has to be zero at entry; each call overwrites what
+ * it reads.
+ */
+#define CS_STATIC_SCRATCH_BYTES (4u << 20)
+cs_status cs_block_ffn_static(cs_ctx* ctx, int dtype, const void* Wg, const void* Wu, const void* Wd,
+                              int d, int G, int b, const void* x, int T,
+                              const int32_t* support, int k, int shared, void* out);
+
+/*
  * Head-pruned single-query (decode) attention over a key/value cache: heads are
  * the structured units (Sec. 3, Sec. 7).  For every kept head h of sequence i:
  *   out[i][h] = softmax(q[i][h] . K[i][h][:]^T / sqrt(dh)) V[i][h][:]

@@ -17,7 +17,7 @@ CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_plan_drop", "cs_sketch", "cs_sketch_multi",
-           "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
+           "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_block_ffn_static", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
            "cs_softmax_entropy", "cs_uds_budget")
 
 
@@ -57,6 +57,7 @@ def load_library(path=LIB_PATH):
     lib.cs_recover_support_inc.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32,
                                            vp, vp, ctypes.c_float, i32, vp, vp, vp, vp]
     lib.cs_block_ffn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, i32, vp, i32, i32, vp]
+    lib.cs_block_ffn_static.argtypes = lib.cs_block_ffn.argtypes
     lib.cs_head_attn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
     lib.cs_joint_select.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict),
                                     vp, i32, vp, vp, vp, vp]
@@ -232,6 +233,10 @@ class Context:
                                                     _ptr(prev_support), _ptr(prev_coef), float(gamma), swaps,
                                                     _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
+
+    def cs_block_ffn_static(self, Wg, Wu, Wd, x, support, shared, out):
+        """The variant that allocates nothing: the caller passes `out`."""
+        return self.cs_block_ffn(Wg, Wu, Wd, x, support, shared, out, entry=self.lib.cs_block_ffn_static)
 
     def cs_block_ffn(self, Wg, Wu, Wd, x, support, shared, out=None, entry=None):
         G, b, d = Wg.shape

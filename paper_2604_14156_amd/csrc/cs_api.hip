@@ -32,7 +32,15 @@ struct cs_ctx {
     char err[512];
 };
 
+// Workspace of cs_block_ffn_static: device memory that exists from the moment the library is loaded, one
+// copy per GPU.  Host code never uses this name as an address; cs_create looks the device address up once
+// per device (hipGetSymbolAddress) and every later use goes through that pointer.
+static __device__ __align__(256) unsigned char scratch[CS_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {};          // per device: address of that device's copy of `scratch`
 
 constexpr size_t kDefaultScratch = 64ull << 20;
 constexpr int kMaxWeightedRb = 16;
@@ -193,6 +201,11 @@ cs_status cs_create(cs_ctx** out, int device, void* hip_stream, size_t scratch_b
     hipError_t e = hipGetDeviceCount(&ndev);
     if (e != hipSuccess || device < 0 || device >= ndev) { (void)hipGetLastError(); return CS_EHIP; }
     if ((e = hipSetDevice(device)) != hipSuccess) return CS_EHIP;
+    if (device < kMaxDevices && !g_static_scratch[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return CS_EHIP; }
+        g_static_scratch[device] = p;
+    }
     cs_ctx* c = new (std::nothrow) cs_ctx();
     if (!c) return CS_ENOMEM;
     c->err[0] = 0;
@@ -502,6 +515,16 @@ cs_status cs_block_ffn(cs_ctx* c, int dtype, const void* Wg, const void* Wu, con
     if (!c) return CS_EINVAL;
     return block_ffn_with_scratch(c, dtype, Wg, Wu, Wd, d, G, b, x, T, support, k, shared, out,
                                   c->scratch, c->scratch_bytes, "the context");
+}
+
+cs_status cs_block_ffn_static(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
+                              int d, int G, int b, const void* x, int T,
+                              const int32_t* support, int k, int shared, void* out) {
+    if (!c) return CS_EINVAL;
+    void* work = c->device < kMaxDevices ? g_static_scratch[c->device] : nullptr;
+    if (!work) return fail(c, CS_EHIP, "cs_block_ffn_static: no static workspace on device %d", c->device);
+    return block_ffn_with_scratch(c, dtype, Wg, Wu, Wd, d, G, b, x, T, support, k, shared, out,
+                                  work, (size_t)CS_STATIC_SCRATCH_BYTES, "the static workspace");
 }
 
 cs_status cs_head_attn(cs_ctx* c, int dtype, const void* q, const void* K, const void* V,
