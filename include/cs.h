@@ -322,6 +322,17 @@ cs_status cs_softmax_entropy(cs_ctx* ctx, const float* logits, int B, int V, flo
 int32_t cs_uds_budget(int32_t m_base, float gamma, float entropy, int32_t m_min, int32_t m_max);
 
 /*
+ * Diagnostic, not a step of the method: read `bytes` bytes of device memory once, 16 bytes per lane, and
+ * xor every 32-bit word read into checksum[0] (atomically; zero it beforehand to get the xor of the
+ * buffer; a trailing bytes % 16 is not read).  The duration of this call is what a plain streaming read
+ * reaches on the device.  Sec. 14 and Sec. 15 ask for latency on real hardware, where the
+ * bandwidth-bound calls (decode FFN, attention over the cache) are limited by the memory system; the
+ * benchmark reports their bandwidth against the published peak and against this measured ceiling.
+ *   src: device pointer, 16-byte aligned;  checksum: device uint32_t[1].
+ */
+cs_status cs_stream_read(cs_ctx* ctx, const void* src, size_t bytes, uint32_t* checksum);
+
+/*
  * Token-selection operator of Sec. 6 (the retained prompt x~ = Pi(r) x): copy the rows
  * of x named by `tokens` into a dense matrix, in the order given.
  *   x: [n_rows][d] in, tokens: int32[k_tok] with entries in [0, n_rows), out: [k_tok][d] out,

@@ -18,7 +18,7 @@ CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_plan_drop", "cs_sketch", "cs_sketch_multi",
            "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_block_ffn_static", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
-           "cs_softmax_entropy", "cs_uds_budget")
+           "cs_softmax_entropy", "cs_uds_budget", "cs_stream_read")
 
 
 class CsOp(ctypes.Structure):
@@ -65,6 +65,7 @@ def load_library(path=LIB_PATH):
                                             vp, i32, vp, vp, vp, vp, vp]
     lib.cs_softmax_entropy.argtypes = [vp, vp, i32, i32, vp]
     lib.cs_uds_budget.argtypes = [ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_int32]
+    lib.cs_stream_read.argtypes = [vp, vp, u64, vp]
     lib.cs_gather_rows.argtypes = [vp, i32, vp, i32, i32, vp, i32, vp]
     for name in EXPORTS:
         if name not in ("cs_destroy", "cs_last_error"):
@@ -279,6 +280,11 @@ class Context:
 
     def cs_uds_budget(self, m_base, gamma, entropy, m_min, m_max):
         return int(self.lib.cs_uds_budget(int(m_base), float(gamma), float(entropy), int(m_min), int(m_max)))
+
+    def cs_stream_read(self, src, checksum):
+        """Diagnostic streaming read of the whole tensor `src`; checksum: uint32/int32 tensor of one element."""
+        self._check(self.lib.cs_stream_read(self._h, _ptr(src), src.numel() * src.element_size(), _ptr(checksum)))
+        return checksum
 
     def cs_gather_rows(self, x, tokens, out=None):
         n_rows, d = x.shape

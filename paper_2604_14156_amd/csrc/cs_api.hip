@@ -638,6 +638,21 @@ cs_status cs_softmax_entropy(cs_ctx* c, const float* logits, int B, int V, float
     });
 }
 
+cs_status cs_stream_read(cs_ctx* c, const void* src, size_t bytes, uint32_t* checksum) {
+    if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
+    if (bytes == 0) return CS_OK;
+    if (!src || !checksum) return fail(c, CS_EINVAL, "cs_stream_read: NULL buffer");
+    if (!aligned16(src) || (reinterpret_cast<uintptr_t>(checksum) & 3u))
+        return fail(c, CS_EALIGN, "cs_stream_read: src must be 16-byte aligned, checksum 4-byte aligned");
+    cs_status st;
+    if ((st = bind_device(c)) != CS_OK) return st;
+    hipError_t e = launch_stream_read(src, bytes, checksum, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_stream_read");
+    return CS_OK;
+    });
+}
+
 int32_t cs_uds_budget(int32_t m_base, float gamma, float entropy, int32_t m_min, int32_t m_max) {
     if (m_min > m_max || m_min < 1 || !std::isfinite(gamma) || !std::isfinite(entropy)) return -1;
     const double v = std::floor((double)m_base * (1.0 + (double)gamma * (double)entropy));

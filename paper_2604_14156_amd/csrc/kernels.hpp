@@ -73,6 +73,9 @@ hipError_t launch_gather_rows(const void* x, int n_rows, size_t row_bytes, const
 // zero `bytes` bytes (a multiple of 4) with a kernel, so that the call can be captured in a graph
 hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s);
 
+// xor of all 32-bit words of the first bytes/16*16 bytes of src into *checksum (atomically; the caller zeroes it)
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* checksum, hipStream_t s);
+
 struct FfnArgs {
     int dtype;            // 0 f32, 1 bf16
     const void *Wg, *Wu, *Wd; int d, G, b;

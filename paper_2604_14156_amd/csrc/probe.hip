@@ -1,0 +1,54 @@
+// Diagnostic: a plain streaming read.  The bandwidth-bound calls of the library (block-sparse FFN at
+// decode, head-pruned attention; the paper's Sec. 14 names memory bandwidth and KV-cache traffic as what
+// decides latency) are reported against the published peak of the device and, beside it, against what
+// this kernel reaches on the same device in the same run.
+#include "kernels.hpp"
+
+namespace csk {
+
+constexpr int PR_THREADS = 1024;
+constexpr int PR_UNROLL = 8;          // 16-byte loads in flight per lane
+
+__global__ __launch_bounds__(PR_THREADS)
+void stream_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* __restrict__ checksum) {
+    const size_t stride = (size_t)gridDim.x * PR_THREADS;
+    size_t i = (size_t)blockIdx.x * PR_THREADS + threadIdx.x;
+    uint32_t acc = 0u;
+    for (; i + (PR_UNROLL - 1) * stride < n16; i += PR_UNROLL * stride) {
+        uint4 v[PR_UNROLL];
+#pragma unroll
+        for (int u = 0; u < PR_UNROLL; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < PR_UNROLL; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 v = src[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    // one atomic per workgroup keeps the loads from being optimised away and makes the result checkable
+    // (atomics on one address are serialised by the memory system: a few thousand per launch are free,
+    // one per wavefront of a large grid is not)
+    __shared__ uint32_t part[PR_THREADS / 64];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc ^= __shfl_xor(acc, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t v = 0u;
+#pragma unroll
+        for (int w = 0; w < PR_THREADS / 64; ++w) v ^= part[w];
+        if (v != 0u) atomicXor(checksum, v);
+    }
+}
+
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* checksum, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (!n16) return hipSuccess;
+    size_t blocks = (n16 + (size_t)PR_THREADS * PR_UNROLL - 1) / ((size_t)PR_THREADS * PR_UNROLL);
+    if (blocks > 1024) blocks = 1024;                 // 4 workgroups per compute unit, grid-stride beyond
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(PR_THREADS), 0, s,
+                       reinterpret_cast<const uint4*>(src), n16, checksum);
+    return hipGetLastError();
+}
+
+}  // namespace csk

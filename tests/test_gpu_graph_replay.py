@@ -101,8 +101,10 @@ def test_pipelined_step_graph_replays_match_eager():
 
 
 def test_next_step_graph_with_batched_recovery_replays_match_eager():
-    """The other step shape: execution reads one generation of supports while the second stream sketches
-    all layers with one launch per kind and recovers them with one launch per kind into the other generation."""
+    """The other step shape: execution reads one generation of supports while the second stream sketches a
+    group of layers with one launch per kind, after the group has been issued, and recovers it with one
+    launch per kind into the other generation; the last group's work opens the next step (cross-stream
+    edges in both directions in the middle of the captured step)."""
     dev = "cuda:0"
     c = wl.scaled(wl.CFG2, d=512, G=24, k=6, m=64)
     hs = wl.scaled(wl.CFG3_HEADS, L=200)
@@ -137,44 +139,73 @@ def test_next_step_graph_with_batched_recovery_replays_match_eager():
         o = [torch.empty((B, hs.H, hs.dh), device=dev, dtype=bf) for _ in range(layers)]
         out = [torch.empty((B, c.d), device=dev, dtype=bf) for _ in range(layers)]
 
-        def recover_all(cx, gen_idx):
-            cx.cs_recover_support_multi(hop, hdict, hs.kh, Yh, Hh[gen_idx], None, None, mg[0], want_coef=False, want_resid=False)
-            cx.cs_recover_support_multi(fop, fdict, c.k, Y, S[gen_idx], None, None, mg[1], want_coef=False, want_resid=False)
+        def recover_rows(cx, gen_idx, l0, l1):
+            cx.cs_recover_support_multi(hop[l0:l1], hdict[l0:l1], hs.kh, Yh[l0:l1], Hh[gen_idx][l0:l1], None, None,
+                                        mg[0][l0:l1], want_coef=False, want_resid=False)
+            cx.cs_recover_support_multi(fop[l0:l1], fdict[l0:l1], c.k, Y[l0:l1], S[gen_idx][l0:l1], None, None,
+                                        mg[1][l0:l1], want_coef=False, want_resid=False)
+
+        def sketch_rows(cx, l0, l1):
+            cx.cs_sketch_multi(hop[l0:l1], u[l0:l1], Yh[l0:l1])
+            cx.cs_sketch_multi(fop[l0:l1], z[l0:l1], Y[l0:l1])
 
         # generation 0 from the sketches themselves (eager, first stream), device tables of both contexts
+        cut = layers - 1                       # two groups of layers: [0, cut) and the last layer
         for l in range(layers):
             ctx.cs_sketch(hop[l], u[l], Yh[l])
             ctx.cs_sketch(fop[l], z[l], Y[l])
-        recover_all(ctx, 0)
+        recover_rows(ctx, 0, 0, cut)
+        recover_rows(ctx, 0, cut, layers)
         torch.cuda.synchronize()
         with torch.cuda.stream(s_rec):
-            recover_all(rctx, 1)
+            recover_rows(rctx, 1, 0, cut)
+            recover_rows(rctx, 1, cut, layers)
         torch.cuda.synchronize()
+        S0_ref, H0_ref = S[0].clone(), Hh[0].clone()
+
+        def run_layer(l):
+            ctx.cs_head_attn(q[l], K[l], V[l], Hh[0][l], o[l])
+            ctx.cs_block_ffn(Wg[l], Wu[l], Wd[l], x[l], S[0][l], False, out[l])
 
         def step():
+            # the last group's measurement and recovery (carried over from the step before) open the step
+            # on the second stream and fill generation 0, which the last layer reads after a wait; the
+            # first group is measured once its layers have been issued and fills generation 1
             s_rec.wait_stream(s_exec)
-            for l in range(layers):
-                with torch.cuda.stream(s_exec):
-                    ctx.cs_head_attn(q[l], K[l], V[l], Hh[0][l], o[l])
-                    ctx.cs_block_ffn(Wg[l], Wu[l], Wd[l], x[l], S[0][l], False, out[l])
             with torch.cuda.stream(s_rec):
-                rctx.cs_sketch_multi(hop, u, Yh)
-                rctx.cs_sketch_multi(fop, z, Y)
-                recover_all(rctx, 1)
+                sketch_rows(rctx, cut, layers)
+                recover_rows(rctx, 0, cut, layers)
+                carried = torch.cuda.Event()
+                carried.record(s_rec)
+            with torch.cuda.stream(s_exec):
+                for l in range(cut):
+                    run_layer(l)
+                issued = torch.cuda.Event()
+                issued.record(s_exec)
+            with torch.cuda.stream(s_rec):
+                s_rec.wait_event(issued)
+                sketch_rows(rctx, 0, cut)
+                recover_rows(rctx, 1, 0, cut)
+            with torch.cuda.stream(s_exec):
+                s_exec.wait_event(carried)
+                for l in range(cut, layers):
+                    run_layer(l)
             s_exec.wait_stream(s_rec)
 
         def snapshot():
             torch.cuda.synchronize()
-            return [t.clone() for t in [S[1], Hh[1], Y, Yh] + o + out]
+            return [t.clone() for t in [S[1][:cut], Hh[1][:cut], S[0], Hh[0], Y, Yh] + o + out]
 
         step()
         ref = snapshot()
-        assert torch.equal(ref[0], S[0]) and torch.equal(ref[1], Hh[0])      # same sketches, same supports
+        assert torch.equal(ref[0], S0_ref[:cut]) and torch.equal(ref[1], H0_ref[:cut])      # same sketches, same supports
+        assert torch.equal(ref[2], S0_ref) and torch.equal(ref[3], H0_ref)
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=s_exec, capture_error_mode="thread_local"):
             step()
         for rep in range(4):
             S[1].fill_(-7); Hh[1].fill_(-7); Y.fill_(0.5); Yh.fill_(0.5)
+            S[0][cut:].fill_(-7); Hh[0][cut:].fill_(-7)             # the step itself refills these before the last layer reads them
             for t in o + out:
                 t.fill_(3.0)
             torch.cuda.synchronize()
@@ -184,6 +215,6 @@ def test_next_step_graph_with_batched_recovery_replays_match_eager():
                 assert torch.equal(a, b), rep
             ctx.cs_recover_support_multi(fop, fdict, c.k, Y, S[1], None, None, mg[1], want_coef=False, want_resid=False)
             torch.cuda.synchronize()
-            assert torch.equal(S[1], ref[0])
+            assert torch.equal(S[1], S0_ref)
     ctx.close()
     rctx.close()
