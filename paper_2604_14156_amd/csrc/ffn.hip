@@ -305,6 +305,72 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     }
 }
 
+// Single-token decode (T == 1): there is nothing to share between tokens, so the first product is a
+// plain matrix-vector product and the matrix cores would multiply 15 rows of padding.  A wavefront owns
+// one channel of one listed block: it reads the channel's gate row and up row contiguously (1 KB per
+// load instruction, all loads of both rows in flight at once), multiplies with the token by packed
+// bf16 dot products, reduces over the 64 lanes and writes one hidden value.  k*b wavefronts, each with
+// one memory round trip after the support entry has arrived.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+constexpr int GV_WAVES = 4;
+constexpr int GV_CHUNKS = 8;                          // 512-column chunks in flight per row
+
+__device__ __forceinline__ float dot8(const uint4& w, const uint4& v, float acc) {
+    acc = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w.x), *reinterpret_cast<const bf16x2_t*>(&v.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w.y), *reinterpret_cast<const bf16x2_t*>(&v.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w.z), *reinterpret_cast<const bf16x2_t*>(&v.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2_t*>(&w.w), *reinterpret_cast<const bf16x2_t*>(&v.w), acc, false);
+    return acc;
+}
+
+__global__ __launch_bounds__(GV_WAVES * 64)
+void ffn_gateup_gemv(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
+                     const uint16_t* __restrict__ x, const int32_t* __restrict__ support, int k,
+                     uint16_t* __restrict__ hbuf, uint32_t* __restrict__ list_out) {
+    const int lane = threadIdx.x & 63;
+    const int unit = __builtin_amdgcn_readfirstlane((int)blockIdx.x * GV_WAVES + (int)(threadIdx.x >> 6));
+    // the down kernel takes the list of used blocks from here (see ffn_gateup_mfma): one wavefront
+    // compacts the in-range support entries, 64 at a time, in their order; every listed block is used by token 0
+    if (unit == 0) {
+        int base = 0;
+        for (int i0 = 0; i0 < k; i0 += 64) {
+            const int i = i0 + lane;
+            const int g = i < k ? support[i] : -1;
+            const bool used = g >= 0 && g < G;
+            const unsigned long long bal = __ballot(used);
+            if (used) {
+                const int slot = base + __popcll(bal & ((1ull << lane) - 1ull));
+                list_out[1 + slot] = (uint32_t)g;
+                list_out[1 + FD_MAXG + slot] = 1u;
+            }
+            base += __popcll(bal);
+        }
+        if (lane == 0) list_out[0] = (uint32_t)base;
+    }
+    const int j = unit / b, c = unit - j * b;
+    if (j >= k) return;
+    const int g = support[j];                          // uniform over the wavefront
+    if (g < 0 || g >= G) return;
+    const uint16_t* wg = Wg + ((size_t)g * b + c) * d;
+    const uint16_t* wu = Wu + ((size_t)g * b + c) * d;
+    float sg = 0.f, su = 0.f;
+    for (int e0 = 0; e0 < d; e0 += GV_CHUNKS * 512) {
+        uint4 a[GV_CHUNKS], u[GV_CHUNKS], v[GV_CHUNKS];
+#pragma unroll
+        for (int q = 0; q < GV_CHUNKS; ++q) {
+            const int e = e0 + q * 512 + lane * 8;
+            const bool ok = e < d;
+            a[q] = ok ? *reinterpret_cast<const uint4*>(wg + e) : make_uint4(0u, 0u, 0u, 0u);
+            u[q] = ok ? *reinterpret_cast<const uint4*>(wu + e) : make_uint4(0u, 0u, 0u, 0u);
+            v[q] = ok ? *reinterpret_cast<const uint4*>(x + e) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int q = 0; q < GV_CHUNKS; ++q) { sg = dot8(a[q], v[q], sg); su = dot8(u[q], v[q], su); }
+    }
+    sg = wave_sum(sg); su = wave_sum(su);
+    if (lane == 0) hbuf[(size_t)g * 16 * b + c] = f32_to_bf16(sg / (1.0f + __expf(-sg)) * su);
+}
+
 // Down projection.  8 waves per workgroup and at most 128 registers per lane, so that two
 // workgroups fit on a compute unit when some units are busy with another stream's kernels.
 constexpr int DN_WAVES = 8;
@@ -394,10 +460,17 @@ static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     if (grid < 1) grid = 1;
     // a dense union is expected when the tokens list at least twice as many entries as there are blocks
     const int direct = (!a.shared && a.T > 1 && (long)a.T * a.k >= 2L * a.G) ? 1 : 0;
+    if (a.T == 1) {
+        const long units = (long)a.k * a.b;
+        hipLaunchKernelGGL(ffn_gateup_gemv, dim3((unsigned)((units + GV_WAVES - 1) / GV_WAVES)), dim3(GV_WAVES * 64), 0, s,
+                           (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.support, a.k,
+                           hbuf, list);
+    } else {
 #define CS_GU(NSV) hipLaunchKernelGGL((ffn_gateup_mfma<NSV>), dim3(grid), dim3(FD_THREADS), 0, s, \
         (const uint16_t*)a.Wg, (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, direct, hbuf, list)
     if (ns <= 2) CS_GU(2); else if (ns <= 4) CS_GU(4); else if (ns <= 8) CS_GU(8); else CS_GU(16);
 #undef CS_GU
+    }
     int dgrid = (a.d + 15) / 16;
     if (dgrid > 256) dgrid = 256;
     hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), 0, s,
