@@ -11,19 +11,19 @@ constexpr int PR_UNROLL = 8;          // 16-byte loads in flight per lane
 
 __global__ __launch_bounds__(PR_THREADS)
 void stream_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* __restrict__ checksum) {
-    const size_t stride = (size_t)gridDim.x * PR_THREADS;
-    size_t i = (size_t)blockIdx.x * PR_THREADS + threadIdx.x;
+    // a workgroup takes contiguous pieces of PR_THREADS * PR_UNROLL 16-byte words (128 KB) in turn; within
+    // a piece a wavefront's load instruction covers 1 KB of consecutive addresses
+    constexpr size_t PIECE = (size_t)PR_THREADS * PR_UNROLL;
     uint32_t acc = 0u;
-    for (; i + (PR_UNROLL - 1) * stride < n16; i += PR_UNROLL * stride) {
+    for (size_t base = (size_t)blockIdx.x * PIECE; base < n16; base += (size_t)gridDim.x * PIECE) {
         uint4 v[PR_UNROLL];
 #pragma unroll
-        for (int u = 0; u < PR_UNROLL; ++u) v[u] = src[i + u * stride];
+        for (int u = 0; u < PR_UNROLL; ++u) {
+            const size_t i = base + (size_t)u * PR_THREADS + threadIdx.x;
+            v[u] = i < n16 ? src[i] : make_uint4(0u, 0u, 0u, 0u);
+        }
 #pragma unroll
         for (int u = 0; u < PR_UNROLL; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-    }
-    for (; i < n16; i += stride) {
-        const uint4 v = src[i];
-        acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     // one atomic per workgroup keeps the loads from being optimised away and makes the result checkable
     // (atomics on one address are serialised by the memory system: a few thousand per launch are free,

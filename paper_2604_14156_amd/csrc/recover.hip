@@ -48,8 +48,6 @@ static RecoverLayout make_layout(const Plan& p, int k, int lds_limit) {
     return L;
 }
 
-static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, struct FastLayout& L);
-
 size_t recover_spill_floats(const Plan& p, int k, int lds_limit) {
     const RecoverLayout L = make_layout(p, k, lds_limit);
     return L.off_D < 0 ? (size_t)k * p.rb * p.N : 0;
@@ -298,19 +296,20 @@ struct FastLayout {
 constexpr int RF_MAXK = 64;        // selected atoms handled by the single-wavefront solves
 constexpr int RF_THREADS = 512;
 
-static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, FastLayout& L) {
+// fit = false (support and margin only): no refit work areas and no padding rows in the factor.
+static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, bool fit, FastLayout& L) {
     const int N = p.N, m = p.op.m;
     int KS = (k + 3) & ~3;
     if (((KS >> 2) & 1) == 0) KS += 4;        // odd number of 16-byte groups per row: conflict-free b128 reads
     L.KS = KS;
-    L.rows = (N + 63) & ~63;
+    L.rows = fit ? ((N + 63) & ~63) : N;
     int o = 0;
     L.off_y = o; o += (m + 3) & ~3;
-    L.off_r = o; o += (m + 3) & ~3;
+    L.off_r = o; if (fit) o += (m + 3) & ~3;
     L.off_cand = o; o += 2 * 16 * 4;
     L.off_beta = o; o += RF_MAXK;
-    L.off_alpha = o; o += RF_MAXK;
-    L.off_gv = o; o += 16 * RF_MAXK;
+    L.off_alpha = o; if (fit) o += RF_MAXK;
+    L.off_gv = o; if (fit) o += 16 * RF_MAXK;
     L.off_red = o; o += 16;
     L.off_selcol = o; o += RF_MAXK;
     // the factor's storage doubles as the staging area of the initial correlation partial sums
@@ -341,8 +340,12 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return max(max(a, b), max(c, d));
 }
 
-template <bool GRAM_LDS, bool WANT_MARGIN>
-__global__ __launch_bounds__(RF_THREADS) __attribute__((amdgpu_waves_per_eu(1, 2)))
+// WANT_FIT = false is the variant the decode loop runs (support and margin only).  It is held to 128
+// registers per lane and, at the 7B FFN shape, below 148 KB of LDS: its eight waves then take half of a
+// compute unit's register file and wave slots, and a 16-wave workgroup of a bandwidth-bound kernel from
+// another stream (64 registers per lane, a few KB of LDS) fits beside it.
+template <bool GRAM_LDS, bool WANT_MARGIN, bool WANT_FIT>
+__global__ __launch_bounds__(RF_THREADS) __attribute__((amdgpu_waves_per_eu(WANT_FIT ? 1 : 4, WANT_FIT ? 2 : 4)))
 void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, NT = blockDim.x;
@@ -369,7 +372,7 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     const int mrows = (m + NT - 1) / NT;
     float yreg = (tid < m) ? y[tid] : 0.f;
     const float w = (active && p.weighted) ? p.W[tid] : 1.f;
-    constexpr int GU = 16;
+    constexpr int GU = WANT_FIT ? 16 : 12;
     const int n4 = (N * N) >> 2;
     float4 greg[GU];
     if (GRAM_LDS) {
@@ -522,14 +525,13 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             const float dv = (gmine - dot) * inv;
             const float bt = ccol * inv;
             corr -= bt * dv;
-            myrow[J] = dv;
+            if (active) myrow[J] = dv;                    // lanes without an atom have no row of their own
             if (tid == 0) { beta[J] = bt; selcol[J] = gstar; }
         }
     }
     bad = __syncthreads_or(bad);
 
-    const bool want_fit = a.coef != nullptr || a.resid != nullptr;
-    if (want_fit) {
+    if (WANT_FIT) {
         // R[j][i] = Dt[selcol[i]][j] (j <= i).  One wavefront solves the triangular systems: lane l
         // holds component l, row l of R (upper solve) and column l of R (transposed solve) in
         // registers, and the pivots travel by scalar lane reads.
@@ -670,17 +672,17 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     }
 }
 
-template <bool GRAM_LDS, bool WANT_MARGIN>
+template <bool GRAM_LDS, bool WANT_MARGIN, bool WANT_FIT>
 static hipError_t launch_fast(const Plan& p, const RecoverArgs& a, const FastLayout& FL, int nthreads, hipStream_t s) {
     const size_t bytes = (size_t)FL.total_floats * 4;
     static size_t allowed = 0;              // raise the dynamic LDS limit only when a launch needs more
     if (bytes > allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<GRAM_LDS, WANT_MARGIN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_fast_kernel<GRAM_LDS, WANT_MARGIN, WANT_FIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
         if (e != hipSuccess) return e;
         allowed = bytes;
     }
-    hipLaunchKernelGGL((recover_fast_kernel<GRAM_LDS, WANT_MARGIN>), dim3(a.B, a.nplans), dim3(nthreads), bytes, s, p, a, FL);
+    hipLaunchKernelGGL((recover_fast_kernel<GRAM_LDS, WANT_MARGIN, WANT_FIT>), dim3(a.B, a.nplans), dim3(nthreads), bytes, s, p, a, FL);
     return hipGetLastError();
 }
 
@@ -691,12 +693,15 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
         // (Gram matrix, M) have many requests in flight
         const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : RF_THREADS;
         FastLayout FL;
-        if (make_fast_layout(p, a.k, lds_limit, nthreads, FL)) {
+        const bool fit = a.coef != nullptr || a.resid != nullptr;
+        if (make_fast_layout(p, a.k, lds_limit, nthreads, fit, FL)) {
             const bool gl = FL.off_gram >= 0, mg = a.margin != nullptr;
-            if (gl && mg) return launch_fast<true, true>(p, a, FL, nthreads, s);
-            if (gl && !mg) return launch_fast<true, false>(p, a, FL, nthreads, s);
-            if (!gl && mg) return launch_fast<false, true>(p, a, FL, nthreads, s);
-            return launch_fast<false, false>(p, a, FL, nthreads, s);
+#define CS_RF(G_, M_) (fit ? launch_fast<G_, M_, true>(p, a, FL, nthreads, s) : launch_fast<G_, M_, false>(p, a, FL, nthreads, s))
+            if (gl && mg) return CS_RF(true, true);
+            if (gl && !mg) return CS_RF(true, false);
+            if (!gl && mg) return CS_RF(false, true);
+            return CS_RF(false, false);
+#undef CS_RF
         }
     }
     const RecoverLayout L = make_layout(p, a.k, lds_limit);
