@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libcs_mi355x.so"
 LIB_PATH = os.path.join(HERE, LIB_NAME)
-SOURCES = ["cs_api.hip", "sketch.hip", "plan.hip", "recover.hip", "iht.hip", "inc.hip", "select.hip", "ffn.hip", "ffn_gemm.hip", "attn.hip", "probe.hip"]
+SOURCES = ["cs_api.hip", "sketch.hip", "plan.hip", "recover.hip", "iht.hip", "inc.hip", "select.hip", "ffn.hip", "ffn_wide.hip", "ffn_gemm.hip", "attn.hip", "probe.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed fp32 arithmetic is kept off for every kernel in this library

@@ -493,6 +493,7 @@ hipError_t launch_zero_fill(void* dst, size_t bytes, hipStream_t s) {
 
 size_t ffn_scratch_bytes(const FfnArgs& a) {
     if (mfma_decode_ok(a)) return (size_t)a.G * 16 * a.b * sizeof(uint16_t) + (2 * FD_MAXG + 4) * sizeof(uint32_t);
+    if (ffn_wide_ok(a)) return ffn_wide_scratch_bytes(a);
     if (ffn_gemm_ok(a)) return ffn_gemm_scratch_bytes(a);
     return (size_t)a.T * a.k * a.b * sizeof(float);
 }
@@ -500,6 +501,7 @@ size_t ffn_scratch_bytes(const FfnArgs& a) {
 hipError_t launch_block_ffn(const FfnArgs& a, hipStream_t s) {
     if (a.T <= 0) return hipSuccess;
     if (mfma_decode_ok(a)) return run_mfma_decode(a, s);
+    if (ffn_wide_ok(a)) return launch_ffn_wide(a, s);
     if (ffn_gemm_ok(a)) return launch_ffn_gemm(a, s);
     if (a.dtype == 0) return run_generic<float>(a, s);
     return run_generic<uint16_t>(a, s);

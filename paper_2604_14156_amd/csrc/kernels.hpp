@@ -88,6 +88,10 @@ size_t ffn_scratch_bytes(const FfnArgs& a);
 bool ffn_gemm_ok(const FfnArgs& a);
 size_t ffn_gemm_scratch_bytes(const FfnArgs& a);
 hipError_t launch_ffn_gemm(const FfnArgs& a, hipStream_t s);
+// token-adaptive batches of 17 to 64 rows (ffn_wide.hip)
+bool ffn_wide_ok(const FfnArgs& a);
+size_t ffn_wide_scratch_bytes(const FfnArgs& a);
+hipError_t launch_ffn_wide(const FfnArgs& a, hipStream_t s);
 hipError_t launch_block_ffn(const FfnArgs& a, hipStream_t s);
 
 struct AttnArgs {

@@ -155,6 +155,33 @@ def test_joint_prompt_shape_gather_and_ffn(cs):
     assert float(z[1].float().abs().max()) == 0.0 and float(z[2].float().abs().max()) == 0.0 and torch.equal(z[3], X[7])
 
 
+@pytest.mark.parametrize("T,G,b,k,d", [(17, 10, 64, 3, 512), (37, 12, 32, 5, 416), (48, 30, 64, 30, 256), (64, 7, 96, 2, 1056),
+                                       (33, 300, 64, 4, 128)])
+def test_ffn_bf16_17_to_64_rows_per_token_supports(cs, T, G, b, k, d):
+    """The path for 17 to 64 token rows with their own supports: ragged token tiles, a width that is no
+    multiple of the staged chunk, blocks of 32 and 96 channels, k == G, more channels than one pass of a
+    workgroup holds (300 blocks on few workgroups is not reached here, many blocks on 256 are)."""
+    _ffn_case(cs, 1800 + T, G, b, d, k, T, "bf16", False, 0.05)
+
+
+def test_ffn_17_to_64_rows_out_of_range_units(cs):
+    rng = wl.rng_for(1850)
+    G, b, d, T = 8, 64, 256, 20
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, G, b, d, 0.05, "bf16")
+    x = wl.make_tokens(rng, T, d, "bf16")
+    sup = wl.random_supports(rng, G, 3, T)
+    sup[0, 1] = -1
+    sup[5, 0] = G + 3
+    sup[19, :] = [G, -5, 99]                                   # a token with no valid unit: a zero row
+    got = host(cs.cs_block_ffn(dev_bf16(Wg), dev_bf16(Wu), dev_bf16(Wd), dev_bf16(x), dev_i32(sup), False))
+    for t in range(T):
+        want = oracle.block_ffn(Wg, Wu, Wd, x[t:t + 1], [g for g in sup[t] if 0 <= g < G])[0]
+        if t == 19:
+            assert np.all(got[t] == 0.0)
+        else:
+            check_row(got[t], want, "bf16", t)
+
+
 def test_ffn_bf16_block_of_32_channels(cs):
     _ffn_case(cs, 1300, 12, 32, 256, 5, 4, "bf16", False, 0.05)
 
