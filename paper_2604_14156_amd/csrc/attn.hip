@@ -12,6 +12,7 @@
 // kernel merges the partial results; a short cache is handled by one workgroup per
 // head that writes the result directly.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "op_desc.hpp"
 
 #define CS_WAVE 64
 
@@ -28,15 +29,6 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
     return o;
 }
 
-// Operator descriptor as the kernels see it.
-struct OpDesc {
-    uint32_t k0, k1;      // seed halves
-    uint32_t stream;
-    int ens;              // 0 Gaussian, 1 Rademacher, 2 subsampled randomised Hadamard
-    int m, n;
-    float scale;          // 1/sqrt(m)
-    int nbits;            // Hadamard ensemble: the transform has 2^nbits >= max(n, 2) points
-};
 
 // 128 sign bits of row `row`, column group `cg` (columns 128*cg .. 128*cg+127).
 __device__ __forceinline__ u32x4 rademacher_bits(const OpDesc& op, uint32_t row, uint32_t cg) {

@@ -3,6 +3,7 @@
 //   out[t] = sum_{g in S_t} Wd_g ( silu(Wg_g x_t) * (Wu_g x_t) ).
 // Only the weight blocks named by the support are read.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 

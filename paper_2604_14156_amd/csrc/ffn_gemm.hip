@@ -12,6 +12,7 @@
 // during the multiplies.  LDS rows are 128 bytes; the eight 16-byte chunks of a row
 // are stored XOR-swizzled by the row index so that fragment reads are conflict free.
 #include "kernels.hpp"
+#include "common.hpp"
 #include <type_traits>
 
 namespace csk {

@@ -22,6 +22,7 @@
 // Hidden values travel as bf16 in [G][64][b] order; entries of tokens that do not list the block are
 // neither written nor read.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 

@@ -12,6 +12,7 @@
 // by least squares on the final support (Cholesky factor of G_SS built in LDS by one
 // wavefront, then one refinement step against the explicit residual).
 #include "kernels.hpp"
+#include "common.hpp"
 #include "small_dense.hpp"
 #include "gram_loads.hpp"
 

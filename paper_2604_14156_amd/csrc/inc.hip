@@ -15,6 +15,7 @@
 // residual of a fit on S is c0 - G[:, S] alpha, the fits are Cholesky solves of G_SS by one
 // wavefront (a factorisation per refit of a changed list, one appended row per greedy round).
 #include "kernels.hpp"
+#include "common.hpp"
 #include "small_dense.hpp"
 #include "gram_loads.hpp"
 

@@ -1,8 +1,11 @@
-// Host-callable launchers of the HIP kernels (internal to the library).
+// Host-callable launchers of the HIP kernels (internal to the library).  Host-side declarations only:
+// the C ABI (cs_api.hip) needs nothing else, which also lets its argument checking and bookkeeping be
+// built for the host alone, against stand-in launchers, and run under the address and
+// undefined-behaviour sanitizers on a machine without a GPU.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include "common.hpp"
+#include "op_desc.hpp"
 
 namespace csk {
 

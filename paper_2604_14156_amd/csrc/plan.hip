@@ -4,6 +4,7 @@
 // Sums run in fp64 and are rounded once: these run once per (operator,
 // dictionary) pair, never in the per-token loop.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 

@@ -3,6 +3,7 @@
 // decides latency) are reported against the published peak of the device and, beside it, against what
 // this kernel reaches on the same device in the same run.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 

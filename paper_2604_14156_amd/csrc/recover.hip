@@ -14,6 +14,7 @@
 // the explicitly formed residual y - M_S alpha, which removes the squared condition
 // number the Gram form would otherwise leave in the result.
 #include "kernels.hpp"
+#include "common.hpp"
 #include <math.h>
 
 namespace csk {

@@ -2,6 +2,7 @@
 // sketch, p = Phi^T y, and selection of the k largest entries (ties -> smaller
 // index) returned in ascending index order.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 

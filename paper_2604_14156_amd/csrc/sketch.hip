@@ -19,6 +19,7 @@
 // levels of the transform commute, so the passes simply walk over the index bits), then reads
 // the m selected entries.  n' log2 n' additions per token instead of m n.
 #include "kernels.hpp"
+#include "common.hpp"
 
 namespace csk {
 
