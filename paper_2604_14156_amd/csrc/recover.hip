@@ -289,39 +289,51 @@ __global__ void recover_kernel(Plan p, RecoverArgs a, RecoverLayout L) {
 // ---------------------------------------------------------------------------
 struct FastLayout {
     int off_y, off_r, off_cand, off_beta, off_alpha, off_gv, off_red, off_selcol, off_Dt, off_gram;
-    int KS;               // padded row length of the factor (floats)
+    int KL;               // leading factor entries per atom kept in LDS (the rest in a global spill)
+    int KS;               // padded row length of the factor in LDS (floats)
     int rows;             // rows of the factor = atoms rounded up to a wavefront
     int total_floats;
 };
 
 constexpr int RF_MAXK = 64;        // selected atoms handled by the single-wavefront solves
+constexpr int RF_MAXK_SELECT = 256; // selected atoms of the support-only variant (no solves)
 constexpr int RF_THREADS = 512;
 
 // fit = false (support and margin only): no refit work areas and no padding rows in the factor.
-static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, bool fit, FastLayout& L) {
+static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, bool fit, bool have_spill, FastLayout& L) {
     const int N = p.N, m = p.op.m;
-    int KS = (k + 3) & ~3;
-    if (((KS >> 2) & 1) == 0) KS += 4;        // odd number of 16-byte groups per row: conflict-free b128 reads
-    L.KS = KS;
+    const int kcap = fit ? RF_MAXK : RF_MAXK_SELECT;
     L.rows = fit ? ((N + 63) & ~63) : N;
     int o = 0;
     L.off_y = o; o += (m + 3) & ~3;
     L.off_r = o; if (fit) o += (m + 3) & ~3;
     L.off_cand = o; o += 2 * 16 * 4;
-    L.off_beta = o; o += RF_MAXK;
+    L.off_beta = o; o += kcap;
     L.off_alpha = o; if (fit) o += RF_MAXK;
     L.off_gv = o; if (fit) o += 16 * RF_MAXK;
     L.off_red = o; o += 16;
-    L.off_selcol = o; o += RF_MAXK;
+    L.off_selcol = o; o += kcap;
+    const long limit = lds_limit / 4 - 16;
+    auto padded = [](int kl) {
+        int ks = (kl + 3) & ~3;
+        if (((ks >> 2) & 1) == 0) ks += 4;    // odd number of 16-byte groups per row: conflict-free b128 reads
+        return ks;
+    };
+    // the factor: as many leading entries per atom in LDS as fit; the support-only variant may keep the
+    // rest in a global spill (the late rounds then read a few values per atom through L2)
+    int KL = k;
+    while (KL > 4 && (long)o + (long)L.rows * padded(KL) > limit) KL -= 4;
+    if (KL < k && (fit || !have_spill)) return false;
+    L.KL = KL;
+    L.KS = padded(KL);
     // the factor's storage doubles as the staging area of the initial correlation partial sums
-    int dt = L.rows * KS;
+    int dt = L.rows * L.KS;
     const int stage = nthreads * 4;
     if (dt < stage) dt = stage;
     L.off_Dt = o; o += dt;
     L.off_gram = -1;
-    const long limit = lds_limit / 4 - 16;
     if (o > limit) return false;
-    if ((long)o + (long)N * N <= limit) { L.off_gram = o; o += N * N; }
+    if (KL == k && (long)o + (long)N * N <= limit) { L.off_gram = o; o += N * N; }
     L.total_floats = o;
     return true;
 }
@@ -353,7 +365,7 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     const int lane = tid & 63, wave = tid >> 6, nwaves = NT >> 6;
     const int prob = blockIdx.y * a.B + blockIdx.x;
     if (a.plans) p = a.plans[blockIdx.y];
-    const int N = p.N, m = p.op.m, k = a.k, KS = L.KS;
+    const int N = p.N, m = p.op.m, k = a.k, KS = L.KS, KL = L.KL;
     const bool active = tid < N;
     const int round_waves = (N + 63) >> 6;     // waves that own atoms
 
@@ -455,6 +467,9 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     bool selected = false;
     float margin = 1.f;
     float* myrow = Dt + (size_t)(tid < L.rows ? tid : 0) * KS;
+    // factor entries beyond the KL kept in LDS: [atom][k - KL] in the global spill of this sketch
+    float* spill = (KL < k) ? a.spill + (size_t)prob * a.spill_stride : nullptr;
+    float* myspill = spill ? spill + (size_t)(active ? tid : 0) * (k - KL) : nullptr;
 
     for (int J = 0; J < k; ++J) {
         if (wave < round_waves) {
@@ -507,17 +522,26 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             const float gmine = active ? grow[tid] : 0.f;
             const float* prow = Dt + (size_t)gstar * KS;
             float dot = 0.f, piv = 0.f;
-            const int J4 = J & ~3;
+            const int JL = J < KL ? J : KL;            // entries of this round's dot products that sit in LDS
+            const int J4 = JL & ~3;
             for (int j = 0; j < J4; j += 4) {
                 const float4 u = *reinterpret_cast<const float4*>(myrow + j);
                 const float4 v = *reinterpret_cast<const float4*>(prow + j);
                 dot += u.x * v.x + u.y * v.y + u.z * v.z + u.w * v.w;
                 piv += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
             }
-            for (int j = J4; j < J; ++j) {
+            for (int j = J4; j < JL; ++j) {
                 const float v = prow[j];
                 dot += myrow[j] * v;
                 piv += v * v;
+            }
+            if (J > KL) {
+                const float* pspill = spill + (size_t)gstar * (k - KL);
+                for (int j = 0; j < J - KL; ++j) {
+                    const float v = pspill[j];
+                    dot += myspill[j] * v;
+                    piv += v * v;
+                }
             }
             const float nrm2 = gdiag - piv;
             float inv = 0.f;
@@ -526,7 +550,9 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             const float dv = (gmine - dot) * inv;
             const float bt = ccol * inv;
             corr -= bt * dv;
-            if (active) myrow[J] = dv;                    // lanes without an atom have no row of their own
+            if (active) {                                 // lanes without an atom have no row of their own
+                if (J < KL) myrow[J] = dv; else myspill[J - KL] = dv;
+            }
             if (tid == 0) { beta[J] = bt; selcol[J] = gstar; }
         }
     }
@@ -689,13 +715,13 @@ static hipError_t launch_fast(const Plan& p, const RecoverArgs& a, const FastLay
 
 hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hipStream_t s) {
     if (a.B <= 0) return hipSuccess;
-    if (p.rb == 1 && a.k <= RF_MAXK && p.N <= RF_THREADS) {
+    const bool fit = a.coef != nullptr || a.resid != nullptr;
+    if (p.rb == 1 && p.N <= RF_THREADS && a.k <= (fit ? RF_MAXK : RF_MAXK_SELECT)) {
         // one wavefront for small problems, otherwise a full workgroup so that the bulk loads
         // (Gram matrix, M) have many requests in flight
         const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : RF_THREADS;
         FastLayout FL;
-        const bool fit = a.coef != nullptr || a.resid != nullptr;
-        if (make_fast_layout(p, a.k, lds_limit, nthreads, fit, FL)) {
+        if (make_fast_layout(p, a.k, lds_limit, nthreads, fit, a.spill != nullptr && a.spill_stride >= (size_t)a.k * p.N, FL)) {
             const bool gl = FL.off_gram >= 0, mg = a.margin != nullptr;
 #define CS_RF(G_, M_) (fit ? launch_fast<G_, M_, true>(p, a, FL, nthreads, s) : launch_fast<G_, M_, false>(p, a, FL, nthreads, s))
             if (gl && mg) return CS_RF(true, true);

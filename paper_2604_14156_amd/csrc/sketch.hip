@@ -214,6 +214,57 @@ void sketch_gauss_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, in
     }
 }
 
+// The same products with the columns of a row dealt to all waves of a workgroup (one workgroup per row):
+// for launches with few rows and tokens (a prompt-level sketch: one token, a few hundred rows), where one
+// wave per row would leave most of the chip idle while every lane draws its hundred-odd Gaussians one after
+// the other.  Wave w takes column groups w*64 + lane, + 64*nwaves, ...; the waves' sums are added in wave
+// order.  The split depends on the operator's shape and the batch only, never on how many operators share
+// the launch, so a multi-operator launch returns the bits of the single-operator call.
+template <int TB, bool VEC>
+__global__ __launch_bounds__(1024)
+void sketch_gauss_split_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ y) {
+    __shared__ float part[16][TB];
+    pick_operator(op, keys);
+    z += (size_t)blockIdx.z * B * op.n;
+    y += (size_t)blockIdx.z * B * op.m;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int row = blockIdx.x;
+    const int t0 = blockIdx.y * TB;
+    const int nt = min(TB, B - t0);
+    float acc[TB];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) acc[t] = 0.f;
+    const int ngroups = (op.n + 3) >> 2;
+    for (int cg = wave * 64 + lane; cg < ngroups; cg += 64 * nwaves) {
+        float e[4];
+        gauss4(op, (uint32_t)row, (uint32_t)cg, e);
+        const int c0 = cg << 2;
+        if (VEC && c0 + 4 <= op.n) {
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                if (t < nt) {
+                    const float4 v = *reinterpret_cast<const float4*>(z + (size_t)(t0 + t) * op.n + c0);
+                    acc[t] += e[0] * v.x + e[1] * v.y + e[2] * v.z + e[3] * v.w;
+                }
+            }
+        } else {
+            for (int c = c0; c < min(c0 + 4, op.n); ++c)
+                for (int t = 0; t < nt; ++t) acc[t] += e[c - c0] * z[(size_t)(t0 + t) * op.n + c];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        const float s = wave_sum(acc[t]);
+        if (lane == 0) part[wave][t] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < nt) {
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w) s += part[w][threadIdx.x];
+        y[(size_t)(t0 + threadIdx.x) * op.m + row] = s * op.scale;
+    }
+}
+
 // LDS position of transform index i: one float of padding per 32 keeps both the 16-float runs of the
 // first pass and the unit-stride accesses of the later passes free of bank conflicts
 __device__ __forceinline__ int wht_pos(int i) { return i + (i >> 5); }
@@ -351,8 +402,19 @@ hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int
                 hipLaunchKernelGGL((sketch_rademacher_kernel<2, 8>), dim3((op.m + 1) / 2, tgroups, nz), dim3(SR_WAVES * 64), 0, s, op, keys, zj, B, yj);
             }
         } else {
-            dim3 grid((op.m + SK_WAVES - 1) / SK_WAVES, (B + SK_TB - 1) / SK_TB, nz);
             const bool vec = (op.n & 3) == 0;   // float4 loads need 16-byte aligned rows of z
+            // few rows x token groups per operator: deal each row's columns to several waves
+            const long waves = (long)op.m * ((B + SK_TB - 1) / SK_TB);
+            const int useful = (((op.n + 3) >> 2) + 63) / 64;          // waves that get at least one column group
+            int split = 1;
+            while (split < 16 && waves * split < 2048 && split * 2 <= useful) split *= 2;
+            if (split > 1) {
+                dim3 sgrid(op.m, (B + SK_TB - 1) / SK_TB, nz);
+                if (vec) hipLaunchKernelGGL((sketch_gauss_split_kernel<SK_TB, true>), sgrid, dim3(split * 64), 0, s, op, keys, zj, B, yj);
+                else hipLaunchKernelGGL((sketch_gauss_split_kernel<SK_TB, false>), sgrid, dim3(split * 64), 0, s, op, keys, zj, B, yj);
+                continue;
+            }
+            dim3 grid((op.m + SK_WAVES - 1) / SK_WAVES, (B + SK_TB - 1) / SK_TB, nz);
             if (vec) hipLaunchKernelGGL((sketch_gauss_kernel<SK_TB, true>), grid, dim3(SK_WAVES * 64), 0, s, op, keys, zj, B, yj);
             else hipLaunchKernelGGL((sketch_gauss_kernel<SK_TB, false>), grid, dim3(SK_WAVES * 64), 0, s, op, keys, zj, B, yj);
         }

@@ -180,6 +180,17 @@ def test_prefill_shape_uses_the_spill_path(cs):
     sup = host(cs.cs_recover_support(op, dct, c.k, cs.cs_sketch(op, dev_f32(z)))[0])
     for t in range(B):
         assert list(sup[t]) == list(S[t])
+    # support and margin only: the one-atom kernel with the tail of its factor in the global spill
+    sel, _, _, mg = cs.cs_recover_support(op, dct, c.k, dev_f32(Y), want_coef=False, want_resid=False)
+    sel, mg = host(sel), host(mg)
+    exact = 0
+    for t in range(B):
+        y = Y[t].astype(np.float64)
+        rec = oracle.block_omp(M, y, c.G, 1, c.k, True)
+        exact += assert_greedy_support(M, y, c.G, 1, c.k, True, sel[t], rec)
+        if rec["margin"] > MARGIN:
+            assert abs(mg[t] - rec["margin"]) <= 1e-3
+    assert exact == 4
 
 
 def test_textbook_block_mode_identity_dictionary(cs):
