@@ -232,7 +232,8 @@ cs_status cs_recover_support_inc(cs_ctx* ctx, const cs_op* op, const cs_dict* di
  *   support: int32[k] if shared != 0 (one support for all T rows: task-conditioned
  *            prefill, Sec. 4), else int32[T][k] (token-adaptive decode, Sec. 5);
  *            entries distinct within a row and in [0, G).  Order is irrelevant.
- * Accumulation is in fp32; bf16 results are rounded once at the end.
+ * Accumulation is in fp32.  On the bf16 paths the hidden values silu(Wg x) * (Wu x) are stored as bf16
+ * between the two products (the second accumulation sees bf16 inputs) and the result is rounded to bf16 once.
  * Requires d % 8 == 0 and b % 8 == 0.  An out-of-range support entry makes that
  * unit contribute nothing (it is never dereferenced).
  */

@@ -1,6 +1,6 @@
-// Block orthogonal matching pursuit on the GPU (paper Sec. 8: "orthogonal matching
-// pursuit over a constrained support dictionary"; support of exactly k units,
-// Sec. 3 / Sec. 7).  One workgroup solves one sketch; the k rounds are sequential.
+// Block orthogonal matching pursuit on the GPU (paper Sec. 8 lists greedy pursuit
+// restricted to the admissible supports among the per-token solvers; support of
+// exactly k units, Sec. 3 / Sec. 7).  One workgroup solves one sketch; the k rounds are sequential.
 //
 // The rounds run in the Gram domain.  With M = Phi Psi (Sec. 9), G = M^T M and
 // c = M^T r, selecting atom a and orthogonalising it against the atoms already
