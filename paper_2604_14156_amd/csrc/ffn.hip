@@ -380,9 +380,13 @@ constexpr int DN_UB = 6;                              // blocks in flight per wa
 __global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
                    int T, const uint32_t* __restrict__ list_in, uint16_t* __restrict__ out) {
-    __shared__ uint16_t ulist[FD_MAXG];
-    __shared__ uint32_t umask[FD_MAXG];
-    __shared__ float red[DN_WAVES][256];
+    // LDS sized by the number of blocks (8 KB + 6 bytes per block), not by the largest list the path
+    // accepts: at the 7B shape that is 9.2 KB, which still fits on a compute unit beside a recovery
+    // workgroup of another stream (147 KB), so the kernel does not have to wait for that unit
+    extern __shared__ __attribute__((aligned(16))) unsigned char dn_lds[];
+    float (*red)[256] = reinterpret_cast<float (*)[256]>(dn_lds);                       // [DN_WAVES][256]
+    uint32_t* umask = reinterpret_cast<uint32_t*>(dn_lds + DN_WAVES * 256 * sizeof(float));
+    uint16_t* ulist = reinterpret_cast<uint16_t*>(umask + G);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // the list of used blocks, written by the gate/up kernel of the same call
     // (G entries are fetched whatever the count says, so that both loads are in flight together)
@@ -474,7 +478,8 @@ static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     }
     int dgrid = (a.d + 15) / 16;
     if (dgrid > 256) dgrid = 256;
-    hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), 0, s,
+    const size_t dn_lds = DN_WAVES * 256 * sizeof(float) + (size_t)a.G * (sizeof(uint32_t) + sizeof(uint16_t));
+    hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), dn_lds, s,
                        (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, list, (uint16_t*)a.out);
     return hipGetLastError();
 }
