@@ -278,12 +278,15 @@ __global__ void recover_kernel(Plan p, RecoverArgs a, RecoverLayout L) {
 // registers and its row of the factor (d_j[c], j = 0..) in LDS.  A round costs one
 // workgroup barrier:
 //   every wave finds its best and second-best score with lane-crossbar reductions
-//   and posts (best, index, second, correlation of the best) to LDS; after the
-//   barrier every thread merges the few per-wave candidates itself, so the winner,
-//   the margin and the step length are known everywhere without another exchange;
-//   the new factor entry needs only the winner's row (broadcast reads) and the
-//   thread's own row, and the pivot is recomputed by every thread from the same
-//   broadcast values.
+//   and posts (best, index, second, correlation of the best, reciprocal pivot of the
+//   best) to LDS; after the barrier every thread merges the few per-wave candidates
+//   itself, so the winner, the margin and the step length are known everywhere
+//   without another exchange; the new factor entry needs only the winner's row
+//   (broadcast reads) and the thread's own row.  A thread keeps the squared norm of
+//   its own factor row in a register, so the pivot of a candidate (its atom's squared
+//   norm less that) costs nothing per round.  The single waves that run a round are
+//   bound by instruction issue, not by memory: the round is written for few
+//   instructions and few separate waits.
 // The triangular solves of the refit run inside one wavefront with scalar lane
 // broadcasts instead of barriers.
 // ---------------------------------------------------------------------------
@@ -307,7 +310,7 @@ static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, 
     int o = 0;
     L.off_y = o; o += (m + 3) & ~3;
     L.off_r = o; if (fit) o += (m + 3) & ~3;
-    L.off_cand = o; o += 2 * 16 * 4;
+    L.off_cand = o; o += 2 * 16 * 8;
     L.off_beta = o; o += kcap;
     L.off_alpha = o; if (fit) o += RF_MAXK;
     L.off_gv = o; if (fit) o += 16 * RF_MAXK;
@@ -370,7 +373,7 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     const int round_waves = (N + 63) >> 6;     // waves that own atoms
 
     float* yv = lds + L.off_y;
-    float* cand = lds + L.off_cand;            // [2][16][4]
+    float* cand = lds + L.off_cand;            // [2][16][8]
     float* beta = lds + L.off_beta;
     float* alpha = lds + L.off_alpha;
     float* gv = lds + L.off_gv;                // [16][RF_MAXK]
@@ -385,6 +388,7 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     const int mrows = (m + NT - 1) / NT;
     float yreg = (tid < m) ? y[tid] : 0.f;
     const float w = (active && p.weighted) ? p.W[tid] : 1.f;
+    const float gd = active ? p.gram[(size_t)tid * N + tid] : 1.f;   // squared norm of the thread's atom
     constexpr int GU = WANT_FIT ? 16 : 12;
     const int n4 = (N * N) >> 2;
     float4 greg[GU];
@@ -466,10 +470,15 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     }
     bool selected = false;
     float margin = 1.f;
+    float sq = 0.f;                                     // squared norm of the thread's factor row so far
     float* myrow = Dt + (size_t)(tid < L.rows ? tid : 0) * KS;
     // factor entries beyond the KL kept in LDS: [atom][k - KL] in the global spill of this sketch
     float* spill = (KL < k) ? a.spill + (size_t)prob * a.spill_stride : nullptr;
     float* myspill = spill ? spill + (size_t)(active ? tid : 0) * (k - KL) : nullptr;
+
+    // rows are zero beyond their last written entry, so that a round may read whole groups of four
+    for (int i = tid; i < (L.rows * KS) >> 2; i += NT)
+        reinterpret_cast<float4*>(Dt)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 
     for (int J = 0; J < k; ++J) {
         if (wave < round_waves) {
@@ -485,29 +494,49 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             const unsigned long long hit = __ballot(key == m1);
             const int l1 = __ffsll((long long)hit) - 1;
             const float c1 = readlane_f32(corr, l1);
+            // the pivot of the wave's candidate: its squared norm less that of its factor row
+            const float nrm2 = gd - sq;
+            float rs = 0.f;
+            if (nrm2 > 1e-10f * gd && nrm2 > 0.f) rs = __builtin_amdgcn_rsqf(nrm2);
+            const float i1 = readlane_f32(rs, l1);
             uint32_t m2 = 0u;
             if (WANT_MARGIN) m2 = wave_max_u32(lane == l1 ? 0u : key);
             if (lane == 0) {
                 float4 cv;
                 cv.x = __uint_as_float(m1); cv.y = __int_as_float(wave * 64 + l1); cv.z = __uint_as_float(m2); cv.w = c1;
-                *reinterpret_cast<float4*>(cand + ((J & 1) * 16 + wave) * 4) = cv;
+                float* cw = cand + ((J & 1) * 16 + wave) * 8;
+                *reinterpret_cast<float4*>(cw) = cv;
+                cw[4] = i1;
             }
         }
         __syncthreads();
         if (wave < round_waves) {
-            const float4* cb = reinterpret_cast<const float4*>(cand + (J & 1) * 16 * 4);
-            float4 c0 = cb[0];
-            uint32_t k1 = __float_as_uint(c0.x), k2 = __float_as_uint(c0.z);
-            int gstar = __float_as_int(c0.y);
-            float ccol = c0.w;
-            for (int wv = 1; wv < round_waves; ++wv) {
-                const float4 cw = cb[wv];
-                const uint32_t o1 = __float_as_uint(cw.x);
-                if (o1 > k1) {                            // ties keep the lower wave = lower index
-                    k2 = max(max(k2, k1), __float_as_uint(cw.z));
-                    k1 = o1; gstar = __float_as_int(cw.y); ccol = cw.w;
-                } else {
-                    k2 = max(k2, o1);
+            const float* cb = cand + (J & 1) * 16 * 8;
+            // the waves' candidates are read four at a time and merged by selects: one LDS latency per
+            // four waves instead of one (and a branch) per wave
+            uint32_t k1 = 0u, k2 = 0u;
+            int gstar = 0;
+            float ccol = 0.f, inv = 0.f;
+            for (int w0 = 0; w0 < round_waves; w0 += 4) {
+                float4 cw[4];
+                float ci[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float* e = cb + min(w0 + q, round_waves - 1) * 8;
+                    cw[q] = *reinterpret_cast<const float4*>(e);
+                    ci[q] = e[4];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool live = w0 + q < round_waves;
+                    const uint32_t o1 = live ? __float_as_uint(cw[q].x) : 0u;
+                    const uint32_t o2 = live ? __float_as_uint(cw[q].z) : 0u;
+                    const bool up = o1 > k1 || w0 + q == 0;   // ties keep the lower wave = lower index
+                    k2 = up ? max(max(k2, k1), o2) : max(k2, o1);
+                    gstar = up ? __float_as_int(cw[q].y) : gstar;
+                    ccol = up ? cw[q].w : ccol;
+                    inv = up ? ci[q] : inv;
+                    k1 = up ? o1 : k1;
                 }
             }
             if (WANT_MARGIN) {
@@ -518,38 +547,53 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             if (tid == gstar) selected = true;
 
             const float* grow = (GRAM_LDS ? gl : p.gram) + (size_t)gstar * N;
-            const float gdiag = grow[gstar];
             const float gmine = active ? grow[tid] : 0.f;
             const float* prow = Dt + (size_t)gstar * KS;
-            float dot = 0.f, piv = 0.f;
-            const int JL = J < KL ? J : KL;            // entries of this round's dot products that sit in LDS
-            const int J4 = JL & ~3;
-            for (int j = 0; j < J4; j += 4) {
-                const float4 u = *reinterpret_cast<const float4*>(myrow + j);
-                const float4 v = *reinterpret_cast<const float4*>(prow + j);
-                dot += u.x * v.x + u.y * v.y + u.z * v.z + u.w * v.w;
-                piv += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            float dot = 0.f;
+            const int JL = J < KL ? J : KL;            // entries of this round's dot product that sit in LDS
+            const int JU = (JL + 3) & ~3;              // in whole groups of four: the rows end in zeros
+            // 16 entries per turn, all eight LDS reads issued before the first use: the loop is a chain of
+            // LDS latencies otherwise (its trip count is not known at compile time)
+            int j = 0;
+            for (; j + 16 <= JU; j += 16) {
+                float4 u[4], v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    u[q] = *reinterpret_cast<const float4*>(myrow + j + 4 * q);
+                    v[q] = *reinterpret_cast<const float4*>(prow + j + 4 * q);
+                }
+                float d2 = 0.f;
+#pragma unroll
+                for (int q = 0; q < 4; q += 2) {
+                    dot += u[q].x * v[q].x + u[q].y * v[q].y + u[q].z * v[q].z + u[q].w * v[q].w;
+                    d2 += u[q + 1].x * v[q + 1].x + u[q + 1].y * v[q + 1].y + u[q + 1].z * v[q + 1].z + u[q + 1].w * v[q + 1].w;
+                }
+                dot += d2;
             }
-            for (int j = J4; j < JL; ++j) {
-                const float v = prow[j];
-                dot += myrow[j] * v;
-                piv += v * v;
+            if (j < JU) {                               // one to three groups left, read together as well
+                const float4 u0 = *reinterpret_cast<const float4*>(myrow + j);
+                const float4 v0 = *reinterpret_cast<const float4*>(prow + j);
+                if (j + 4 < JU) {
+                    const float4 u1 = *reinterpret_cast<const float4*>(myrow + j + 4);
+                    const float4 v1 = *reinterpret_cast<const float4*>(prow + j + 4);
+                    if (j + 8 < JU) {
+                        const float4 u2 = *reinterpret_cast<const float4*>(myrow + j + 8);
+                        const float4 v2 = *reinterpret_cast<const float4*>(prow + j + 8);
+                        dot += u2.x * v2.x + u2.y * v2.y + u2.z * v2.z + u2.w * v2.w;
+                    }
+                    dot += u1.x * v1.x + u1.y * v1.y + u1.z * v1.z + u1.w * v1.w;
+                }
+                dot += u0.x * v0.x + u0.y * v0.y + u0.z * v0.z + u0.w * v0.w;
             }
             if (J > KL) {
                 const float* pspill = spill + (size_t)gstar * (k - KL);
-                for (int j = 0; j < J - KL; ++j) {
-                    const float v = pspill[j];
-                    dot += myspill[j] * v;
-                    piv += v * v;
-                }
+                for (int j = 0; j < J - KL; ++j) dot += myspill[j] * pspill[j];
             }
-            const float nrm2 = gdiag - piv;
-            float inv = 0.f;
-            if (nrm2 > 1e-10f * gdiag && nrm2 > 0.f) inv = __builtin_amdgcn_rsqf(nrm2);
-            else bad = 1;
+            if (inv == 0.f) bad = 1;
             const float dv = (gmine - dot) * inv;
             const float bt = ccol * inv;
             corr -= bt * dv;
+            sq += dv * dv;
             if (active) {                                 // lanes without an atom have no row of their own
                 if (J < KL) myrow[J] = dv; else myspill[J - KL] = dv;
             }
