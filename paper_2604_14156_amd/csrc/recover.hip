@@ -522,15 +522,17 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
                 float ci[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const float* e = cb + min(w0 + q, round_waves - 1) * 8;
-                    cw[q] = *reinterpret_cast<const float4*>(e);
-                    ci[q] = e[4];
+                    if (w0 + q < round_waves) {           // uniform: waves without atoms post nothing
+                        const float* e = cb + (w0 + q) * 8;
+                        cw[q] = *reinterpret_cast<const float4*>(e);
+                        ci[q] = e[4];
+                    }
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const bool live = w0 + q < round_waves;
-                    const uint32_t o1 = live ? __float_as_uint(cw[q].x) : 0u;
-                    const uint32_t o2 = live ? __float_as_uint(cw[q].z) : 0u;
+                    if (w0 + q >= round_waves) break;
+                    const uint32_t o1 = __float_as_uint(cw[q].x);
+                    const uint32_t o2 = __float_as_uint(cw[q].z);
                     const bool up = o1 > k1 || w0 + q == 0;   // ties keep the lower wave = lower index
                     k2 = up ? max(max(k2, k1), o2) : max(k2, o1);
                     gstar = up ? __float_as_int(cw[q].y) : gstar;
@@ -585,7 +587,7 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
                 }
                 dot += u0.x * v0.x + u0.y * v0.y + u0.z * v0.z + u0.w * v0.w;
             }
-            if (J > KL) {
+            if (!GRAM_LDS && J > KL) {                  // a Gram matrix in LDS means the whole factor is too
                 const float* pspill = spill + (size_t)gstar * (k - KL);
                 for (int j = 0; j < J - KL; ++j) dot += myspill[j] * pspill[j];
             }
@@ -595,9 +597,9 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
             corr -= bt * dv;
             sq += dv * dv;
             if (active) {                                 // lanes without an atom have no row of their own
-                if (J < KL) myrow[J] = dv; else myspill[J - KL] = dv;
+                if (GRAM_LDS || J < KL) myrow[J] = dv; else myspill[J - KL] = dv;
             }
-            if (tid == 0) { beta[J] = bt; selcol[J] = gstar; }
+            if (WANT_FIT && tid == 0) { beta[J] = bt; selcol[J] = gstar; }
         }
     }
     bad = __syncthreads_or(bad);
@@ -726,12 +728,25 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
         if (lane == 0) red[wave] = ss;
         __syncthreads();
     }
-    for (int qi = tid; qi < k; qi += NT) {
-        const int g = selcol[qi];
-        int rank = 0;
-        for (int o = 0; o < k; ++o) rank += selcol[o] < g;
-        a.support[(size_t)prob * k + rank] = g;
-        if (a.coef) a.coef[(size_t)prob * k + rank] = alpha[qi];
+    if (WANT_FIT) {
+        for (int qi = tid; qi < k; qi += NT) {
+            const int g = selcol[qi];
+            int rank = 0;
+            for (int o = 0; o < k; ++o) rank += selcol[o] < g;
+            a.support[(size_t)prob * k + rank] = g;
+            if (a.coef) a.coef[(size_t)prob * k + rank] = alpha[qi];
+        }
+    } else {
+        // ascending support straight from the selection flags: the rank of a selected atom is the number
+        // of selected atoms below it (no record of the order of selection is kept in this variant)
+        const unsigned long long sb = __ballot(selected);
+        if (lane == 0) red[wave] = __int_as_float(__popcll(sb));
+        __syncthreads();
+        if (selected) {
+            int rank = __popcll(sb & ((1ull << lane) - 1ull));
+            for (int wv = 0; wv < wave; ++wv) rank += __float_as_int(red[wv]);
+            a.support[(size_t)prob * k + rank] = tid;
+        }
     }
     if (tid == 0) {
         if (a.resid) {
