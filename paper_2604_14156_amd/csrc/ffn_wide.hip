@@ -7,14 +7,15 @@
 // registers of the waves that split the reduction index; sixty-four do not (they would take the whole
 // register file of a compute unit).  So here
 //   gate/up : the channels of all listed blocks form one range cut into gridDim.x equal pieces, so every
-//             workgroup streams the same number of bytes.  A workgroup takes its piece in passes of a
-//             few tiles of 8 channels (8 gate rows + 8 up rows each); its waves split the reduction index
-//             (within a chunk of 512 columns wave w owns columns 64 w .. 64 w + 63, so the workgroup
-//             reads 1 KB of consecutive addresses of every weight row per chunk), weights go
-//             global -> registers -> matrix core, one chunk ahead; the token rows are staged chunk by
-//             chunk through LDS, shared by the waves, and come from L2 (every workgroup reads the same
-//             rows).  Accumulators stay in registers over the whole reduction index and the waves'
-//             partial tiles are summed through LDS once per pass.
+//             workgroup streams the same number of bytes, and a workgroup's piece is cut once more
+//             among its waves.  A wave owns a tile of 8 channels (8 gate rows + 8 up rows) over the
+//             whole reduction index: its accumulators (one per tile of 16 tokens) are final, nothing
+//             is summed across waves.  Weights go global -> registers -> matrix core; the registers
+//             of a k-step are refilled with the next chunk's weights right after use, so every load
+//             has a chunk's time to arrive.  The token rows are staged chunk by chunk (512 columns)
+//             through LDS, double buffered and shared by the waves, and come from L2 (every
+//             workgroup reads the same rows).  The first chunk of weights is requested before the
+//             supports have arrived when their union can be guessed.
 //   down    : as for 16 rows (a workgroup owns 16 output columns, waves split the blocks), with one
 //             accumulator per tile of 16 tokens; a lane fetches the hidden values of (block, token)
 //             only when the token lists the block, which keeps the traffic from L2 at the size of the
@@ -23,6 +24,7 @@
 // neither written nor read.
 #include "kernels.hpp"
 #include "common.hpp"
+#include <type_traits>
 
 namespace csk {
 
@@ -32,8 +34,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 constexpr int FW_MAXG = 1024;
 constexpr int FW_ROWS = 64;                           // token rows of the hidden-value buffer per block
 constexpr int GW_WAVES = 8, GW_THREADS = GW_WAVES * 64;
-constexpr int GW_KC = GW_WAVES * 64;                  // columns of the token rows per staged chunk: 64 per wave
-constexpr int GW_NT = 6;                              // tiles of 8 channels per pass of a workgroup
+constexpr int GW_KC = 512;                            // columns of the token rows per staged chunk
 constexpr int GW_XROW = GW_KC + 8;                    // LDS row stride in elements: 16 bytes of padding
 constexpr int DW_WAVES = 8;
 constexpr int DW_UB = 3;                              // blocks in flight per wave
@@ -45,10 +46,12 @@ __device__ __forceinline__ bf16x8_t zfrag() {
 }
 
 // Token masks per block (two words: bit t of word t / 32) and the ascending list of blocks used by at
-// least one token.  Returns the number of listed blocks.
-template <int NWAVES>
-__device__ __forceinline__ int build_list64(const int32_t* __restrict__ support, int T, int k, int shared, int G,
-                                            uint32_t* mlo, uint32_t* mhi, uint16_t* ulist, int* wcount) {
+// least one token.  Returns the number of listed blocks.  `pre` holds support[tid + q * NTH] (or -1 past
+// the end) for q < NPRE, fetched by the caller ahead of its other loads: loads return in order, so an
+// entry requested after the first weights would arrive behind them.
+template <int NWAVES, int NPRE>
+__device__ __forceinline__ int build_list64(const int32_t* __restrict__ support, const int (&pre)[NPRE], int T, int k,
+                                            int shared, int G, uint32_t* mlo, uint32_t* mhi, uint16_t* ulist, int* wcount) {
     constexpr int NTH = NWAVES * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int g = tid; g < G; g += NTH) { mlo[g] = 0u; mhi[g] = 0u; }
@@ -56,16 +59,20 @@ __device__ __forceinline__ int build_list64(const int32_t* __restrict__ support,
     const uint32_t all_lo = T >= 32 ? 0xFFFFFFFFu : ((1u << T) - 1u);
     const uint32_t all_hi = T >= 64 ? 0xFFFFFFFFu : (T > 32 ? ((1u << (T - 32)) - 1u) : 0u);
     const int total = shared ? k : T * k;
-    for (int i = tid; i < total; i += NTH) {
-        const int g = support[i];
+    auto mark = [&](int i, int g) {
         if (g >= 0 && g < G) {
             if (shared) { mlo[g] = all_lo; mhi[g] = all_hi; }
             else {
-                const int t = i / k;
+                // i / k without the integer division: exact, since the token index stays below 64 and k
+                // below 2^10, so (i + 0.5) / k keeps 2^-11 away from the next integer
+                const int t = (int)__fdividef((float)i + 0.5f, (float)k);
                 if (t < 32) atomicOr(&mlo[g], 1u << t); else atomicOr(&mhi[g], 1u << (t - 32));
             }
         }
-    }
+    };
+#pragma unroll
+    for (int q = 0; q < NPRE; ++q) { const int i = tid + q * NTH; if (i < total) mark(i, pre[q]); }
+    for (int i = tid + NPRE * NTH; i < total; i += NTH) mark(i, support[i]);
     __syncthreads();
     int base = 0;
     for (int g0 = 0; g0 < G; g0 += NTH) {
@@ -83,41 +90,115 @@ __device__ __forceinline__ int build_list64(const int32_t* __restrict__ support,
     return base;
 }
 
+// `dense` is the host's guess that the union of the supports is all G blocks (many rows, each listing a
+// good share of the blocks).  The weights of the first chunk are then requested at kernel entry for the
+// channel range that guess implies, a full memory round trip before the supports have come in and the
+// list is known; if the list turns out shorter, the range is recomputed and the loads are issued again
+// (the dropped ones were in bounds whatever the supports say).
 template <int TT>
 __global__ __launch_bounds__(GW_THREADS)
 void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict__ Wu, int d, int G, int b,
                      const uint16_t* __restrict__ x, int T, const int32_t* __restrict__ support, int k, int shared,
-                     uint16_t* __restrict__ hbuf, uint32_t* __restrict__ list_out) {
+                     int dense, uint16_t* __restrict__ hbuf, uint32_t* __restrict__ list_out) {
     __shared__ uint32_t mlo[FW_MAXG], mhi[FW_MAXG];
     __shared__ uint16_t ulist[FW_MAXG];
     __shared__ int wcount[GW_WAVES];
-    // token rows of one chunk, double buffered; the same memory holds the waves' partial tiles at the end of a pass
-    __shared__ __attribute__((aligned(16))) uint16_t xs[2][TT * 16 * GW_XROW];
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][TT * 16 * GW_XROW];   // token rows of one chunk, double buffered
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, kg = lane >> 4;
 
     // staging of the token rows: a chunk is TT*16 rows x GW_KC columns, in pieces of 16 bytes
     constexpr int PPR = GW_KC / 8;                                     // pieces per row
     constexpr int XP = (TT * 16 * PPR + GW_THREADS - 1) / GW_THREADS;  // pieces per thread
+    static_assert((TT * 16 * PPR) % GW_THREADS == 0, "every thread stages the same number of pieces");
     uint4 xr[XP];
-    auto x_fetch = [&](int chunk) {
+    // rows past the last token repeat it: their products land in accumulator rows that are never stored
+    uint32_t xoff[XP];
 #pragma unroll
-        for (int p = 0; p < XP; ++p) {
-            const int id = tid + p * GW_THREADS, row = id / PPR, piece = id % PPR;
-            const bool ok = id < TT * 16 * PPR && row < T && chunk * GW_KC + piece * 8 < d;
-            xr[p] = ok ? *reinterpret_cast<const uint4*>(x + (size_t)row * d + chunk * GW_KC + piece * 8) : make_uint4(0u, 0u, 0u, 0u);
+    for (int p = 0; p < XP; ++p) {
+        const int id = tid + p * GW_THREADS, row = id / PPR, piece = id % PPR;
+        xoff[p] = (uint32_t)min(row, T - 1) * (uint32_t)d + (uint32_t)piece * 8u;
+    }
+    auto x_fetch = [&](int chunk) {
+        if ((chunk + 1) * GW_KC <= d) {                // uniform: a whole chunk
+#pragma unroll
+            for (int p = 0; p < XP; ++p) xr[p] = *reinterpret_cast<const uint4*>(x + xoff[p] + (uint32_t)(chunk * GW_KC));
+        } else {
+#pragma unroll
+            for (int p = 0; p < XP; ++p) {
+                const int piece = (tid + p * GW_THREADS) % PPR;
+                xr[p] = chunk * GW_KC + piece * 8 < d ? *reinterpret_cast<const uint4*>(x + xoff[p] + (uint32_t)(chunk * GW_KC))
+                                                      : make_uint4(0u, 0u, 0u, 0u);
+            }
         }
     };
     auto x_stash = [&](int buf) {
 #pragma unroll
         for (int p = 0; p < XP; ++p) {
             const int id = tid + p * GW_THREADS, row = id / PPR, piece = id % PPR;
-            if (id < TT * 16 * PPR) *reinterpret_cast<uint4*>(&xs[buf][row * GW_XROW + piece * 8]) = xr[p];
+            *reinterpret_cast<uint4*>(&xs[buf][row * GW_XROW + piece * 8]) = xr[p];
         }
     };
-    x_fetch(0);                                       // in flight while the list is built
+    constexpr int NPRE = 8;
+    int pre[NPRE];
+    {
+        const int total = shared ? k : T * k;
+#pragma unroll
+        for (int q = 0; q < NPRE; ++q) { const int i = tid + q * GW_THREADS; pre[q] = i < total ? support[i] : -1; }
+    }
 
-    const int nblocks = build_list64<GW_WAVES>(support, T, k, shared, G, mlo, mhi, ulist, wcount);
+    // The channels of the listed blocks form one range cut into gridDim.x equal pieces, and a workgroup's
+    // piece into GW_WAVES equal pieces: wave w owns channels [w_lo, w_hi) and works through them in tiles
+    // of 8 (8 gate rows + 8 up rows = the 16 columns of a matrix-core tile), all of the reduction index
+    // per tile.  Lane (ln, kg) loads row ln of the tile: channel c0 + (ln & 7) of the gate (ln < 8) or up
+    // matrix, 16 bytes at column 32 s + 8 kg of k-step s.
+    constexpr int KS = GW_KC / 32;                     // k-steps per chunk
+    int w_lo = 0, w_hi = 0, npass = 0;
+    auto set_range = [&](int nb) {
+        const long F = (long)nb * b;
+        const int f_lo = (int)((long)blockIdx.x * F / gridDim.x), f_hi = (int)((long)(blockIdx.x + 1) * F / gridDim.x);
+        const int cpw = (f_hi - f_lo + GW_WAVES - 1) / GW_WAVES;
+        w_lo = min(f_hi, f_lo + wave * cpw);
+        w_hi = min(f_hi, w_lo + cpw);
+        npass = (cpw + 7) >> 3;                        // the same for every wave of the workgroup
+    };
+    const uint16_t* rp = Wg;                           // this lane's weight row of the current tile, at column 8 kg
+    int my_g = 0, my_ch = 0;
+    bool my_ok = false;
+    auto set_tile = [&](int c0, bool identity) {
+        const int f = c0 + (ln & 7);
+        my_ok = f < w_hi;
+        const int fc = my_ok ? f : c0;                 // rows past the end repeat the first one; they are not stored
+        const int slot = fc / b;
+        my_ch = fc - slot * b;
+        my_g = identity ? slot : (int)ulist[slot];
+        rp = (ln < 8 ? Wg : Wu) + ((size_t)my_g * b + my_ch) * d + kg * 8;
+    };
+    // The weights of a chunk, one fragment per k-step.  In a chunk that runs past the last column the k-steps
+    // beyond it read column 0 instead (in bounds) and meet the zeros staged for the token rows.
+    bf16x8_t wb[KS];
+    auto w_fetch_all = [&](int chunk) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int col = chunk * GW_KC + s * 32;
+            wb[s] = ldfrag(rp + (col < d ? col : 0));
+        }
+    };
+    // Chunks are taken in an order rotated by the workgroup's index (when all chunks are whole), so that the
+    // workgroups do not all ask L2 for the same token rows at the same moment.
+    const int nchunks = (d + GW_KC - 1) / GW_KC;
+    const int nwhole = d / GW_KC;                      // chunks 0 .. nwhole - 1 are whole, one ragged chunk may follow
+    const int rot = nwhole == nchunks ? (int)(blockIdx.x % (unsigned)nchunks) : 0;
+    auto chunk_of = [&](int i) { const int c = i + rot; return c >= nchunks ? c - nchunks : c; };
+
+    // issued by every lane whatever `dense` says (a wave without a share, or a call whose union is not
+    // guessed, reads rows it will drop): the number of loads in flight is then known at compile time, and
+    // the wait for the support entries does not have to cover the weights as well
+    x_fetch(chunk_of(0));
+    set_range(G);
+    set_tile(min(w_lo, G * b - 1), true);
+    w_fetch_all(chunk_of(0));
+    const int nblocks = build_list64<GW_WAVES, NPRE>(support, pre, T, k, shared, G, mlo, mhi, ulist, wcount);
     // the down kernel takes the list and the masks from here: [0] count, [1 + i] block of slot i,
     // [1 + FW_MAXG + i] and [1 + 2 FW_MAXG + i] the two words of its token mask
     if (blockIdx.x == 0) {
@@ -129,90 +210,82 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
             list_out[1 + 2 * FW_MAXG + i] = mhi[g];
         }
     }
-    // this workgroup's piece of the channel range, in passes of GW_NT tiles of 8 channels.  All waves work
-    // on the same tiles and split the reduction index: within a chunk of GW_KC columns wave w takes
-    // columns 64 w .. 64 w + 63, so that the workgroup as a whole reads 1 KB of consecutive addresses of
-    // every weight row per chunk.
-    const long F = (long)nblocks * b;
-    const int f_lo = (int)((long)blockIdx.x * F / gridDim.x), f_hi = (int)((long)(blockIdx.x + 1) * F / gridDim.x);
-    const int nchunks = (d + GW_KC - 1) / GW_KC;
-    for (int f0 = f_lo; f0 < f_hi; f0 += GW_NT * 8) {
-        // rows of this lane: tile nt, channel f0 + 8 nt + (ln & 7); lanes 0-7 of a 16-lane row take the
-        // gate matrix, lanes 8-15 the up matrix
-        const uint16_t* rp[GW_NT];
-        bool row_ok[GW_NT];
-#pragma unroll
-        for (int nt = 0; nt < GW_NT; ++nt) {
-            const int f = f0 + 8 * nt + (ln & 7);
-            row_ok[nt] = f < f_hi;
-            const int slot = row_ok[nt] ? f / b : 0;
-            const int ch = row_ok[nt] ? f - slot * b : 0;
-            rp[nt] = (ln < 8 ? Wg : Wu) + ((size_t)ulist[slot] * b + ch) * d + wave * 64 + kg * 8;
-        }
-        // the weights of the next chunk are requested into the registers of the current one as soon as
-        // the matrix instructions have consumed them
-        bf16x8_t wb[GW_NT][2];
-        auto w_fetch = [&](int s, int chunk) {
-            const int col = chunk * GW_KC + wave * 64 + s * 32;
-#pragma unroll
-            for (int nt = 0; nt < GW_NT; ++nt)
-                wb[nt][s] = (row_ok[nt] && col < d) ? ldfrag(rp[nt] + chunk * GW_KC + s * 32) : zfrag();
-        };
-        w_fetch(0, 0);
-        w_fetch(1, 0);
-        if (f0 != f_lo) x_fetch(0);
+    const bool guessed = dense && nblocks == G;        // an ascending list of all G blocks is the identity
+    if (!guessed) set_range(nblocks);
+    for (int pass = 0; pass < npass; ++pass) {
+        const int c0 = w_lo + 8 * pass;
+        const bool busy = c0 < w_hi;                   // uniform over the wave
+        if (busy && !(pass == 0 && guessed)) { set_tile(c0, false); w_fetch_all(chunk_of(0)); }
+        if (pass != 0) x_fetch(chunk_of(0));
         __syncthreads();                               // everybody is done with the staging buffers
         x_stash(0);
         __syncthreads();
-        f32x4_t acc[GW_NT][TT];
+        f32x4_t acc[TT];
 #pragma unroll
-        for (int nt = 0; nt < GW_NT; ++nt)
+        for (int mt = 0; mt < TT; ++mt) acc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        // One chunk (the i-th in this workgroup's order): the token rows of the next chunk are requested
+        // first, then the k-steps run: the token fragments of k-step s + 1 are read from LDS before the
+        // matrix instructions of k-step s are issued (the scheduling fences keep that order, so no matrix
+        // instruction waits for a read issued just before it), and the registers of a k-step take the
+        // next chunk's weights as soon as they are free, so every fragment has a chunk's time to arrive.
+        // NEXT says what follows the chunk (0 nothing, 1 a whole chunk, 2 a ragged one) at compile time:
+        // the loop over the whole chunks is free of branches, and the other two cases stand after it.
+        auto chunk_step = [&](int i, auto next) {
+            constexpr int NEXT = decltype(next)::value;
+            const int buf = i & 1;
+            const int cn = chunk_of(i + 1);
+            if (NEXT != 0) x_fetch(cn);
+            if (busy) {
+                const uint16_t* rpn = rp + cn * GW_KC;
+                const uint16_t* xb = &xs[buf][ln * GW_XROW + kg * 8];
+                bf16x8_t a[2][TT];
 #pragma unroll
-            for (int mt = 0; mt < TT; ++mt) acc[nt][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < nchunks; ++c) {
-            const int buf = c & 1;
-            if (c + 1 < nchunks) x_fetch(c + 1);
+                for (int mt = 0; mt < TT; ++mt) a[0][mt] = *reinterpret_cast<const bf16x8_t*>(xb + mt * 16 * GW_XROW);
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                bf16x8_t a[TT];
+                for (int s = 0; s < KS; ++s) {
+                    if (s + 1 < KS) {
 #pragma unroll
-                for (int mt = 0; mt < TT; ++mt)
-                    a[mt] = *reinterpret_cast<const bf16x8_t*>(&xs[buf][(mt * 16 + ln) * GW_XROW + wave * 64 + s * 32 + kg * 8]);
-#pragma unroll
-                for (int nt = 0; nt < GW_NT; ++nt)
+                        for (int mt = 0; mt < TT; ++mt)
+                            a[(s + 1) & 1][mt] = *reinterpret_cast<const bf16x8_t*>(xb + mt * 16 * GW_XROW + (s + 1) * 32);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int mt = 0; mt < TT; ++mt)
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], wb[nt][s], acc[nt][mt], 0, 0, 0);
-                if (c + 1 < nchunks) w_fetch(s, c + 1);
-            }
-            if (c + 1 < nchunks) x_stash(buf ^ 1);
-            __syncthreads();
-        }
-        // the waves' partial tiles are summed through LDS, one tile of 8 channels (x TT token tiles) at a time.
-        // Element e = lane*4 + i of a 16 x 16 tile is (token 4*(lane/16)+i, column lane%16); columns 0-7 are
-        // gate channels, 8-15 the matching up channels (32 elements further).
-        float* red = reinterpret_cast<float*>(&xs[0][0]);              // [GW_WAVES][TT][256]
-#pragma unroll
-        for (int nt = 0; nt < GW_NT; ++nt) {
-            if (f0 + 8 * nt < f_hi) {                                  // uniform over the workgroup
-#pragma unroll
-                for (int mt = 0; mt < TT; ++mt)
-                    *reinterpret_cast<f32x4_t*>(&red[(wave * TT + mt) * 256 + lane * 4]) = acc[nt][mt];
-                __syncthreads();
-                for (int e = tid; e < TT * 256; e += GW_THREADS) {
-                    const int mt = e >> 8, r = e & 255, col = (r >> 2) & 15;
-                    const int f = f0 + 8 * nt + col;
-                    if (col < 8 && f < f_hi) {
-                        float sg = 0.f, su = 0.f;
-#pragma unroll
-                        for (int w = 0; w < GW_WAVES; ++w) { sg += red[(w * TT + mt) * 256 + r]; su += red[(w * TT + mt) * 256 + r + 32]; }
-                        const int slot = f / b, ch = f - slot * b, g = ulist[slot];
-                        const int tok = mt * 16 + 4 * (r >> 6) + (r & 3);
-                        const bool uses = tok < 32 ? ((mlo[g] >> tok) & 1u) : ((mhi[g] >> (tok - 32)) & 1u);
-                        if (tok < T && uses) hbuf[((size_t)g * FW_ROWS + tok) * b + ch] = f32_to_bf16(sg / (1.0f + __expf(-sg)) * su);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s & 1][mt], wb[s], acc[mt], 0, 0, 0);
+                    if (NEXT == 1) wb[s] = ldfrag(rpn + s * 32);
+                    if (NEXT == 2) {
+                        const int col = cn * GW_KC + s * 32;
+                        wb[s] = ldfrag(rp + (col < d ? col : 0));
                     }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __syncthreads();
+            }
+            if (NEXT != 0) x_stash(buf ^ 1);
+            __syncthreads();
+        };
+        int i = 0;
+        for (; i + 1 < nwhole; ++i) chunk_step(i, std::integral_constant<int, 1>{});
+        if (nwhole < nchunks) {
+            if (nwhole > 0) { chunk_step(i, std::integral_constant<int, 2>{}); ++i; }
+            chunk_step(i, std::integral_constant<int, 0>{});
+        } else {
+            chunk_step(i, std::integral_constant<int, 0>{});
+        }
+        // Element i of a lane's accumulator is (token 16 mt + 4 (lane / 16) + i, column lane % 16); columns 0-7
+        // are the gate channels, 8-15 the matching up channels, eight lanes further.
+        if (busy) {
+            const uint32_t lo = mlo[my_g], hi = mhi[my_g];
+#pragma unroll
+            for (int mt = 0; mt < TT; ++mt) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float mine = acc[mt][e];
+                    const float other = __shfl_xor(mine, 8);
+                    const int tok = mt * 16 + 4 * kg + e;
+                    const bool uses = mt < 2 ? ((lo >> (tok & 31)) & 1u) : ((hi >> (tok & 31)) & 1u);
+                    if (ln < 8 && my_ok && tok < T && uses)
+                        hbuf[((size_t)my_g * FW_ROWS + tok) * b + my_ch] = f32_to_bf16(mine / (1.0f + __expf(-mine)) * other);
+                }
             }
         }
     }
@@ -303,6 +376,7 @@ hipError_t launch_ffn_wide(const FfnArgs& a, hipStream_t s) {
     uint32_t* list = reinterpret_cast<uint32_t*>(hbuf + (size_t)a.G * FW_ROWS * a.b);
     const int union_max = a.T * a.k < a.G ? a.T * a.k : a.G;
     long grid = (long)union_max * a.b / 8;             // at least one tile of 8 channels per workgroup
+    const int dense = (long)a.T * a.k >= 4L * a.G;     // every block is then listed by some row, almost surely
     if (grid > 256) grid = 256;
     if (grid < 1) grid = 1;
     int dgrid = (a.d + 15) / 16;
@@ -310,7 +384,7 @@ hipError_t launch_ffn_wide(const FfnArgs& a, hipStream_t s) {
     const int tt = (a.T + 15) / 16;
 #define CS_WIDE(TTV) do { \
         hipLaunchKernelGGL((ffn_gateup_wide<TTV>), dim3((unsigned)grid), dim3(GW_THREADS), 0, s, (const uint16_t*)a.Wg, \
-                           (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, hbuf, list); \
+                           (const uint16_t*)a.Wu, a.d, a.G, a.b, (const uint16_t*)a.x, a.T, a.support, a.k, a.shared, dense, hbuf, list); \
         hipLaunchKernelGGL((ffn_down_wide<TTV>), dim3(dgrid), dim3(DW_WAVES * 64), 0, s, (const uint16_t*)a.Wd, a.d, a.G, \
                            a.b, hbuf, a.T, list, (uint16_t*)a.out); } while (0)
     if (tt <= 2) CS_WIDE(2); else if (tt == 3) CS_WIDE(3); else CS_WIDE(4);
