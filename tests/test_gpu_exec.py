@@ -156,11 +156,13 @@ def test_joint_prompt_shape_gather_and_ffn(cs):
 
 
 @pytest.mark.parametrize("T,G,b,k,d", [(17, 10, 64, 3, 512), (37, 12, 32, 5, 416), (48, 30, 64, 30, 256), (64, 7, 96, 2, 1056),
-                                       (33, 300, 64, 4, 128)])
+                                       (33, 300, 64, 4, 128), (64, 9, 64, 7, 512), (30, 6, 64, 5, 256), (64, 40, 64, 10, 1536)])
 def test_ffn_bf16_17_to_64_rows_per_token_supports(cs, T, G, b, k, d):
     """The path for 17 to 64 token rows with their own supports: ragged token tiles, a width that is no
     multiple of the staged chunk, blocks of 32 and 96 channels, k == G, more channels than one pass of a
-    workgroup holds (300 blocks on few workgroups is not reached here, many blocks on 256 are)."""
+    workgroup holds (300 blocks on few workgroups is not reached here, many blocks on 256 are), blocks
+    listed by more than half of the tokens (two items per block in the down kernel for 64-channel blocks,
+    at two, three and four token tiles) and by fewer (one item)."""
     _ffn_case(cs, 1800 + T, G, b, d, k, T, "bf16", False, 0.05)
 
 
