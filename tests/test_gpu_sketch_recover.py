@@ -130,6 +130,40 @@ def test_decode_shape_batch(cs):
     for t in range(6):
         rec = oracle.block_omp(M, Y[t].astype(np.float64), c.G, 1, c.k, True)
         assert_greedy_support(M, Y[t].astype(np.float64), c.G, 1, c.k, True, sup[t], rec)
+    # support and margin only (the variant the decode loop runs: no record of the order of selection,
+    # the ascending support written from the selection flags)
+    sel, _, _, mg = cs.cs_recover_support(op, dct, c.k, dev_f32(Y), want_coef=False, want_resid=False)
+    sel, mg = host(sel), host(mg)
+    for t in range(6):
+        rec = oracle.block_omp(M, Y[t].astype(np.float64), c.G, 1, c.k, True)
+        assert list(sel[t]) == list(rec["support"]) and abs(mg[t] - rec["margin"]) <= 1e-3
+
+
+def test_gram_matrix_outside_lds_whole_factor_inside(cs):
+    """300 units of one atom, k = 24, m = 96: the Gram matrix (360 KB) stays in global memory while the whole
+    factor fits in LDS, five waves own atoms (the last one partly), the unit count is no multiple of 64.
+    Both variants of the one-atom kernel against the oracle; the oracle's margins on this seed are 1.1e-2,
+    1.2e-2, 1.7e-3, 9.4e-4 and 1.8e-2: four instances bit for bit, one through the near-tie replay."""
+    seed, G, b, k, m, B = 2701, 300, 8, 24, 96, 5
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, G, b)
+    z, S = wl.plant_usage(rng, pi, k, B, 1.0, 0.01)
+    op = binding.make_op(wl.RADEMACHER, seed, 1, m, G * b)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, G, b, 1)
+    M = oracle.effective_matrix(wl.RADEMACHER, seed, 1, m, G * b, G, b, 1, psi)
+    Y = oracle.sketch(wl.RADEMACHER, seed, 1, m, z).astype(np.float32)
+    exact = _check_recovery(cs, op, dct, psi_dev, M, Y, G, 1, k, True)
+    sel, _, _, mg = cs.cs_recover_support(op, dct, k, dev_f32(Y), want_coef=False, want_resid=False)
+    sel, mg = host(sel), host(mg)
+    again = 0
+    for t in range(B):
+        y = Y[t].astype(np.float64)
+        rec = oracle.block_omp(M, y, G, 1, k, True)
+        again += assert_greedy_support(M, y, G, 1, k, True, sel[t], rec)
+        if rec["margin"] > MARGIN:
+            assert abs(mg[t] - rec["margin"]) <= 1e-3
+    assert again == exact == 4
 
 
 def test_literal_entrywise_usage_still_matches_oracle(cs):
