@@ -166,6 +166,22 @@ def test_ffn_bf16_17_to_64_rows_per_token_supports(cs, T, G, b, k, d):
     _ffn_case(cs, 1800 + T, G, b, d, k, T, "bf16", False, 0.05)
 
 
+def test_ffn_17_to_64_rows_supports_from_a_few_blocks(cs):
+    """Forty rows whose supports all come from 12 of 50 blocks: the rows list eight times as many entries as
+    there are blocks, so the kernel starts on the guess that every block is listed, finds a list of at most
+    12 and has to take its channel ranges from that list instead."""
+    rng = wl.rng_for(1860)
+    G, b, d, T, k = 50, 64, 1024, 40, 10
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, G, b, d, 0.05, "bf16")
+    x = wl.make_tokens(rng, T, d, "bf16")
+    pool = rng.choice(G, size=12, replace=False)
+    sup = np.stack([rng.choice(pool, size=k, replace=False) for _ in range(T)]).astype(np.int32)
+    got = host(cs.cs_block_ffn(dev_bf16(Wg), dev_bf16(Wu), dev_bf16(Wd), dev_bf16(x), dev_i32(sup), False))
+    want = oracle.block_ffn(Wg, Wu, Wd, x, sup)
+    for t in range(T):
+        check_row(got[t], want[t], "bf16", t)
+
+
 def test_ffn_17_to_64_rows_out_of_range_units(cs):
     rng = wl.rng_for(1850)
     G, b, d, T = 8, 64, 256, 20
