@@ -194,9 +194,10 @@ void ffn_gemm_kernel(GemmArgs a) {
 // wave fills bytes 16p .. 16p+15 of a 1 KB run, i.e. 16 rows of 64 bytes), which needs no staging
 // registers; the XOR swizzle that keeps the fragment reads conflict free is applied on the global
 // side, by choosing which 16-byte chunk of its row a lane fetches.  Tiles travel in pairs (a
-// 64-column step): while one pair is multiplied the next is in flight, and one barrier per pair
-// sits before the pair's last k-step, whose multiplies hide the issue of the following fetch.
-// Fragment reads for the next k-step are spread between the multiplies of the current one.
+// 64-column step) through four stages; a stage is refilled with the tile two pairs ahead as soon as
+// every wave has read it for the last time (two barriers per pair), its loads spread one per four
+// multiplies over the next two k-steps.  Fragment reads for the next k-step are spread between the
+// multiplies of the current one.
 // ---------------------------------------------------------------------------
 constexpr int GW_BM = 256, GW_BN = 256, GW_BK = 32;
 #ifndef CS_GW_MIN_WGS
@@ -264,39 +265,33 @@ void ffn_gemm_wide_kernel(GemmArgs a) {
             pb[u] = a.Wd + (size_t)min(bn + r, d - 1) * 64 + chunk * 8;
         }
     }
-    // Tiles are fetched in pairs (one 64-column step: both 64-byte halves of every 128-byte line
-    // are requested back to back, so each line crosses the L2 -> L1 path once).  Pair q goes to
-    // stages 2 (q & 1) and 2 (q & 1) + 1; a pair past the last one repeats the last one and is never
-    // multiplied.  Part u of 4 is one run of A rows and one run of B rows, for both tiles.
+    // Tiles travel in pairs (a 64-column step, one block of the down product): pair q lives in stages
+    // 2 (q & 1) (its first tile) and 2 (q & 1) + 1 (its second); a pair past the last one repeats the last
+    // one and is never multiplied.  A stage takes 8 loads per wave (4 parts of A rows, 4 parts of B rows);
+    // they are issued one per four multiplies, spread over two k-steps, because the compute unit's load
+    // path takes 16 cycles per instruction and wave: sixteen of them inside one k-step (32 KB for the
+    // workgroup against 512 cycles of multiplies) made that k-step three times as long as the others.
     // Inside the loop the block id of the down product comes from a copy of the list in LDS: LDS
     // reads complete in order, so waiting for it does not drain the fragment reads in flight the
     // way a scalar load's wait would (and a vector load's wait would drain the tiles in flight).
     const int plast = ktiles / 2 - 1;
-    const bf16x8_t* St_issue = nullptr;
-    size_t aoff_issue = 0, boff_issue = 0;
-    int q_issue = 0;
-    uint32_t g_issue = 0;
-    auto issue_prefetch = [&](int q, bool from_lds) {
-        q_issue = q;
-        if (MODE == 1) g_issue = from_lds ? (uint32_t)blk_lds[min(q, plast)] : (uint32_t)blocks[min(q, plast)];
+    struct Refill { const bf16x8_t* St; size_t ao, bo; };
+    auto refill_of = [&](int q, int second, uint32_t g) {
+        Refill r;
+        r.St = S[2 * (q & 1) + second];
+        r.ao = (size_t)min(q, plast) * (2 * GW_BK) + second * GW_BK;
+        r.bo = MODE == 0 ? r.ao : (size_t)g * d * 64 + second * GW_BK;
+        return r;
     };
-    auto issue_begin = [&]() {
-        St_issue = S[2 * (q_issue & 1)];
-        aoff_issue = (size_t)min(q_issue, plast) * (2 * GW_BK);
-        if (MODE == 0) boff_issue = aoff_issue;
-        else boff_issue = (size_t)g_issue * d * 64;
+    // load i (0..7) of a stage: part i / 2 of the A rows (even i) or of the B rows (odd i)
+    auto issue_one = [&](const Refill& r, int i) {
+        const int u = i >> 1;
+        if ((i & 1) == 0) load_to_lds_16(pa[u] + r.ao, r.St + (u * 4 + wave) * 64);
+        else load_to_lds_16(pb[u] + r.bo, r.St + GW_BM * 4 + (u * 4 + wave) * 64);
     };
-    auto issue_part = [&](int u) {
-        load_to_lds_16(pa[u] + aoff_issue, St_issue + (u * 4 + wave) * 64);
-        load_to_lds_16(pa[u] + aoff_issue + GW_BK, St_issue + GW_STAGE + (u * 4 + wave) * 64);
-        load_to_lds_16(pb[u] + boff_issue, St_issue + GW_BM * 4 + (u * 4 + wave) * 64);
-        load_to_lds_16(pb[u] + boff_issue + GW_BK, St_issue + GW_STAGE + GW_BM * 4 + (u * 4 + wave) * 64);
-    };
-    auto issue = [&](int q) {
-        issue_prefetch(q, false);
-        issue_begin();
-#pragma unroll
-        for (int u = 0; u < 4; ++u) issue_part(u);
+    auto block_of = [&](int q, bool from_lds) -> uint32_t {
+        if (MODE != 1) return 0u;
+        return from_lds ? (uint32_t)blk_lds[min(q, plast)] : (uint32_t)blocks[min(q, plast)];
     };
     f32x16_t acc[4][4];
 #pragma unroll
@@ -330,40 +325,59 @@ void ffn_gemm_wide_kernel(GemmArgs a) {
     };
     // The order below is pinned with scheduling barriers: left alone, the compiler sinks every
     // fragment read next to its first use, which exposes the LDS latency four times per tile.
-    // One workgroup barrier per pair of tiles, placed between the two k-steps of the pair's second
-    // tile; s_waitcnt immediates: vmcnt(16) / vmcnt(0), each with lgkmcnt(0) (a pair is 16 loads).
+    // A pair is four k-steps of 16 multiplies; k-step s multiplies fragment set s & 1 while the next
+    // k-step's fragments are read into the other set.  Two workgroup barriers per pair: after the first
+    // k-step every wave has read the pair's first stage for the last time, after the third the second
+    // stage.  A freed stage is refilled with the tile two pairs ahead over the next two k-steps.  In issue
+    // order the loads of a wave are: first tile of pair q+2 (k-steps 2, 3 of pair q), second tile of pair
+    // q+2 (k-step 4 of pair q, k-step 1 of pair q+1), first tile of pair q+3, ...  A barrier that must see
+    // a tile landed (the second tile of pair q at the first barrier, the first tile of pair q+1 at the
+    // second) therefore has exactly two younger stages in flight: s_waitcnt vmcnt(16), with lgkmcnt(0)
+    // for the wave's own fragment reads of the stage that is about to be refilled.
     if (ktiles > 0) {
-        issue(0); issue(1);
+        {
+            const uint32_t g0 = block_of(0, false), g1 = block_of(1, false);
+            const Refill r00 = refill_of(0, 0, g0), r01 = refill_of(0, 1, g0), r10 = refill_of(1, 0, g1), r11 = refill_of(1, 1, g1);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) issue_one(r00, i);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) issue_one(r01, i);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) issue_one(r10, i);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) issue_one(r11, i);
+        }
         __builtin_amdgcn_s_waitcnt(0x4070);            // pair 0 has landed (pair 1 still in flight)
         __syncthreads();
         frags(0, 0, 0);
         // one k-step: the 16 multiplies of fragment set `set`, with the reads of the next k-step's
-        // fragments (two per four multiplies) spread between them
-        auto kstep = [&](int set, int tn, int kkn) {
+        // fragments (two per four multiplies) and four loads of a refill (one per four multiplies)
+        // spread between them
+        auto kstep = [&](int set, int tn, int kkn, const Refill& r, int half, bool loads) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 frag_pair(set ^ 1, tn, kkn, i);
                 multiply_row(set, i);
+                if (loads) issue_one(r, 4 * half + i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
+        uint32_t g_prev = block_of(1, false);          // block of pair q + 1
         for (int q = 0; q <= plast; ++q) {
             const int t = 2 * q;
-            issue_prefetch(q + 2, true);
-            kstep(0, t, 1);
-            kstep(1, t + 1, 0);
-            kstep(0, t + 1, 1);
-            __builtin_amdgcn_s_waitcnt(0x0070);        // pair q+1 has landed, own reads of pair q are done
-            __syncthreads();                            // ... for every wave: the stages of pair q are free
-            issue_begin();
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                frag_pair(0, t + 2, 0, i);
-                multiply_row(1, i);
-                issue_part(i);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            const uint32_t g_next = block_of(q + 2, true);
+            const Refill rb_prev = refill_of(q + 1, 1, g_prev);     // second tile of pair q + 1, half issued already
+            kstep(0, t, 1, rb_prev, 1, q > 0);
+            __builtin_amdgcn_s_waitcnt(0x4070);        // second tile of pair q landed; own reads of the first stage done
+            __syncthreads();
+            const Refill ra = refill_of(q + 2, 0, g_next);
+            kstep(1, t + 1, 0, ra, 0, true);
+            kstep(0, t + 1, 1, ra, 1, true);
+            __builtin_amdgcn_s_waitcnt(0x4070);        // first tile of pair q + 1 landed; own reads of the second stage done
+            __syncthreads();
+            const Refill rb = refill_of(q + 2, 1, g_next);
+            kstep(1, t + 2, 0, rb, 0, true);
+            g_prev = g_next;
         }
         __builtin_amdgcn_s_waitcnt(0x0070);            // surplus fetches land before the LDS is released
     }
