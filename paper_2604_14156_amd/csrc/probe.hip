@@ -9,6 +9,7 @@ namespace csk {
 
 constexpr int PR_THREADS = 1024;
 constexpr int PR_UNROLL = 8;          // 16-byte loads in flight per lane
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
 __global__ __launch_bounds__(PR_THREADS)
 void stream_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* __restrict__ checksum) {
@@ -21,7 +22,13 @@ void stream_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* __r
 #pragma unroll
         for (int u = 0; u < PR_UNROLL; ++u) {
             const size_t i = base + (size_t)u * PR_THREADS + threadIdx.x;
-            v[u] = i < n16 ? src[i] : make_uint4(0u, 0u, 0u, 0u);
+            // read once: the non-temporal hint is worth about a tenth of the rate on this device
+            if (i < n16) {
+                const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src) + i);
+                v[u] = make_uint4(t[0], t[1], t[2], t[3]);
+            } else {
+                v[u] = make_uint4(0u, 0u, 0u, 0u);
+            }
         }
 #pragma unroll
         for (int u = 0; u < PR_UNROLL; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;

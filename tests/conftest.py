@@ -21,5 +21,8 @@ def cs():
         pytest.fail("GPU test collected on a machine without a GPU")
     ctx = gpu_util.guarded_context(0)
     yield ctx
-    assert ctx.guards_checked > 0
+    # every buffer the binding allocated for a result was checked (a selection of tests that lets the caller
+    # allocate all outputs allocates none)
+    assert ctx.guards_checked >= ctx.guards_allocated - len(ctx._pending)
+    assert ctx.guards_allocated == 0 or ctx.guards_checked > 0
     ctx.close()

@@ -58,6 +58,7 @@ def guarded_context(device=0):
         def __init__(self, device):
             super().__init__(device=device)
             self._pending = []
+            self.guards_allocated = 0
             self.guards_checked = 0
 
         def _alloc(self, shape, dtype, device):
@@ -67,6 +68,7 @@ def guarded_context(device=0):
             nbytes = n * torch.empty((), dtype=dtype).element_size()
             raw = torch.full((2 * GUARD_BYTES + nbytes,), GUARD_FILL, dtype=torch.uint8, device=device)
             self._pending.append((raw, nbytes))
+            self.guards_allocated += 1
             return raw[GUARD_BYTES:GUARD_BYTES + nbytes].view(dtype).view(tuple(shape))
 
         def _check(self, st):
