@@ -425,10 +425,16 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     // accepts: at the 7B shape that is 9.2 KB, which still fits on a compute unit beside a recovery
     // workgroup of another stream (147 KB), so the kernel does not have to wait for that unit
     extern __shared__ __attribute__((aligned(16))) unsigned char dn_lds[];
+    // the waves' turning tiles (16 rows x 144 bytes each: weights arrive as whole lines, the matrix cores
+    // want fragments, as in the gate/up kernel) share their memory with the partial sums, which are
+    // written after the last tile has been read
+    static_assert(DN_WAVES * 16 * FD_TROW * sizeof(uint16_t) >= DN_WAVES * 256 * sizeof(float), "the sums fit into the tiles' memory");
     float (*red)[256] = reinterpret_cast<float (*)[256]>(dn_lds);                       // [DN_WAVES][256]
-    uint32_t* umask = reinterpret_cast<uint32_t*>(dn_lds + DN_WAVES * 256 * sizeof(float));
+    uint32_t* umask = reinterpret_cast<uint32_t*>(dn_lds + DN_WAVES * 16 * FD_TROW * sizeof(uint16_t));
     uint16_t* ulist = reinterpret_cast<uint16_t*>(umask + G);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint16_t* turn = reinterpret_cast<uint16_t*>(dn_lds) + wave * 16 * FD_TROW;
+    const int lr = lane >> 3, lc = lane & 7;          // as a loader: row of the half tile, 16-byte piece of the line
     // the list of used blocks, written by the gate/up kernel of the same call
     // (G entries are fetched whatever the count says, so that both loads are in flight together)
     for (int i = tid; i < G; i += DN_WAVES * 64) {
@@ -455,20 +461,31 @@ void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
                     const bool ok = u < nblocks && ks + e < ksteps;
-                    const int g = ok ? ulist[u] : 0;
+                    const int g = u < nblocks ? ulist[u] : 0;
                     const bool tok_uses = ok && ((umask[ok ? u : 0] >> ln) & 1u);      // token ln lists block g
                     const int ch = (ks + e) * 32 + kg * 8;
-                    wa[q][e] = (ok && row_ok) ? load_frag(Wd + ((size_t)g * d + col0 + ln) * b + ch) : zero_frag();
+                    // load e of a block: lines of rows col0 + 8 e + lr, the 64 channels of k-steps ks and ks + 1
+                    const int wrow = col0 + 8 * e + lr, wch = ks * 32 + lc * 8;
+                    const bool wok = u < nblocks && wch < b && wrow < d;
+                    wa[q][e] = wok ? load_frag_once(Wd + ((size_t)g * d + wrow) * b + wch) : zero_frag();
                     hb[q][e] = (tok_uses && tok_ok) ? load_frag(hbuf + ((size_t)g * 16 + ln) * b + ch) : zero_frag();
                 }
             }
 #pragma unroll
-            for (int q = 0; q < DN_UB; ++q)
-#pragma unroll
-                for (int e = 0; e < 2; ++e)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[q][e], hb[q][e], acc, 0, 0, 0);
+            for (int q = 0; q < DN_UB; ++q) {
+                // lines -> fragments through the wave's tile: lane (ln, kg) reads row ln, piece 4 e + kg
+                *reinterpret_cast<bf16x8_t*>(turn + lr * FD_TROW + lc * 8) = wa[q][0];
+                *reinterpret_cast<bf16x8_t*>(turn + (8 + lr) * FD_TROW + lc * 8) = wa[q][1];
+                wave_fence_lds();
+                const bf16x8_t f0 = *reinterpret_cast<const bf16x8_t*>(turn + ln * FD_TROW + kg * 8);
+                const bf16x8_t f1 = *reinterpret_cast<const bf16x8_t*>(turn + ln * FD_TROW + 32 + kg * 8);
+                wave_fence_lds();
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hb[q][0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1, hb[q][1], acc, 0, 0, 0);
+            }
         }
     }
+    __syncthreads();                                  // every wave is done with its tile: the sums take their place
     *reinterpret_cast<f32x4_t*>(&red[wave][lane * 4]) = acc;
     __syncthreads();
     // element e = lane*4 + i is (output column 4*(lane/16)+i, token lane%16)
@@ -519,7 +536,7 @@ static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     }
     int dgrid = (a.d + 15) / 16;
     if (dgrid > 256) dgrid = 256;
-    const size_t dn_lds = DN_WAVES * 256 * sizeof(float) + (size_t)a.G * (sizeof(uint32_t) + sizeof(uint16_t));
+    const size_t dn_lds = DN_WAVES * 16 * FD_TROW * sizeof(uint16_t) + (size_t)a.G * (sizeof(uint32_t) + sizeof(uint16_t));
     hipLaunchKernelGGL(ffn_down_mfma, dim3(dgrid), dim3(DN_WAVES * 64), dn_lds, s,
                        (const uint16_t*)a.Wd, a.d, a.G, a.b, hbuf, a.T, list, (uint16_t*)a.out);
     return hipGetLastError();
