@@ -36,10 +36,22 @@ constexpr int FW_ROWS = 64;                           // token rows of the hidde
 constexpr int GW_WAVES = 8, GW_THREADS = GW_WAVES * 64;
 constexpr int GW_KC = 512;                            // columns of the token rows per staged chunk
 constexpr int GW_XROW = GW_KC + 8;                    // LDS row stride in elements: 16 bytes of padding
+constexpr int GW_TROW = 72;                           // row stride of a wave's turning tile in elements (128 + 16 bytes)
 constexpr int DW_WAVES = 8;
 constexpr int DW_UB = 3;                              // blocks in flight per wave
 
 __device__ __forceinline__ bf16x8_t ldfrag(const uint16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
+__device__ __forceinline__ bf16x8_t ldfrag_once(const uint16_t* p) {       // read once, whole lines per load
+    return __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(p));
+}
+// Lanes of one wave hand data to each other through LDS without a workgroup barrier.  The hardware runs a
+// wave's LDS operations in program order; the compiler, which otherwise may treat what a thread has not
+// written itself as unchanged, is told by this fence that the other lanes' stores are to be seen.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 __device__ __forceinline__ bf16x8_t zfrag() {
     const uint4 z = make_uint4(0u, 0u, 0u, 0u);
     return *reinterpret_cast<const bf16x8_t*>(&z);
@@ -104,6 +116,7 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     __shared__ uint16_t ulist[FW_MAXG];
     __shared__ int wcount[GW_WAVES];
     __shared__ __attribute__((aligned(16))) uint16_t xs[2][TT * 16 * GW_XROW];   // token rows of one chunk, double buffered
+    __shared__ __attribute__((aligned(16))) uint16_t turns[TT < 4 ? GW_WAVES : 1][16 * GW_TROW];   // per wave: 16 weight rows x 128 bytes, padded
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, kg = lane >> 4;
 
@@ -150,8 +163,11 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     // The channels of the listed blocks form one range cut into gridDim.x equal pieces, and a workgroup's
     // piece into GW_WAVES equal pieces: wave w owns channels [w_lo, w_hi) and works through them in tiles
     // of 8 (8 gate rows + 8 up rows = the 16 columns of a matrix-core tile), all of the reduction index
-    // per tile.  Lane (ln, kg) loads row ln of the tile: channel c0 + (ln & 7) of the gate (ln < 8) or up
-    // matrix, 16 bytes at column 32 s + 8 kg of k-step s.
+    // per tile.  Weights are loaded as whole 128-byte lines with the non-temporal hint (eight lanes per row:
+    // lane (lr, lc) takes piece lc of gate row c0 + lr and of up row c0 + lr for each pair of k-steps) and
+    // turned into the two fragments of the pair through a per-wave LDS tile, as in the 16-row kernels:
+    // fragment-order loads (16 rows x 64 bytes per instruction) fetch every line twice and lose 13 % of the
+    // streaming rate.
     constexpr int KS = GW_KC / 32;                     // k-steps per chunk
     int w_lo = 0, w_hi = 0, npass = 0;
     auto set_range = [&](int nb) {
@@ -162,8 +178,13 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
         w_hi = min(f_hi, w_lo + cpw);
         npass = (cpw + 7) >> 3;                        // the same for every wave of the workgroup
     };
-    const uint16_t* rp = Wg;                           // this lane's weight row of the current tile, at column 8 kg
-    int my_g = 0, my_ch = 0;
+    // At four token tiles the registers do not hold the turning as well (spills make it slower than it is
+    // fast): that instance keeps loads in fragment order, 16 rows x 64 bytes per instruction.
+    constexpr bool LINES = TT < 4;
+    const int lr = lane >> 3, lc = lane & 7;           // as a loader: row of the half tile, 16-byte piece of the line
+    size_t wrow = 0;                                   // the loader's weight row of the current tile (same offset in Wg and Wu), at piece lc
+    const uint16_t* rp = Wg;                           // fragment order: this lane's weight row of the current tile, at column 8 kg
+    int my_g = 0, my_ch = 0;                           // the block and channel whose hidden values this lane stores
     bool my_ok = false;
     auto set_tile = [&](int c0, bool identity) {
         const int f = c0 + (ln & 7);
@@ -172,17 +193,42 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
         const int slot = fc / b;
         my_ch = fc - slot * b;
         my_g = identity ? slot : (int)ulist[slot];
-        rp = (ln < 8 ? Wg : Wu) + ((size_t)my_g * b + my_ch) * d + kg * 8;
+        if (LINES) {
+            const int fl = c0 + lr < w_hi ? c0 + lr : c0;
+            const int lslot = fl / b;
+            const int lg = identity ? lslot : (int)ulist[lslot];
+            wrow = ((size_t)lg * b + (fl - lslot * b)) * d + lc * 8;
+        } else {
+            rp = (ln < 8 ? Wg : Wu) + ((size_t)my_g * b + my_ch) * d + kg * 8;
+        }
     };
-    // The weights of a chunk, one fragment per k-step.  In a chunk that runs past the last column the k-steps
-    // beyond it read column 0 instead (in bounds) and meet the zeros staged for the token rows.
+    // The weights of a chunk as loaded: wb[2 p] the gate lines, wb[2 p + 1] the up lines of the pair of k-steps p.
+    // In a chunk that runs past the last column the pieces beyond it are read at column 0 instead (in bounds)
+    // and meet the zeros staged for the token rows.
     bf16x8_t wb[KS];
     auto w_fetch_all = [&](int chunk) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int col = chunk * GW_KC + s * 32;
-            wb[s] = ldfrag(rp + (col < d ? col : 0));
+        for (int pr = 0; pr < KS / 2; ++pr) {
+            const int col = chunk * GW_KC + pr * 64;
+            if (LINES) {
+                const size_t off = wrow + (col + lc * 8 < d ? col : -lc * 8);
+                wb[2 * pr] = ldfrag_once(Wg + off);
+                wb[2 * pr + 1] = ldfrag_once(Wu + off);
+            } else {
+                wb[2 * pr] = ldfrag(rp + (col < d ? col : 0));
+                wb[2 * pr + 1] = ldfrag(rp + (col + 32 < d ? col + 32 : 0));
+            }
         }
+    };
+    // lines -> fragments: lane (ln, kg) reads row ln (gate rows 0-7, up rows 8-15), piece 4 e + kg for k-step 2 p + e
+    uint16_t* turn = turns[TT < 4 ? wave : 0];
+    auto to_frags = [&](const bf16x8_t& gate_lines, const bf16x8_t& up_lines, bf16x8_t& f0, bf16x8_t& f1) {
+        *reinterpret_cast<bf16x8_t*>(turn + lr * GW_TROW + lc * 8) = gate_lines;
+        *reinterpret_cast<bf16x8_t*>(turn + (8 + lr) * GW_TROW + lc * 8) = up_lines;
+        wave_lds_fence();
+        f0 = *reinterpret_cast<const bf16x8_t*>(turn + ln * GW_TROW + kg * 8);
+        f1 = *reinterpret_cast<const bf16x8_t*>(turn + ln * GW_TROW + 32 + kg * 8);
+        wave_lds_fence();
     };
     // Chunks are taken in an order rotated by the workgroup's index (when all chunks are whole), so that the
     // workgroups do not all ask L2 for the same token rows at the same moment.
@@ -236,26 +282,49 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
             const int cn = chunk_of(i + 1);
             if (NEXT != 0) x_fetch(cn);
             if (busy) {
-                const uint16_t* rpn = rp + cn * GW_KC;
+                const size_t wnext = wrow + (size_t)cn * GW_KC;
                 const uint16_t* xb = &xs[buf][ln * GW_XROW + kg * 8];
                 bf16x8_t a[2][TT];
 #pragma unroll
                 for (int mt = 0; mt < TT; ++mt) a[0][mt] = *reinterpret_cast<const bf16x8_t*>(xb + mt * 16 * GW_XROW);
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    if (s + 1 < KS) {
+                for (int pr = 0; pr < KS / 2; ++pr) {
+                    bf16x8_t f[2];
+                    if (LINES) to_frags(wb[2 * pr], wb[2 * pr + 1], f[0], f[1]);
+                    else { f[0] = wb[2 * pr]; f[1] = wb[2 * pr + 1]; }
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int s = 2 * pr + e;
+                        if (s + 1 < KS) {
+#pragma unroll
+                            for (int mt = 0; mt < TT; ++mt)
+                                a[(s + 1) & 1][mt] = *reinterpret_cast<const bf16x8_t*>(xb + mt * 16 * GW_XROW + (s + 1) * 32);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int mt = 0; mt < TT; ++mt)
-                            a[(s + 1) & 1][mt] = *reinterpret_cast<const bf16x8_t*>(xb + mt * 16 * GW_XROW + (s + 1) * 32);
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s & 1][mt], f[e], acc[mt], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int mt = 0; mt < TT; ++mt)
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s & 1][mt], wb[s], acc[mt], 0, 0, 0);
-                    if (NEXT == 1) wb[s] = ldfrag(rpn + s * 32);
+                    if (NEXT == 1) {
+                        if (LINES) {
+                            wb[2 * pr] = ldfrag_once(Wg + wnext + pr * 64);
+                            wb[2 * pr + 1] = ldfrag_once(Wu + wnext + pr * 64);
+                        } else {
+                            wb[2 * pr] = ldfrag(rp + cn * GW_KC + pr * 64);
+                            wb[2 * pr + 1] = ldfrag(rp + cn * GW_KC + pr * 64 + 32);
+                        }
+                    }
                     if (NEXT == 2) {
-                        const int col = cn * GW_KC + s * 32;
-                        wb[s] = ldfrag(rp + (col < d ? col : 0));
+                        const int col = cn * GW_KC + pr * 64;
+                        if (LINES) {
+                            const size_t off = wrow + (col + lc * 8 < d ? col : -lc * 8);
+                            wb[2 * pr] = ldfrag_once(Wg + off);
+                            wb[2 * pr + 1] = ldfrag_once(Wu + off);
+                        } else {
+                            wb[2 * pr] = ldfrag(rp + (col < d ? col : 0));
+                            wb[2 * pr + 1] = ldfrag(rp + (col + 32 < d ? col + 32 : 0));
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -298,7 +367,10 @@ void ffn_down_wide(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     __shared__ uint16_t ulist[FW_MAXG];
     __shared__ uint32_t ulo[FW_MAXG], uhi[FW_MAXG];
     __shared__ float red[DW_WAVES][TT * 256];
+    __shared__ __attribute__((aligned(16))) uint16_t turns[DW_WAVES][16 * GW_TROW];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint16_t* turn = turns[wave];
+    const int lr = lane >> 3, lc = lane & 7;           // as a loader: row of the half tile, 16-byte piece of the line
     for (int i = tid; i < G; i += DW_WAVES * 64) {
         ulist[i] = (uint16_t)list_in[1 + i];
         ulo[i] = list_in[1 + FW_MAXG + i];
@@ -311,7 +383,6 @@ void ffn_down_wide(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
     __syncthreads();
     for (int tile = blockIdx.x; tile < ntiles; tile += (int)gridDim.x) {
         const int col0 = tile * 16;
-        const bool row_ok = col0 + ln < d;
         f32x4_t acc[TT];
 #pragma unroll
         for (int mt = 0; mt < TT; ++mt) acc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -328,7 +399,9 @@ void ffn_down_wide(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
                     for (int e = 0; e < 2; ++e) {
                         const bool ok = in_list && ks + e < ksteps;
                         const int ch = (ks + e) * 32 + kg * 8;
-                        wa[q][e] = (ok && row_ok) ? ldfrag(Wd + ((size_t)g * d + col0 + ln) * b + ch) : zfrag();
+                        // Weights come as whole lines, read once: load e is 64 channels of output rows 8 e .. 8 e + 7.
+                        const int wrow = col0 + 8 * e + lr, wch = ks * 32 + lc * 8;
+                        wa[q][e] = (in_list && wch < b && wrow < d) ? ldfrag_once(Wd + ((size_t)g * d + wrow) * b + wch) : zfrag();
 #pragma unroll
                         for (int mt = 0; mt < TT; ++mt) {
                             const int tok = mt * 16 + ln;
@@ -338,12 +411,21 @@ void ffn_down_wide(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
                     }
                 }
 #pragma unroll
-                for (int q = 0; q < DW_UB; ++q)
+                for (int q = 0; q < DW_UB; ++q) {
+                    // The wave's tile turns the two line loads into the fragments of the two k-steps.
+                    bf16x8_t f[2];
+                    *reinterpret_cast<bf16x8_t*>(turn + lr * GW_TROW + lc * 8) = wa[q][0];
+                    *reinterpret_cast<bf16x8_t*>(turn + (8 + lr) * GW_TROW + lc * 8) = wa[q][1];
+                    wave_lds_fence();
+                    f[0] = *reinterpret_cast<const bf16x8_t*>(turn + ln * GW_TROW + kg * 8);
+                    f[1] = *reinterpret_cast<const bf16x8_t*>(turn + ln * GW_TROW + 32 + kg * 8);
+                    wave_lds_fence();
 #pragma unroll
                     for (int e = 0; e < 2; ++e)
 #pragma unroll
                         for (int mt = 0; mt < TT; ++mt)
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[q][e], hb[q][mt][e], acc[mt], 0, 0, 0);
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[e], hb[q][mt][e], acc[mt], 0, 0, 0);
+                }
             }
         }
 #pragma unroll
