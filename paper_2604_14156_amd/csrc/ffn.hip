@@ -219,15 +219,18 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     auto kcol = [&](int s) { return (((s >> 1) * FD_WAVES + wave) * 2 + (s & 1)) * 32; };
     const int cpb = b >> 3;                           // 8-channel chunks per block
     // row lr of the item's gate rows (its up row sits at the same offset in Wu), at piece lc of a line
-    auto row_off = [&](int g, int cc) -> size_t { return ((size_t)g * b + cc * 8 + lr) * d + lc * 8; };
+    // Offsets are 32-bit element counts from the uniform bases (the host sends larger weight arrays down
+    // another path): fewer address registers, 1.3 us per call at 8 and 16 rows.
+    auto row_off = [&](int g, int cc) -> uint32_t { return (uint32_t)((g * b + cc * 8 + lr) * d + lc * 8); };
     // the two loads of pair p of an item: lines of the 8 gate rows, lines of the 8 up rows
-    auto fetch_item = [&](bf16x8_t (&dst)[NS], size_t off) {
+    auto fetch_item = [&](bf16x8_t (&dst)[NS], uint32_t off) {
 #pragma unroll
         for (int pr = 0; pr < NS / 2; ++pr) {
             const int col = (pr * FD_WAVES + wave) * 64 + lc * 8;
             const bool ok = col < d;
-            dst[2 * pr] = ok ? load_frag_once(Wg + off + (col - lc * 8)) : zero_frag();
-            dst[2 * pr + 1] = ok ? load_frag_once(Wu + off + (col - lc * 8)) : zero_frag();
+            const uint32_t at = off + (uint32_t)(col - lc * 8);
+            dst[2 * pr] = ok ? load_frag_once(Wg + at) : zero_frag();
+            dst[2 * pr + 1] = ok ? load_frag_once(Wu + at) : zero_frag();
         }
     };
     // raw lines -> fragments: pair pr's two loads are written to the wave's tile by rows and read back in
@@ -508,7 +511,7 @@ static int gateup_steps(int d) {
 
 static bool mfma_decode_ok(const FfnArgs& a) {
     return a.dtype == 1 && a.T <= 16 && a.G <= FD_MAXG && (a.d % 32) == 0 && (a.b % 32) == 0 &&
-           gateup_steps(a.d) <= 16;
+           gateup_steps(a.d) <= 16 && (long long)a.G * a.b * a.d < (1LL << 31);   // 32-bit element offsets in the gate/up kernel
 }
 
 static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
