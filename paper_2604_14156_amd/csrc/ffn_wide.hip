@@ -116,7 +116,7 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     __shared__ uint16_t ulist[FW_MAXG];
     __shared__ int wcount[GW_WAVES];
     __shared__ __attribute__((aligned(16))) uint16_t xs[2][TT * 16 * GW_XROW];   // token rows of one chunk, double buffered
-    __shared__ __attribute__((aligned(16))) uint16_t turns[TT < 4 ? GW_WAVES : 1][16 * GW_TROW];   // per wave: 16 weight rows x 128 bytes, padded
+    __shared__ __attribute__((aligned(16))) uint16_t turns[GW_WAVES][16 * GW_TROW];   // per wave: 16 weight rows x 128 bytes, padded
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, kg = lane >> 4;
 
@@ -178,12 +178,11 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
         w_hi = min(f_hi, w_lo + cpw);
         npass = (cpw + 7) >> 3;                        // the same for every wave of the workgroup
     };
-    // At four token tiles the registers do not hold the turning as well (spills make it slower than it is
-    // fast): that instance keeps loads in fragment order, 16 rows x 64 bytes per instruction.
-    constexpr bool LINES = TT < 4;
     const int lr = lane >> 3, lc = lane & 7;           // as a loader: row of the half tile, 16-byte piece of the line
-    size_t wrow = 0;                                   // the loader's weight row of the current tile (same offset in Wg and Wu), at piece lc
-    const uint16_t* rp = Wg;                           // fragment order: this lane's weight row of the current tile, at column 8 kg
+    // the loader's weight row of the current tile (same offset in Wg and Wu), at piece lc; a 32-bit element
+    // offset from the uniform bases (the host sends larger weight arrays down another path), which is what
+    // lets the instance with four token tiles keep everything in registers
+    uint32_t wrow = 0;
     int my_g = 0, my_ch = 0;                           // the block and channel whose hidden values this lane stores
     bool my_ok = false;
     auto set_tile = [&](int c0, bool identity) {
@@ -193,14 +192,10 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
         const int slot = fc / b;
         my_ch = fc - slot * b;
         my_g = identity ? slot : (int)ulist[slot];
-        if (LINES) {
-            const int fl = c0 + lr < w_hi ? c0 + lr : c0;
-            const int lslot = fl / b;
-            const int lg = identity ? lslot : (int)ulist[lslot];
-            wrow = ((size_t)lg * b + (fl - lslot * b)) * d + lc * 8;
-        } else {
-            rp = (ln < 8 ? Wg : Wu) + ((size_t)my_g * b + my_ch) * d + kg * 8;
-        }
+        const int fl = c0 + lr < w_hi ? c0 + lr : c0;
+        const int lslot = fl / b;
+        const int lg = identity ? lslot : (int)ulist[lslot];
+        wrow = (uint32_t)((lg * b + (fl - lslot * b)) * d + lc * 8);
     };
     // The weights of a chunk as loaded: wb[2 p] the gate lines, wb[2 p + 1] the up lines of the pair of k-steps p.
     // In a chunk that runs past the last column the pieces beyond it are read at column 0 instead (in bounds)
@@ -210,18 +205,13 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
 #pragma unroll
         for (int pr = 0; pr < KS / 2; ++pr) {
             const int col = chunk * GW_KC + pr * 64;
-            if (LINES) {
-                const size_t off = wrow + (col + lc * 8 < d ? col : -lc * 8);
-                wb[2 * pr] = ldfrag_once(Wg + off);
-                wb[2 * pr + 1] = ldfrag_once(Wu + off);
-            } else {
-                wb[2 * pr] = ldfrag(rp + (col < d ? col : 0));
-                wb[2 * pr + 1] = ldfrag(rp + (col + 32 < d ? col + 32 : 0));
-            }
+            const uint32_t off = wrow + (uint32_t)(col + lc * 8 < d ? col : -lc * 8);
+            wb[2 * pr] = ldfrag_once(Wg + off);
+            wb[2 * pr + 1] = ldfrag_once(Wu + off);
         }
     };
     // lines -> fragments: lane (ln, kg) reads row ln (gate rows 0-7, up rows 8-15), piece 4 e + kg for k-step 2 p + e
-    uint16_t* turn = turns[TT < 4 ? wave : 0];
+    uint16_t* turn = turns[wave];
     auto to_frags = [&](const bf16x8_t& gate_lines, const bf16x8_t& up_lines, bf16x8_t& f0, bf16x8_t& f1) {
         *reinterpret_cast<bf16x8_t*>(turn + lr * GW_TROW + lc * 8) = gate_lines;
         *reinterpret_cast<bf16x8_t*>(turn + (8 + lr) * GW_TROW + lc * 8) = up_lines;
@@ -282,7 +272,7 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
             const int cn = chunk_of(i + 1);
             if (NEXT != 0) x_fetch(cn);
             if (busy) {
-                const size_t wnext = wrow + (size_t)cn * GW_KC;
+                const uint32_t wnext = wrow + (uint32_t)(cn * GW_KC);
                 const uint16_t* xb = &xs[buf][ln * GW_XROW + kg * 8];
                 bf16x8_t a[2][TT];
 #pragma unroll
@@ -290,8 +280,7 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
 #pragma unroll
                 for (int pr = 0; pr < KS / 2; ++pr) {
                     bf16x8_t f[2];
-                    if (LINES) to_frags(wb[2 * pr], wb[2 * pr + 1], f[0], f[1]);
-                    else { f[0] = wb[2 * pr]; f[1] = wb[2 * pr + 1]; }
+                    to_frags(wb[2 * pr], wb[2 * pr + 1], f[0], f[1]);
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
                         const int s = 2 * pr + e;
@@ -307,24 +296,14 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     if (NEXT == 1) {
-                        if (LINES) {
-                            wb[2 * pr] = ldfrag_once(Wg + wnext + pr * 64);
-                            wb[2 * pr + 1] = ldfrag_once(Wu + wnext + pr * 64);
-                        } else {
-                            wb[2 * pr] = ldfrag(rp + cn * GW_KC + pr * 64);
-                            wb[2 * pr + 1] = ldfrag(rp + cn * GW_KC + pr * 64 + 32);
-                        }
+                        wb[2 * pr] = ldfrag_once(Wg + wnext + pr * 64);
+                        wb[2 * pr + 1] = ldfrag_once(Wu + wnext + pr * 64);
                     }
                     if (NEXT == 2) {
                         const int col = cn * GW_KC + pr * 64;
-                        if (LINES) {
-                            const size_t off = wrow + (col + lc * 8 < d ? col : -lc * 8);
-                            wb[2 * pr] = ldfrag_once(Wg + off);
-                            wb[2 * pr + 1] = ldfrag_once(Wu + off);
-                        } else {
-                            wb[2 * pr] = ldfrag(rp + (col < d ? col : 0));
-                            wb[2 * pr + 1] = ldfrag(rp + (col + 32 < d ? col + 32 : 0));
-                        }
+                        const uint32_t off = wrow + (uint32_t)(col + lc * 8 < d ? col : -lc * 8);
+                        wb[2 * pr] = ldfrag_once(Wg + off);
+                        wb[2 * pr + 1] = ldfrag_once(Wu + off);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -446,7 +425,7 @@ void ffn_down_wide(const uint16_t* __restrict__ Wd, int d, int G, int b, const u
 
 bool ffn_wide_ok(const FfnArgs& a) {
     return a.dtype == 1 && !a.shared && a.T > 16 && a.T <= FW_ROWS && a.G <= FW_MAXG && (a.d % 32) == 0 &&
-           (a.b % 32) == 0;
+           (a.b % 32) == 0 && (long long)a.G * a.b * a.d < (1LL << 31);   // 32-bit element offsets in the gate/up kernel
 }
 
 size_t ffn_wide_scratch_bytes(const FfnArgs& a) {
