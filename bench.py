@@ -48,9 +48,11 @@ def parse():
                     help="next-step: the sketches of step t give the supports step t+1 executes, and the recoveries of "
                          "all layers are solved in batched launches; same-step: every layer's support is recovered "
                          "just ahead of that layer's execution in the same step")
-    ap.add_argument("--recovery-stream", choices=["second", "same"], default="second",
-                    help="next-step mode: measurement and recovery on a second stream beside execution (default), or on "
-                         "the execution stream between the groups' layers (measured slower: 4.42 against 4.33 ms per step)")
+    ap.add_argument("--recovery-stream", choices=["second", "same"], default="same",
+                    help="next-step mode: measurement and recovery on the execution stream between the groups' layers "
+                         "(default: adds the kernels' own 0.18 ms to the step), or on a second stream beside execution "
+                         "(the workgroups of the recovery hold compute units the FFN kernels need: measured slower, "
+                         "the default run times both in alternation and reports them as stream_arrangements)")
     ap.add_argument("--groups", type=int, default=None,
                     help="next-step mode: number of layer groups per step (each is sketched and recovered with one launch per kind)")
     ap.add_argument("--no-verify", action="store_true",
@@ -791,6 +793,28 @@ def main():
         if args.recovery == "next-step" and not args.no_verify:
             verify = verify_last_step(ctx, st, wl, args.warmup + args.steps - 1)
         exec_only_ms = None
+        other_mode_ms = None
+        if graphs is not None and args.recovery == "next-step" and len(st.groups) >= 2:
+            # the step with measurement and recovery on the other stream arrangement, replayed the same way
+            other_fn = decode_step_next if NEXT_INLINE else decode_step_next_inline
+            og = []
+            for i in range(min(4, nsteps)):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream, capture_error_mode="thread_local"):
+                    other_fn(ctx, rctx, st, i, stream, rstream)
+                og.append(g)
+            for g in og:
+                g.replay()
+            # The step time drifts by a few per cent with the device's temperature (the first pass on an
+            # idle device is the fastest), so the two arrangements are timed in alternation and compared
+            # by their medians.
+            mine, other = [], []
+            for r in range(5):
+                mine.append(time_loop(lambda i: graphs[i % len(graphs)].replay(), 8, stream))
+                other.append(time_loop(lambda i: og[i % len(og)].replay(), 8, stream))
+            other_mode_ms = {"this_arrangement_ms": sorted(mine)[2], "other_arrangement_ms": sorted(other)[2],
+                             "how": "medians of 5 alternating passes of 8 replayed steps each"}
+            del og
         if graphs is not None and args.recovery == "next-step":
             def exec_only(i):
                 cur = i % 2
@@ -903,6 +927,10 @@ def main():
                              "measurement and recovery run on a second stream up to 4 layers ahead of execution in the same step"},
         "step_ms_spread": step_spread,
         "ms_per_step_execution_only": exec_only_ms,
+        "stream_arrangements": None if other_mode_ms is None else {
+            ("one_stream_ms" if NEXT_INLINE else "two_streams_ms"): other_mode_ms["this_arrangement_ms"],
+            ("two_streams_ms" if NEXT_INLINE else "one_stream_ms"): other_mode_ms["other_arrangement_ms"],
+            "how": other_mode_ms["how"]},
         "measurement_and_recovery_overhead": None if exec_only_ms is None else (ms_per_step - exec_only_ms) / ms_per_step,
         "serial_step_breakdown_ms": step_share,
         "ms_per_step_serial_sum": sum(step_share.values()),
