@@ -650,6 +650,17 @@ def extra_measurements(ctx, st, wl, stream, binding_mod):
                                                   support=st.S[0], margin=st.margin, want_coef=False, want_resid=False)
         time_loop(fn, nl, stream)
         res["recover_ffn_incremental_us_per_call_B%d_swaps%d" % (B, swaps)] = time_loop(fn, 2 * nl, stream) * 1e3
+    # the same exchange with the state carried from call to call: every layer keeps its own previous supports
+    # (updated in place by each call, as a decode loop would) and its own state
+    prevs = prev.unsqueeze(0).repeat(nl, 1, 1).contiguous()
+    states = [ctx.cs_inc_state(B, c.k, dev) for _ in range(nl)]
+    for swaps in (0, 2, 4, 8):
+        fn = lambda i: ctx.cs_recover_support_inc_carry(st.ffn_op[i % nl], st.ffn_dict[i % nl], c.k, st.y, prevs[i % nl], swaps,
+                                                        states[i % nl], support=prevs[i % nl], margin=st.margin,
+                                                        want_coef=False, want_resid=False)
+        time_loop(fn, 2 * nl, stream)                     # first pass builds the states, second settles the supports
+        res["recover_ffn_carried_us_per_call_B%d_swaps%d" % (B, swaps)] = time_loop(fn, 2 * nl, stream) * 1e3
+    res["recover_ffn_carried_state_age"] = int(states[0][0, 1])
     fn = lambda i: ctx.cs_sketch(st.ffn_op[i % nl], st.z[0][i % nl], st.y)
     time_loop(fn, nl, stream)
     res["sketch_ffn_us_per_call_B%d" % B] = time_loop(fn, 2 * nl, stream) * 1e3

@@ -223,6 +223,29 @@ cs_status cs_recover_support_inc(cs_ctx* ctx, const cs_op* op, const cs_dict* di
                                  int32_t* support, float* coef, float* resid_norm, float* margin);
 
 /*
+ * The same exchange (gamma = 0) with state carried from token to token, so that the cost of a
+ * token follows its drift and not the size of the support (Sec. 5: the loop runs once per token;
+ * Sec. 10, proposition on incremental token-adaptive recovery: only the changed part has to be
+ * identified).  Results are those of cs_recover_support_inc with prev_coef == NULL: what differs is
+ * how the least-squares fits are solved.  A token leaves the inverse of the Gram matrix of its
+ * support behind; the next token fits on that support with one k x k product, removes a unit or
+ * adds one with one rank-one correction of the inverse, and no factorisation is computed.
+ *   state: device, caller-owned, [B][cs_inc_state_words(k)] 32-bit words, 16-byte aligned; row i
+ *          belongs to sketch i of every call of the sequence.  Zero-fill it before the first call
+ *          (a zero header means "no state": the inverse is then built from prev_support).  The call
+ *          reads it and overwrites it with the state of the support it returns.  It is built again
+ *          from nothing when prev_support is not the set the state was left for, and every 64 calls
+ *          (rounding errors of the corrections add up from token to token).
+ * Other arguments, failure of a row (its state is then cleared) and supported shapes as for
+ * cs_recover_support_inc.
+ */
+size_t cs_inc_state_words(int k);
+cs_status cs_recover_support_inc_carry(cs_ctx* ctx, const cs_op* op, const cs_dict* dict, int k,
+                                       const float* y, int B,
+                                       const int32_t* prev_support, int swaps, uint32_t* state,
+                                       int32_t* support, float* coef, float* resid_norm, float* margin);
+
+/*
  * Block-sparse gated (SwiGLU) feed-forward layer restricted to the support
  * (masked execution of Sec. 3; block sparsity of Sec. 7):
  *   out[t] = sum_{g in S_t} Wd_g ( silu(Wg_g x_t) * (Wu_g x_t) ),  silu(u) = u/(1+exp(-u)).

@@ -17,7 +17,7 @@ CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
 EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_plan_drop", "cs_sketch", "cs_sketch_multi",
-           "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_block_ffn", "cs_block_ffn_static", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
+           "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_recover_support_inc_carry", "cs_inc_state_words", "cs_block_ffn", "cs_block_ffn_static", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
            "cs_softmax_entropy", "cs_uds_budget", "cs_stream_read")
 
 
@@ -56,6 +56,9 @@ def load_library(path=LIB_PATH):
     lib.cs_recover_support_iht.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, i32, vp, i32, vp, vp, vp, vp]
     lib.cs_recover_support_inc.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32,
                                            vp, vp, ctypes.c_float, i32, vp, vp, vp, vp]
+    lib.cs_recover_support_inc_carry.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict), i32, vp, i32,
+                                                 vp, i32, vp, vp, vp, vp, vp]
+    lib.cs_inc_state_words.argtypes = [i32]
     lib.cs_block_ffn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, i32, vp, i32, i32, vp]
     lib.cs_block_ffn_static.argtypes = lib.cs_block_ffn.argtypes
     lib.cs_head_attn.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
@@ -70,6 +73,7 @@ def load_library(path=LIB_PATH):
     for name in EXPORTS:
         if name not in ("cs_destroy", "cs_last_error"):
             getattr(lib, name).restype = ctypes.c_int       # cs_status, or the budget of cs_uds_budget
+    lib.cs_inc_state_words.restype = ctypes.c_size_t
     return lib
 
 
@@ -233,6 +237,29 @@ class Context:
         self._check(self.lib.cs_recover_support_inc(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                     _ptr(prev_support), _ptr(prev_coef), float(gamma), swaps,
                                                     _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
+        return support, coef, resid, margin
+
+    def cs_inc_state(self, B, k, device):
+        """A zero-filled state buffer for a sequence of cs_recover_support_inc_carry calls on B sketches."""
+        words = int(self.lib.cs_inc_state_words(k))
+        return torch.zeros((B, words), dtype=torch.int32, device=device)
+
+    def cs_recover_support_inc_carry(self, op, dct, k, y, prev_support, swaps, state,
+                                     support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True):
+        B = y.shape[0]
+        dev = y.device
+        self._retain(dct)
+        if support is None:
+            support = self._alloc((B, k), torch.int32, dev)
+        if coef is None and want_coef:
+            coef = self._alloc((B, k * dct.rb), torch.float32, dev)
+        if resid is None and want_resid:
+            resid = self._alloc((B,), torch.float32, dev)
+        if margin is None:
+            margin = self._alloc((B,), torch.float32, dev)
+        self._check(self.lib.cs_recover_support_inc_carry(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
+                                                          _ptr(prev_support), swaps, _ptr(state),
+                                                          _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 
     def cs_block_ffn_static(self, Wg, Wu, Wd, x, support, shared, out):

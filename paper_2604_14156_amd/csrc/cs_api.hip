@@ -475,6 +475,40 @@ cs_status cs_recover_support_inc(cs_ctx* c, const cs_op* op, const cs_dict* dict
     });
 }
 
+size_t cs_inc_state_words(int k) { return k < 1 ? 0 : recover_inc_state_words(k); }
+
+cs_status cs_recover_support_inc_carry(cs_ctx* c, const cs_op* op, const cs_dict* dict, int k,
+                                       const float* y, int B,
+                                       const int32_t* prev_support, int swaps, uint32_t* state,
+                                       int32_t* support, float* coef, float* resid_norm, float* margin) {
+    if (!c) return CS_EINVAL;
+    return guarded(c, [&]() -> cs_status {
+    cs_status st;
+    if ((st = check_recover_args(c, op, dict, k, "cs_recover_support_inc_carry")) != CS_OK) return st;
+    if (swaps < 0 || swaps > k) return fail(c, CS_EINVAL, "cs_recover_support_inc_carry: swaps=%d out of range [0, k=%d]", swaps, k);
+    if (B < 0) return fail(c, CS_EINVAL, "cs_recover_support_inc_carry: B < 0");
+    if (B == 0) return CS_OK;
+    if (!y || !support || !prev_support || !state) return fail(c, CS_EINVAL, "cs_recover_support_inc_carry: NULL buffer");
+    if (!aligned16(y) || !aligned16(support) || !aligned16(coef) || !aligned16(resid_norm) || !aligned16(margin) ||
+        !aligned16(prev_support) || !aligned16(state))
+        return fail(c, CS_EALIGN, "cs_recover_support_inc_carry: buffer not 16-byte aligned");
+    if ((st = bind_device(c)) != CS_OK) return st;
+    const Plan* plan = nullptr;
+    if ((st = find_or_build_plan(c, op, dict, &plan)) != CS_OK) return st;
+    if (!recover_inc_supported(*plan, k, c->lds_limit))
+        return fail(c, CS_EINVAL, "cs_recover_support_inc_carry: needs rb == 1, k <= 64 and G <= 512");
+    RecoverArgs a;
+    a.y = y; a.B = B; a.k = k; a.support = support; a.coef = coef; a.resid = resid_norm; a.margin = margin;
+    a.spill = nullptr; a.spill_stride = 0;
+    IncArgs q;
+    q.prev_support = prev_support; q.prev_coef = nullptr; q.gamma = 0.f; q.swaps = swaps;
+    q.state = state; q.state_stride = recover_inc_state_words(k);
+    hipError_t e = launch_recover_carry(*plan, a, q, c->lds_limit, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "cs_recover_support_inc_carry");
+    return CS_OK;
+    });
+}
+
 static cs_status block_ffn_with_scratch(cs_ctx* c, int dtype, const void* Wg, const void* Wu, const void* Wd,
                                         int d, int G, int b, const void* x, int T,
                                         const int32_t* support, int k, int shared, void* out,

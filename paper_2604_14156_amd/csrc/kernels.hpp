@@ -52,7 +52,12 @@ struct IncArgs {
     const float* prev_coef;        // [B][k] in the order of prev_support, or nullptr
     float gamma;                   // weight of the pull towards prev_coef in the first refit
     int swaps;                     // units that may leave and enter
+    uint32_t* state = nullptr;     // carried state, [B][state_stride] words (launch_recover_carry only)
+    size_t state_stride = 0;
 };
+// 32-bit words of carried state per sketch: header, age, the list of k units, the k x k inverse of their Gram matrix
+size_t recover_inc_state_words(int k);
+hipError_t launch_recover_carry(const Plan& p, const RecoverArgs& a, const IncArgs& q, int lds_limit, hipStream_t s);
 bool recover_inc_supported(const Plan& p, int k, int lds_limit);
 hipError_t launch_recover_inc(const Plan& p, const RecoverArgs& a, const IncArgs& q, int lds_limit, hipStream_t s);
 

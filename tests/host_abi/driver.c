@@ -96,6 +96,11 @@ int main(void) {
     EXPECT(cs_recover_support_inc(ctx, &op, &dct, 4, buf, 1, ibuf, NULL, -1.f, 1, ibuf, buf, buf, buf), CS_EINVAL);
     EXPECT(cs_recover_support_inc(ctx, &op, &dct, 4, buf, 1, NULL, NULL, 0.f, 1, ibuf, buf, buf, buf), CS_EINVAL);
     EXPECT(cs_recover_support_inc(ctx, &op, &dct, 4, buf, 1, ibuf, NULL, 0.f, 1, ibuf, buf, buf, buf), CS_OK);
+    EXPECT(cs_recover_support_inc_carry(ctx, &op, &dct, 4, buf, 1, ibuf, 5, (uint32_t*)ibuf, ibuf, buf, buf, buf), CS_EINVAL);
+    EXPECT(cs_recover_support_inc_carry(ctx, &op, &dct, 4, buf, 1, ibuf, 1, NULL, ibuf, buf, buf, buf), CS_EINVAL);
+    EXPECT(cs_recover_support_inc_carry(ctx, &op, &dct, 4, buf, 1, ibuf, 1, (uint32_t*)((char*)ibuf + 4), ibuf, buf, buf, buf), CS_EALIGN);
+    EXPECT(cs_recover_support_inc_carry(ctx, &op, &dct, 4, buf, 1, ibuf, 1, (uint32_t*)ibuf, ibuf, buf, buf, buf), CS_OK);
+    if (cs_inc_state_words(4) != 24 || cs_inc_state_words(0) != 0) { printf("cs_inc_state_words\n"); return 1; }
 
     /* execution calls */
     EXPECT(cs_block_ffn(ctx, 7, buf, buf, buf, 256, 16, 64, buf, 1, ibuf, 4, 0, buf), CS_EINVAL);

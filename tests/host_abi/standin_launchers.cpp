@@ -19,6 +19,8 @@ bool recover_iht_supported(const Plan& p, int k, int) { return p.rb == 1 && k <=
 hipError_t launch_recover_iht(const Plan&, const RecoverArgs&, int, int, hipStream_t) { return ok(); }
 bool recover_inc_supported(const Plan& p, int k, int) { return p.rb == 1 && k <= 64 && p.N <= 512; }
 hipError_t launch_recover_inc(const Plan&, const RecoverArgs&, const IncArgs&, int, hipStream_t) { return ok(); }
+size_t recover_inc_state_words(int k) { return (size_t)((2 + k + k * k + 3) & ~3); }
+hipError_t launch_recover_carry(const Plan&, const RecoverArgs&, const IncArgs&, int, hipStream_t) { return ok(); }
 hipError_t launch_backproject(const OpDesc&, const float*, float*, hipStream_t) { return ok(); }
 hipError_t launch_topk(const float*, int, int, int32_t*, hipStream_t) { return ok(); }
 size_t pool_rows_scratch_floats(int m, int k_tok) { return (size_t)m * ((k_tok + 63) / 64); }

@@ -14,11 +14,16 @@ SLACK = 1e-3           # below that: the oracle, preferring the GPU's units with
 RES_TOL = 1e-5
 
 
-def _check(cs, op, dct, M, Y, G, k, prev, swaps, normalised, prev_coef=None, gamma=0.0):
-    sup, coef, resid, margin = cs.cs_recover_support_inc(
-        op, dct, k, dev_f32(Y), dev_i32(prev), swaps,
-        prev_coef=None if prev_coef is None else dev_f32(prev_coef), gamma=gamma)
+def _check(cs, op, dct, M, Y, G, k, prev, swaps, normalised, prev_coef=None, gamma=0.0, state=None):
+    """state: a carried-state buffer -> the call goes through cs_recover_support_inc_carry."""
+    if state is None:
+        sup, coef, resid, margin = cs.cs_recover_support_inc(
+            op, dct, k, dev_f32(Y), dev_i32(prev), swaps,
+            prev_coef=None if prev_coef is None else dev_f32(prev_coef), gamma=gamma)
+    else:
+        sup, coef, resid, margin = cs.cs_recover_support_inc_carry(op, dct, k, dev_f32(Y), dev_i32(prev), swaps, state)
     sup, coef, resid, margin = host(sup), host(coef), host(resid), host(margin)
+    _check.last_support = sup
     exact = 0
     for t in range(Y.shape[0]):
         y = Y[t].astype(np.float64)
@@ -158,3 +163,106 @@ def test_invalid_rows_and_arguments(cs):
         cs.cs_recover_support_inc(binding.make_op(wl.GAUSS, 1, 0, 48, 128), big, 3, dev_f32(np.zeros((1, 48))),
                                   dev_i32(np.array([[0, 1, 2]])), 1)
     assert e.value.status == binding.CS_EINVAL
+
+
+# ---- the same exchange with the inverse of the support's Gram matrix carried from token to token
+
+def _drifting_sequence(seed, B, tokens, true_swaps):
+    """Planted usage whose support drifts by `true_swaps` units per token: sketches [tokens][B][m]."""
+    c = wl.CFG2
+    rng = wl.rng_for(seed)
+    pi, psi = wl.make_profiles(rng, c.G, c.b)
+    _, S = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
+    op = binding.make_op(c.ens, seed, 6, c.m, c.n)
+    psi_dev = dev_f32(psi)
+    dct = binding.make_dict(psi_dev, c.G, c.b, 1)
+    M = oracle.effective_matrix(c.ens, seed, 6, c.m, c.n, c.G, c.b, 1, psi)
+    first = np.stack([rng.permutation(S[t]) for t in range(B)]).astype(np.int32)
+    Ys = []
+    for _ in range(tokens):
+        S = wl.drift_supports(rng, S, c.G, true_swaps)
+        z = wl.plant_usage_on(rng, pi, S, c.amp, c.bg)
+        Ys.append(oracle.sketch(c.ens, seed, 6, c.m, z).astype(np.float32))
+    return c, op, dct, psi_dev, M, first, Ys
+
+
+@pytest.mark.parametrize("swaps,true_swaps", [(0, 0), (2, 2), (5, 3)])
+def test_carried_state_over_a_drifting_sequence(cs, swaps, true_swaps):
+    """Every token starts from the support the previous call returned and from the state it left; every
+    call is compared with the oracle's exchange from that same previous support."""
+    B, tokens = 3, 5
+    c, op, dct, psi_dev, M, prev, Ys = _drifting_sequence(4600 + swaps, B, tokens, true_swaps)
+    cs.cs_plan(op, dct, psi_dev)
+    state = cs.cs_inc_state(B, c.k, "cuda:0")
+    exact = 0
+    for t in range(tokens):
+        exact += _check(cs, op, dct, M, Ys[t], c.G, c.k, prev, swaps, True, state=state)
+        plain = host(cs.cs_recover_support_inc(op, dct, c.k, dev_f32(Ys[t]), dev_i32(prev), swaps)[0])
+        prev = _check.last_support.copy()
+        if exact == (t + 1) * B:                 # clear decisions: the two kernels agree unit for unit
+            assert np.array_equal(plain, prev)
+    assert exact >= B * tokens - 2
+    hdr = host(state)[:, :2]
+    assert np.all(hdr[:, 0] == (0x43530000 | c.k)) and np.all(hdr[:, 1] == tokens)
+
+
+def test_carried_state_is_rebuilt_when_it_does_not_fit_and_when_it_is_old(cs):
+    B = 2
+    c, op, dct, psi_dev, M, prev, Ys = _drifting_sequence(4700, B, 70, 1)
+    cs.cs_plan(op, dct, psi_dev)
+    state = cs.cs_inc_state(B, c.k, "cuda:0")
+    ages = []
+    for t in range(70):
+        sup = cs.cs_recover_support_inc_carry(op, dct, c.k, dev_f32(Ys[t]), dev_i32(prev), 1, state)[0]
+        plain = cs.cs_recover_support_inc(op, dct, c.k, dev_f32(Ys[t]), dev_i32(prev), 1)[0]
+        if t % 10 == 9 or t >= 63:               # the oracle on a sample of the tokens, around the rebuild
+            _check(cs, op, dct, M, Ys[t], c.G, c.k, prev, 1, True, state=state.clone())
+        assert np.array_equal(host(sup), host(plain)), t
+        prev = host(sup)
+        ages.append(int(host(state)[0, 1]))
+    assert ages[:64] == list(range(1, 65)) and ages[64] == 1      # built again after 64 tokens
+    # a previous support the state was not left for: the state is ignored and replaced
+    other = np.stack([np.sort(wl.rng_for(1).permutation(c.G)[:c.k]) for _ in range(B)]).astype(np.int32)
+    got = cs.cs_recover_support_inc_carry(op, dct, c.k, dev_f32(Ys[0]), dev_i32(other), 3, state)
+    want = cs.cs_recover_support_inc(op, dct, c.k, dev_f32(Ys[0]), dev_i32(other), 3)
+    assert np.array_equal(host(got[0]), host(want[0]))
+    assert np.allclose(host(got[2]), host(want[2]), rtol=0, atol=RES_TOL * np.linalg.norm(Ys[0], axis=1).max())
+    assert np.all(host(state)[:, 1] == 1)
+
+
+def test_carried_state_full_budget_heads_and_failed_rows(cs):
+    # swaps == k: nothing of the state is used, the result is recovery from nothing
+    B = 3
+    c, op, dct, psi_dev, M, prev, Ys = _drifting_sequence(4800, B, 2, 2)
+    cs.cs_plan(op, dct, psi_dev)
+    state = cs.cs_inc_state(B, c.k, "cuda:0")
+    cs.cs_recover_support_inc_carry(op, dct, c.k, dev_f32(Ys[0]), dev_i32(prev), 2, state)
+    ref = cs.cs_recover_support(op, dct, c.k, dev_f32(Ys[1]))
+    got = cs.cs_recover_support_inc_carry(op, dct, c.k, dev_f32(Ys[1]), dev_i32(prev), c.k, state)
+    assert np.array_equal(host(got[0]), host(ref[0]))
+    # a failed row clears its state and leaves the other rows alone
+    bad = host(got[0]).copy()
+    bad[1, 3] = bad[1, 4]
+    sup, coef, resid, margin = cs.cs_recover_support_inc_carry(op, dct, c.k, dev_f32(Ys[1]), dev_i32(bad), 1, state)
+    assert np.all(host(sup)[1] == -1) and np.isnan(host(resid)[1]) and host(state)[1, 0] == 0
+    assert host(state)[0, 0] == (0x43530000 | c.k) and np.isfinite(host(resid)[0])
+    with pytest.raises(binding.CsError) as e:
+        cs.cs_recover_support_inc_carry(op, dct, c.k, dev_f32(Ys[1]), dev_i32(prev), 1, None)
+    assert e.value.status == binding.CS_EINVAL
+    # identity dictionary (head selection), raw scores
+    hs = wl.CFG3_HEADS
+    rng = wl.rng_for(4810)
+    _, S = wl.plant_head_usage(rng, hs, 4)
+    hop = binding.make_op(hs.ens, 4810, 3, hs.m, hs.H)
+    hd = binding.make_dict(None, hs.H, 1, 1)
+    Mh = oracle.effective_matrix(hs.ens, 4810, 3, hs.m, hs.H, hs.H, 1, 1, None)
+    hstate = cs.cs_inc_state(4, hs.kh, "cuda:0")
+    prevh = S.astype(np.int32)
+    for t in range(3):
+        S = wl.drift_supports(rng, S, hs.H, 2)
+        u = hs.bg * rng.standard_normal((4, hs.H))
+        for i in range(4):
+            u[i, S[i]] += rng.standard_normal(hs.kh)
+        Y = oracle.sketch(hs.ens, 4810, 3, hs.m, u.astype(np.float32)).astype(np.float32)
+        _check(cs, hop, hd, Mh, Y, hs.H, hs.kh, prevh, 2, False, state=hstate)
+        prevh = _check.last_support.copy()
