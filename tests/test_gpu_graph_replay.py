@@ -216,5 +216,33 @@ def test_next_step_graph_with_batched_recovery_replays_match_eager():
             ctx.cs_recover_support_multi(fop, fdict, c.k, Y, S[1], None, None, mg[1], want_coef=False, want_resid=False)
             torch.cuda.synchronize()
             assert torch.equal(S[1], S0_ref)
+
+        # the benchmark's default arrangement: everything on the execution stream, a group measured and
+        # recovered (into the generation the next step reads) right after its last layer
+        def step_one_stream():
+            for l0, l1 in ((0, cut), (cut, layers)):
+                for l in range(l0, l1):
+                    run_layer(l)
+                sketch_rows(ctx, l0, l1)
+                recover_rows(ctx, 1, l0, l1)
+
+        step_one_stream()
+        ref1 = [t.clone() for t in [S[1], Hh[1], Y, Yh] + o + out]
+        torch.cuda.synchronize()
+        assert torch.equal(ref1[0], S0_ref) and torch.equal(ref1[1], H0_ref)
+        g1 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g1, stream=s_exec, capture_error_mode="thread_local"):
+            step_one_stream()
+        for rep in range(3):
+            S[1].fill_(-7); Hh[1].fill_(-7); Y.fill_(0.5); Yh.fill_(0.5)
+            for t in o + out:
+                t.fill_(3.0)
+            torch.cuda.synchronize()
+            g1.replay()
+            torch.cuda.synchronize()
+            for a, b in zip(ref1, [S[1], Hh[1], Y, Yh] + o + out):
+                assert torch.equal(a, b), rep
+            ctx.cs_head_attn(q[0], K[0], V[0], Hh[0][0], o[0])              # eager work between the replays
+            torch.cuda.synchronize()
     ctx.close()
     rctx.close()
