@@ -97,6 +97,19 @@ const char* cs_last_error(const cs_ctx* ctx);
 cs_status cs_set_stream(cs_ctx* ctx, void* hip_stream);
 
 /*
+ * What the caller knows about the union of the per-row supports of the cs_block_ffn calls to come
+ * (token-adaptive decode, Sec. 5: rows of a batch may share most of their units or none).  With 2 to 64 rows
+ * the first weights are requested at kernel entry, before the supports have been read, for the blocks a
+ * dense union implies; if the union turns out sparse those loads are wasted (results are the same).
+ *   CS_UNION_AUTO   (default) dense is assumed when the rows list at least 2 G entries (4 G above 16 rows)
+ *   CS_UNION_DENSE  the rows' supports are independent enough to cover nearly all G units
+ *   CS_UNION_SPARSE the rows share most of their units: wait for the list
+ * Anything else is CS_EINVAL.  The hint stays until it is set again.
+ */
+enum { CS_UNION_AUTO = 0, CS_UNION_DENSE = 1, CS_UNION_SPARSE = 2 };
+cs_status cs_set_union_hint(cs_ctx* ctx, int hint);
+
+/*
  * Build and cache the plan of (op, dict): the effective matrix M = Phi Psi, its
  * column Gram matrix and the per-unit score weights (Sec. 9: M_t = A_t Psi, and
  * the normalised columns used in the coherence definition).  Allocates device

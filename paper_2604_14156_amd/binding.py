@@ -16,7 +16,7 @@ CS_OK, CS_EINVAL, CS_EALIGN, CS_EILLPOSED, CS_ENOMEM, CS_EHIP = 0, -1, -2, -3, -
 CS_GAUSS, CS_RADEMACHER, CS_SRHT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
 
-EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_plan", "cs_plan_drop", "cs_sketch", "cs_sketch_multi",
+EXPORTS = ("cs_create", "cs_destroy", "cs_last_error", "cs_set_stream", "cs_set_union_hint", "cs_plan", "cs_plan_drop", "cs_sketch", "cs_sketch_multi",
            "cs_recover_support", "cs_recover_support_multi", "cs_recover_support_iht", "cs_recover_support_inc", "cs_recover_support_inc_carry", "cs_inc_state_words", "cs_block_ffn", "cs_block_ffn_static", "cs_head_attn", "cs_joint_select", "cs_joint_select_coupled", "cs_gather_rows",
            "cs_softmax_entropy", "cs_uds_budget", "cs_stream_read")
 
@@ -47,6 +47,7 @@ def load_library(path=LIB_PATH):
     lib.cs_last_error.argtypes = [vp]
     lib.cs_last_error.restype = ctypes.c_char_p
     lib.cs_set_stream.argtypes = [vp, vp]
+    lib.cs_set_union_hint.argtypes = [vp, i32]
     lib.cs_plan.argtypes = [vp, ctypes.POINTER(CsOp), ctypes.POINTER(CsDict)]
     lib.cs_plan_drop.argtypes = lib.cs_plan.argtypes
     lib.cs_sketch.argtypes = [vp, ctypes.POINTER(CsOp), vp, i32, vp]
@@ -129,6 +130,10 @@ class Context:
 
     def set_stream(self, stream):
         self._check(self.lib.cs_set_stream(self._h, None if stream is None else ctypes.c_void_p(stream.cuda_stream)))
+
+    def cs_set_union_hint(self, hint):
+        """0 auto, 1 the rows' supports cover nearly all units, 2 they share most of their units."""
+        self._check(self.lib.cs_set_union_hint(self._h, int(hint)))
 
     # -- the calls of the C ABI, same names ---------------------------------
     def _retain(self, dct, psi=None):

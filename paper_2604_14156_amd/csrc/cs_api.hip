@@ -24,6 +24,7 @@ struct cs_ctx {
     void* scratch;
     size_t scratch_bytes;
     int lds_limit;
+    int union_hint = 0;
     std::vector<PlanEntry> plans;
     // device arrays of plans for calls that serve several operators at once, keyed by the plans' atom
     // buffers (one buffer per plan for the lifetime of the context)
@@ -246,6 +247,14 @@ const char* cs_last_error(const cs_ctx* c) { return c ? c->err : "no context"; }
 cs_status cs_set_stream(cs_ctx* c, void* hip_stream) {
     if (!c) return CS_EINVAL;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    return CS_OK;
+}
+
+cs_status cs_set_union_hint(cs_ctx* c, int hint) {
+    if (!c) return CS_EINVAL;
+    if (hint != CS_UNION_AUTO && hint != CS_UNION_DENSE && hint != CS_UNION_SPARSE)
+        return fail(c, CS_EINVAL, "cs_set_union_hint: unknown hint %d", hint);
+    c->union_hint = hint;
     return CS_OK;
 }
 
@@ -534,6 +543,7 @@ static cs_status block_ffn_with_scratch(cs_ctx* c, int dtype, const void* Wg, co
     a.dtype = dtype; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.d = d; a.G = G; a.b = b;
     a.x = x; a.T = T; a.support = support; a.k = k; a.shared = shared ? 1 : 0; a.out = out;
     a.scratch = work; a.scratch_bytes = work_bytes;
+    a.union_hint = c->union_hint;
     const size_t need = ffn_scratch_bytes(a);
     if (need > work_bytes)
         return fail(c, CS_ENOMEM, "cs_block_ffn: needs %zu bytes of scratch, %s has %zu", need, work_name, work_bytes);

@@ -525,7 +525,8 @@ static hipError_t run_mfma_decode(const FfnArgs& a, hipStream_t s) {
     if (grid > 256) grid = 256;                       // one workgroup of 16 waves per compute unit
     if (grid < 1) grid = 1;
     // a dense union is expected when the tokens list at least twice as many entries as there are blocks
-    const int direct = (!a.shared && a.T > 1 && (long)a.T * a.k >= 2L * a.G) ? 1 : 0;
+    const bool guess = a.union_hint == 1 || (a.union_hint == 0 && (long)a.T * a.k >= 2L * a.G);
+    const int direct = (!a.shared && a.T > 1 && guess) ? 1 : 0;
     if (a.T == 1) {
         const long units = (long)a.k * a.b;
         hipLaunchKernelGGL(ffn_gateup_gemv, dim3((unsigned)((units + GV_WAVES - 1) / GV_WAVES)), dim3(GV_WAVES * 64), 0, s,

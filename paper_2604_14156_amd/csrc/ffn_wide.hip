@@ -437,7 +437,8 @@ hipError_t launch_ffn_wide(const FfnArgs& a, hipStream_t s) {
     uint32_t* list = reinterpret_cast<uint32_t*>(hbuf + (size_t)a.G * FW_ROWS * a.b);
     const int union_max = a.T * a.k < a.G ? a.T * a.k : a.G;
     long grid = (long)union_max * a.b / 8;             // at least one tile of 8 channels per workgroup
-    const int dense = (long)a.T * a.k >= 4L * a.G;     // every block is then listed by some row, almost surely
+    // every block is then listed by some row, almost surely (or the caller has said so, or the opposite)
+    const int dense = a.union_hint == 1 || (a.union_hint == 0 && (long)a.T * a.k >= 4L * a.G);
     if (grid > 256) grid = 256;
     if (grid < 1) grid = 1;
     int dgrid = (a.d + 15) / 16;

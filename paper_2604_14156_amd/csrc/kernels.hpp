@@ -90,6 +90,7 @@ struct FfnArgs {
     const void* x; int T; const int32_t* support; int k; int shared;
     void* out;
     void* scratch; size_t scratch_bytes;
+    int union_hint = 0;   // 0: guess from T, k, G whether the rows' supports cover all units; 1: they do; 2: they do not
 };
 size_t ffn_scratch_bytes(const FfnArgs& a);
 // many-row path on the matrix cores (ffn_gemm.hip)

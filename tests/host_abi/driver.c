@@ -148,6 +148,10 @@ int main(void) {
     EXPECT(cs_stream_read(ctx, buf, 4096, (uint32_t*)ibuf), CS_OK);
     EXPECT(cs_set_stream(ctx, NULL), CS_OK);
     EXPECT(cs_set_stream(NULL, NULL), CS_EINVAL);
+    EXPECT(cs_set_union_hint(ctx, CS_UNION_DENSE), CS_OK);
+    EXPECT(cs_set_union_hint(ctx, 3), CS_EINVAL);
+    EXPECT(cs_set_union_hint(NULL, CS_UNION_AUTO), CS_EINVAL);
+    EXPECT(cs_set_union_hint(ctx, CS_UNION_AUTO), CS_OK);
 
     /* many plans: the cache grows and moves; everything is released at the end */
     for (uint32_t s = 100; s < 140; ++s) {

@@ -248,6 +248,36 @@ def test_ffn_decode_dense_union_guess(cs, case):
         check_row(out[t], want[t], "bf16", (case, t))
 
 
+@pytest.mark.parametrize("T,G,k", [(16, 40, 6), (6, 40, 4), (40, 24, 5)])
+def test_ffn_union_hint_changes_no_result(cs, T, G, k):
+    """The caller's word on the union of the supports only moves loads: with the hint set either way, on
+    supports for which it is right and on supports for which it is wrong, the output is that of the default,
+    bit for bit, and within tolerance of the oracle."""
+    b, d = 64, 512
+    rng = wl.rng_for(1800 + T)
+    Wg, Wu, Wd = wl.make_ffn_weights(rng, G, b, d, 0.05, "bf16")
+    x = wl.make_tokens(rng, T, d, "bf16")
+    spread = wl.random_supports(rng, G, k, T)
+    shared = np.tile(wl.random_supports(rng, G, k, 1)[0], (T, 1)).astype(np.int32)
+    args = [dev_bf16(Wg), dev_bf16(Wu), dev_bf16(Wd), dev_bf16(x)]
+    try:
+        for sup in (spread, shared):
+            cs.cs_set_union_hint(0)
+            ref = host(cs.cs_block_ffn(*args, dev_i32(sup), False))
+            want = oracle.block_ffn(Wg, Wu, Wd, x, sup)
+            for t in range(T):
+                check_row(ref[t], want[t], "bf16", t)
+            for hint in (1, 2):
+                cs.cs_set_union_hint(hint)
+                got = host(cs.cs_block_ffn(*args, dev_i32(sup), False))
+                assert np.array_equal(got, ref), hint          # bf16 values widened exactly: equal floats = equal bits
+        with pytest.raises(binding.CsError) as e:
+            cs.cs_set_union_hint(7)
+        assert e.value.status == binding.CS_EINVAL
+    finally:
+        cs.cs_set_union_hint(0)
+
+
 def _full_size_ffn(cs, B, seed):
     """Decode shape at full size: weights drawn on the device, every token against the oracle."""
     c = wl.CFG2
