@@ -30,7 +30,11 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps before the timed ones.  The first 60-80 steps after the set-up run 2-3 %% slower "
+                         "(the device comes out of an idle gap during graph capture), then the step time is flat for "
+                         "seconds; only the last 3 warm-up steps have inputs of their own, the ones before them cycle "
+                         "through the steps' graphs")
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -143,23 +147,28 @@ class DecodeState:
         self.H_gen = [torch.zeros((layers, B, hs.kh), dtype=torch.int32, device=dev) for _ in range(2)]
         self.margin_all = torch.empty((layers, B), device=dev)
         self.marginh_all = torch.empty((layers, B), device=dev)
-        # layer groups of the batched recovery (ctypes arrays of operators and dictionaries per group)
-        self.groups = []
-        ngroups = min(NEXT_GROUPS, layers)
+        self.groups = self.make_groups(binding, NEXT_GROUPS)
+
+    def make_groups(self, binding, ngroups):
+        """Layer groups of the batched measurement and recovery (ctypes arrays of operators and dictionaries per group)."""
+        layers = self.layers
+        groups = []
+        ngroups = min(max(1, ngroups), layers)
         per = (layers + ngroups - 1) // ngroups
         for g0 in range(0, layers, per):
             ls = list(range(g0, min(layers, g0 + per)))
-            self.groups.append({
+            groups.append({
                 "layers": ls,
                 "ffn_ops": (binding.CsOp * len(ls))(*[self.ffn_op[l] for l in ls]),
                 "ffn_dicts": (binding.CsDict * len(ls))(*[self.ffn_dict[l] for l in ls]),
                 "head_ops": (binding.CsOp * len(ls))(*[self.head_op[l] for l in ls]),
                 "head_dicts": (binding.CsDict * len(ls))(*[self.head_dict for _ in ls]),
             })
+        return groups
 
 
 SOLVER = {"name": "omp", "iters": 12}
-NEXT_GROUPS = 2     # layer groups per step: each is sketched and recovered with one launch per kind
+NEXT_GROUPS = 1     # layer groups per step: each is sketched and recovered with one launch per kind
 
 
 def recover_ffn(cx, st, l, y, S, margin):
@@ -713,15 +722,23 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU and the HIP library; there is no CPU fallback")
     SOLVER["name"], SOLVER["iters"] = args.solver, args.iht_iters
+    global NEXT_GROUPS
     if args.groups is not None:
-        global NEXT_GROUPS
         NEXT_GROUPS = max(1, args.groups)
+    else:
+        # on one stream a single group has the fewest launches; beside a second stream the last group's work is
+        # carried into the next step, which needs two
+        NEXT_GROUPS = 1 if args.recovery_stream == "same" else 2
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
     rstream = torch.cuda.Stream()
     ctx = binding.Context(device=0, stream=stream)
     rctx = binding.Context(device=0, stream=rstream)
-    nsteps = args.steps + args.warmup
+    # steps with inputs of their own: the timed ones and the last few warm-up steps before them; earlier
+    # warm-up steps replay those steps' graphs in turn (every step reads one generation of supports and writes
+    # the other, whatever ran before it)
+    own_warm = min(args.warmup, 3)
+    nsteps = args.steps + own_warm
     if args.prefill_pass:
         with torch.cuda.stream(stream):
             res = prefill_measurements(ctx, wl, stream, binding)
@@ -779,13 +796,15 @@ def main():
             else:
                 step_fn(ctx, rctx, st, i, stream, rstream)
 
-        for i in range(args.warmup):
+        for i in range(args.warmup - own_warm):
+            run(i % nsteps)
+        for i in range(own_warm):
             run(i)
         torch.cuda.synchronize()
         # --- timed region: exactly `steps` steps
         t0 = time.perf_counter()
         for i in range(args.steps):
-            run(args.warmup + i)
+            run(own_warm + i)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         # --- after the timed region: the same steps once more with an event between them (spread of
@@ -794,7 +813,7 @@ def main():
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         marks[0].record(stream)
         for i in range(args.steps):
-            run(args.warmup + i)
+            run(own_warm + i)
             marks[i + 1].record(stream)
         torch.cuda.synchronize()
         step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
@@ -802,18 +821,27 @@ def main():
         step_spread = {"p10": pick(0.1), "p50": pick(0.5), "p90": pick(0.9), "note": "one event per step; the timed region has none"}
         verify = None
         if args.recovery == "next-step" and not args.no_verify:
-            verify = verify_last_step(ctx, st, wl, args.warmup + args.steps - 1)
+            verify = verify_last_step(ctx, st, wl, own_warm + args.steps - 1)
         exec_only_ms = None
         other_mode_ms = None
-        if graphs is not None and args.recovery == "next-step" and len(st.groups) >= 2:
-            # the step with measurement and recovery on the other stream arrangement, replayed the same way
+        if graphs is not None and args.recovery == "next-step":
+            # the step with measurement and recovery on the other stream arrangement (with the number of groups
+            # that suits it), replayed the same way
             other_fn = decode_step_next if NEXT_INLINE else decode_step_next_inline
+            main_groups = st.groups
+            other_groups = st.make_groups(binding, 2 if NEXT_INLINE else 1)
+            for grp in other_groups:                      # device tables of both contexts, outside the capture
+                recover_group(ctx, st, grp, 1)
+                recover_group(rctx, st, grp, 1)
+            torch.cuda.synchronize()
+            st.groups = other_groups
             og = []
             for i in range(min(4, nsteps)):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=stream, capture_error_mode="thread_local"):
                     other_fn(ctx, rctx, st, i, stream, rstream)
                 og.append(g)
+            st.groups = main_groups
             for g in og:
                 g.replay()
             # The step time drifts by a few per cent with the device's temperature (the first pass on an
@@ -824,6 +852,7 @@ def main():
                 mine.append(time_loop(lambda i: graphs[i % len(graphs)].replay(), 8, stream))
                 other.append(time_loop(lambda i: og[i % len(og)].replay(), 8, stream))
             other_mode_ms = {"this_arrangement_ms": sorted(mine)[2], "other_arrangement_ms": sorted(other)[2],
+                             "this_groups": len(main_groups), "other_groups": len(other_groups),
                              "how": "medians of 5 alternating passes of 8 replayed steps each"}
             del og
         if graphs is not None and args.recovery == "next-step":
@@ -941,6 +970,8 @@ def main():
         "stream_arrangements": None if other_mode_ms is None else {
             ("one_stream_ms" if NEXT_INLINE else "two_streams_ms"): other_mode_ms["this_arrangement_ms"],
             ("two_streams_ms" if NEXT_INLINE else "one_stream_ms"): other_mode_ms["other_arrangement_ms"],
+            ("one_stream_groups" if NEXT_INLINE else "two_streams_groups"): other_mode_ms["this_groups"],
+            ("two_streams_groups" if NEXT_INLINE else "one_stream_groups"): other_mode_ms["other_groups"],
             "how": other_mode_ms["how"]},
         "measurement_and_recovery_overhead": None if exec_only_ms is None else (ms_per_step - exec_only_ms) / ms_per_step,
         "serial_step_breakdown_ms": step_share,

@@ -21,7 +21,7 @@ def test_bench_options_parse():
     try:
         sys.argv = ["bench.py"]
         a = bench.parse()
-        assert (a.gpus, a.steps, a.warmup, a.layers, a.batch) == (1, 20, 3, 32, 16)
+        assert (a.gpus, a.steps, a.warmup, a.layers, a.batch) == (1, 20, 100, 32, 16)
         assert a.recovery == "next-step" and a.groups is None and not a.no_verify
         sys.argv = ["bench.py", "--gpus", "1", "--steps", "5", "--warmup", "2", "--recovery", "same-step", "--groups", "4"]
         a = bench.parse()
