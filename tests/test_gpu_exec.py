@@ -106,11 +106,13 @@ def test_ffn_prefill_shape_full_size(cs):
     assert float(norms.min()) > 0.5 * ref and float(norms.max()) < 2.0 * ref
 
 
-@pytest.mark.parametrize("T,shared,G,k,d", [(2100, True, 40, 35, 4160), (2052, False, 40, 9, 4128), (1300, True, 64, 63, 2080)])
+@pytest.mark.parametrize("T,shared,G,k,d", [(2100, True, 40, 35, 4160), (2052, False, 40, 9, 4128), (1300, True, 64, 63, 2080),
+                                            (1100, True, 30, 7, 4000), (1290, False, 24, 5, 4064)])
 def test_ffn_wide_tiles_ragged_shapes(cs, T, shared, G, k, d):
     """Shapes large enough for the 256 x 256 tiles on at least one of the two products, with a ragged last
     row tile, an odd number of blocks, an output width that is no multiple of the tile, and (second case)
-    per-row supports; oracle on sampled rows, among them the last ones."""
+    per-row supports; the last two have too few 256 x 256 tiles for the second product and take 128 x 128
+    ones there, again with ragged rows and columns; oracle on sampled rows, among them the last ones."""
     gen = torch.Generator(device="cuda:0").manual_seed(T + d)
     b = 64
     Wg, Wu = (torch.randn((G, b, d), generator=gen, device="cuda:0").mul_(0.03).to(torch.bfloat16) for _ in range(2))
@@ -120,7 +122,7 @@ def test_ffn_wide_tiles_ragged_shapes(cs, T, shared, G, k, d):
     sup = wl.random_supports(rng, G, k, 1)[0] if shared else wl.random_supports(rng, G, k, T)
     out = cs.cs_block_ffn(Wg, Wu, Wd, x, dev_i32(sup), shared)
     torch.cuda.synchronize()
-    rows = [0, 255, 256, T // 2, T - 37, T - 2, T - 1]
+    rows = [0, 127, 128, 255, 256, T // 2, T - 37, T - 2, T - 1]
     hWg, hWu, hWd = host(Wg), host(Wu), host(Wd)
     got = host(out[rows])
     for i, r in enumerate(rows):
