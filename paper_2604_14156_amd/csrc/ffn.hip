@@ -416,17 +416,16 @@ void ffn_gateup_gemv(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     if (lane == 0) hbuf[(size_t)g * 16 * b + c] = f32_to_bf16(sg / (1.0f + __expf(-sg)) * su);
 }
 
-// Down projection.  8 waves per workgroup and at most 128 registers per lane, so that two
-// workgroups fit on a compute unit when some units are busy with another stream's kernels.
+// Down projection.  8 waves per workgroup, 6 blocks in flight per wave (other splits of the same number of
+// loads in flight, 16 x 3 or 4 x 12, are within a microsecond), at most 128 registers per lane.
 constexpr int DN_WAVES = 8;
 constexpr int DN_UB = 6;                              // blocks in flight per wave
 
 __global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
                    int T, const uint32_t* __restrict__ list_in, uint16_t* __restrict__ out) {
-    // LDS sized by the number of blocks (8 KB + 6 bytes per block), not by the largest list the path
-    // accepts: at the 7B shape that is 9.2 KB, which still fits on a compute unit beside a recovery
-    // workgroup of another stream (147 KB), so the kernel does not have to wait for that unit
+    // LDS sized by the number of blocks (18 KB of tiles + 6 bytes per block), not by the largest list the
+    // path accepts
     extern __shared__ __attribute__((aligned(16))) unsigned char dn_lds[];
     // the waves' turning tiles (16 rows x 144 bytes each: weights arrive as whole lines, the matrix cores
     // want fragments, as in the gate/up kernel) share their memory with the partial sums, which are
