@@ -266,3 +266,27 @@ def test_carried_state_full_budget_heads_and_failed_rows(cs):
         Y = oracle.sketch(hs.ens, 4810, 3, hs.m, u.astype(np.float32)).astype(np.float32)
         _check(cs, hop, hd, Mh, Y, hs.H, hs.kh, prevh, 2, False, state=hstate)
         prevh = _check.last_support.copy()
+
+
+@pytest.mark.parametrize("G,k,m,swaps", [(128, 64, 200, 5), (128, 64, 200, 64), (9, 1, 8, 1), (9, 3, 8, 0), (70, 33, 96, 33), (512, 20, 120, 4)])
+def test_carried_state_edge_shapes(cs, G, k, m, swaps):
+    """The largest list the solver takes (k = 64: the padded copy of the inverse is full), a list of one,
+    an odd size, the largest dictionary; identity dictionary, raw scores; three tokens in a row."""
+    B = 3
+    seed = 4900 + G + k
+    rng = wl.rng_for(seed)
+    op = binding.make_op(wl.GAUSS, seed, 2, m, G)
+    dct = binding.make_dict(None, G, 1, 1)
+    M = oracle.effective_matrix(wl.GAUSS, seed, 2, m, G, G, 1, 1, None)
+    S = np.stack([np.sort(rng.permutation(G)[:k]) for _ in range(B)])
+    prev = S.astype(np.int32)
+    state = cs.cs_inc_state(B, k, "cuda:0")
+    assert state.shape[1] == (2 + k + k * k + 3) // 4 * 4
+    for t in range(3):
+        S = wl.drift_supports(rng, S, G, min(swaps, 2, G - k))
+        u = 0.01 * rng.standard_normal((B, G))
+        for i in range(B):
+            u[i, S[i]] += rng.standard_normal(k) + np.sign(rng.standard_normal(k))
+        Y = oracle.sketch(wl.GAUSS, seed, 2, m, u.astype(np.float32)).astype(np.float32)
+        _check(cs, op, dct, M, Y, G, k, prev, swaps, False, state=state)
+        prev = _check.last_support.copy()
