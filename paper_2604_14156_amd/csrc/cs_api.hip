@@ -345,7 +345,7 @@ cs_status cs_sketch_multi(cs_ctx* c, int n_ops, const cs_op* ops, const float* z
     for (int j = 0; j < n_ops; ++j) descs[(size_t)j] = make_desc(ops[j]);
     if (ops[0].ens == CS_SRHT && !sketch_srht_supported(descs[0]))
         return fail(c, CS_EINVAL, "cs_sketch_multi: the Hadamard ensemble is limited to n <= 32768 (n=%d)", ops[0].n);
-    hipError_t e = launch_sketch_multi(descs.data(), n_ops, z, B, y, c->stream);
+    hipError_t e = launch_sketch_multi(descs.data(), n_ops, z, B, y, c->stream, c->scratch, c->scratch_bytes);
     if (e != hipSuccess) return hip_fail(c, e, "cs_sketch_multi");
     return CS_OK;
     });

@@ -11,7 +11,9 @@ namespace csk {
 
 // y[B][m] = Phi z[B][n]
 hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s);
-hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int B, float* y, hipStream_t s);
+// scratch: optional workspace (device) for launches that split the columns over several workgroups per tile
+hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int B, float* y, hipStream_t s,
+                               void* scratch = nullptr, size_t scratch_bytes = 0);
 // the fast transform of the Hadamard ensemble keeps the padded vector in LDS
 bool sketch_srht_supported(const OpDesc& op);
 

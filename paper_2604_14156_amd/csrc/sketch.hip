@@ -124,6 +124,7 @@ void sketch_rademacher_kernel(OpDesc op, OpKeys keys, const float* __restrict__ 
 // as one 16-byte load for s = 0..7; component jj of load s is the B operand of multiply (s, jj), whose k
 // index kg therefore stands for column 16 s + 4 kg + jj.
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float sk_f32x4;
+typedef sk_f32x4 f32x4_acc;
 constexpr int SM_WAVES = 16;
 
 __global__ __launch_bounds__(SM_WAVES * 64)
@@ -172,6 +173,127 @@ void sketch_rademacher_mfma_kernel(OpDesc op, OpKeys keys, const float* __restri
         for (int w = 0; w < SM_WAVES; ++w) sum += red[w][tid];
         const int row = row0 + 4 * (tid >> 6) + (tid & 3), tok = t0 + ((tid >> 2) & 15);
         if (row < op.m && tok < B) y[(size_t)tok * op.m + row] = sum * op.scale;
+    }
+}
+
+// The same contraction on the bf16 matrix cores, sixteen times the rate of the fp32 ones, without
+// giving up exactness of the products: a float is the sum of three bf16 numbers (its leading eight
+// significant bits, the next eight, the last eight: z = h + m + l, every difference formed exactly), and a
+// sign is a bf16 number, so y = S h + S m + S l with every product exact and the sums in fp32 as before.
+// Splitting costs more vector instructions than the multiplies it saves unless it is shared, so here a
+// workgroup owns ALL rows of Phi for one tile of 16 tokens (wave w takes the 16-row blocks w, w + 16) and a
+// range of 128-column chunks: per chunk the 1024 threads split the 16 x 128 values once into three planes
+// in LDS (double buffered, one barrier per chunk), and every wave multiplies its sign tiles (eight signs per
+// lane and k-step packed from one byte of the row's 128 bits) with the planes by `v_mfma_f32_16x16x32_bf16`.
+// The four lanes that hold one row of a sign tile would draw the same Philox block; instead lane (row, q)
+// draws the block of the q-th chunk of a group of four, and each chunk fetches its words from the lane that
+// drew them (`ds_bpermute`).  The column ranges of a token tile are dealt to gridDim.x workgroups (as many
+// as it takes to fill the chip); their partial tiles go to a workspace and are added in a fixed order by
+// sketch_partials_kernel, which also applies the scale.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 sk_bf16x8;
+constexpr int SB_WAVES = 16;
+constexpr int SB_ROW = 136;                            // bf16 per token row of a plane: 128 + 8 (272 bytes: conflict-free 16-byte reads)
+constexpr int SB_PLANE = 16 * SB_ROW;
+constexpr int SB_MAX_SPLITS = 32;                      // column ranges per token tile
+#ifndef SB_TARGET_WGS
+#define SB_TARGET_WGS 256
+#endif
+
+template <int RBW>
+__global__ __launch_bounds__(SB_WAVES * 64)
+void sketch_rademacher_bf16_kernel(OpDesc op, OpKeys keys, const float* __restrict__ z, int B, float* __restrict__ partial) {
+    __shared__ __attribute__((aligned(16))) uint16_t planes[2][3][SB_PLANE];
+    pick_operator(op, keys);
+    z += (size_t)blockIdx.z * B * op.n;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tl = lane & 15, kg = lane >> 4;
+    const int n = op.n, m = op.m;
+    const int t0 = blockIdx.y * 16;
+    const int nchunks = (n + 127) >> 7;
+    const int c_lo = (int)((long)blockIdx.x * nchunks / gridDim.x), c_hi = (int)((long)(blockIdx.x + 1) * nchunks / gridDim.x);
+    // staging: thread (token st, column pair sp) of the chunk
+    const int st = tid >> 6, sp = tid & 63;
+    const bool st_ok = t0 + st < B;
+    const float* zrow = z + (size_t)(st_ok ? t0 + st : 0) * n + 2 * sp;
+    auto fetch = [&](int cc) -> float2 {
+        const int col = (cc << 7) + 2 * sp;                // n is a multiple of 4: a pair is all in or all out
+        return (st_ok && cc < c_hi && col < n) ? *reinterpret_cast<const float2*>(zrow + (cc << 7)) : make_float2(0.f, 0.f);
+    };
+    auto split_store = [&](float2 v, int buf) {
+        const uint32_t a0 = __float_as_uint(v.x) & 0xFFFF0000u, b0 = __float_as_uint(v.y) & 0xFFFF0000u;
+        const float ra = v.x - __uint_as_float(a0), rb = v.y - __uint_as_float(b0);
+        const uint32_t a1 = __float_as_uint(ra) & 0xFFFF0000u, b1 = __float_as_uint(rb) & 0xFFFF0000u;
+        const float sa = ra - __uint_as_float(a1), sb = rb - __uint_as_float(b1);
+        const uint32_t a2 = __float_as_uint(sa) & 0xFFFF0000u, b2 = __float_as_uint(sb) & 0xFFFF0000u;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&planes[buf][0][st * SB_ROW + 2 * sp]);
+        dst[0] = (a0 >> 16) | b0;
+        dst[SB_PLANE / 2] = (a1 >> 16) | b1;
+        dst[SB_PLANE] = (a2 >> 16) | b2;
+    };
+    f32x4_acc acc[RBW];
+    u32x4 drawn[RBW];                                  // Philox block of (row tl, chunk kg of the current group of four)
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) { acc[r] = f32x4_acc{0.f, 0.f, 0.f, 0.f}; drawn[r] = u32x4{{0u, 0u, 0u, 0u}}; }
+    float2 zreg = fetch(c_lo);
+    for (int cc = c_lo; cc < c_hi; ++cc) {
+        const int buf = (cc - c_lo) & 1;
+        split_store(zreg, buf);
+        zreg = fetch(cc + 1);
+        __syncthreads();                               // the planes of chunk cc are complete; the other buffer is free again
+        const int in_group = (cc - c_lo) & 3;
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) {
+            const int row0 = (wave + r * SB_WAVES) * 16;
+            if (row0 < m) {                            // uniform over the wave
+                if (in_group == 0) drawn[r] = rademacher_bits(op, (uint32_t)(row0 + tl), (uint32_t)(cc + kg));
+                const int src = in_group * 16 + tl;    // the lane that drew this chunk's block for row tl
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    // columns 32 ks + 8 kg + j of the chunk: bits 8 kg + j of word ks; a set bit is -1
+                    const uint32_t by = ((uint32_t)__shfl((int)drawn[r].w[ks], src) >> (kg * 8)) & 0xFFu;
+                    union { uint32_t u[4]; sk_bf16x8 v; } sg;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        sg.u[q] = 0x3F803F80u | (((by >> (2 * q)) & 1u) << 15) | (((by >> (2 * q + 1)) & 1u) << 31);
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl) {
+                        const sk_bf16x8 zb = *reinterpret_cast<const sk_bf16x8*>(&planes[buf][pl][tl * SB_ROW + ks * 32 + kg * 8]);
+                        acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sg.v, zb, acc[r], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    // element v of a lane's tile is (row 4 (lane / 16) + v, token lane % 16); partial tiles:
+    // [operator][range][token tile][16 tokens][rows, padded to 16], i.e. the layout of y
+    const int rows_pad = ((m + 15) >> 4) << 4;
+    float* pt = partial + ((((size_t)blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * 16) * rows_pad;
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) {
+        const int row0 = (wave + r * SB_WAVES) * 16;
+        if (row0 < m) *reinterpret_cast<f32x4_acc*>(pt + (size_t)tl * rows_pad + row0 + 4 * kg) = acc[r];
+    }
+}
+
+// y[operator][token][row] = scale * sum over the column ranges of the partial tiles, in the order of the ranges
+__global__ void sketch_partials_kernel(const float* __restrict__ partial, int nz, int splits, int tiles, int m, int B, float scale,
+                                       float* __restrict__ y) {
+    const int rows_pad = ((m + 15) >> 4) << 4;
+    const long total = (long)nz * B * m;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long)gridDim.x * blockDim.x) {
+        const int row = (int)(e % m);
+        const int tok = (int)((e / m) % B);
+        const int j = (int)(e / ((long)m * B));
+        const int ty = tok >> 4, tl = tok & 15;
+        // all ranges' values requested at once, added in the order of the ranges
+        float v[SB_MAX_SPLITS];
+#pragma unroll
+        for (int q = 0; q < SB_MAX_SPLITS; ++q)
+            v[q] = q < splits ? partial[((((size_t)j * splits + q) * tiles + ty) * 16 + tl) * rows_pad + row] : 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < SB_MAX_SPLITS; ++q) sum += v[q];
+        y[e] = sum * scale;
     }
 }
 
@@ -363,7 +485,8 @@ constexpr int SRHT_MAX_BITS = 15;                       // 128 KB of LDS for the
 bool sketch_srht_supported(const OpDesc& op) { return op.nbits <= SRHT_MAX_BITS; }
 
 // ops[0..n_ops): operators of one ensemble and shape; z [n_ops][B][n], y [n_ops][B][m].
-hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int B, float* y, hipStream_t s) {
+hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int B, float* y, hipStream_t s,
+                               void* scratch, size_t scratch_bytes) {
     if (B <= 0 || n_ops <= 0) return hipSuccess;
     const OpDesc& op = ops[0];
     if (op.ens == 2 && !sketch_srht_supported(op)) return hipErrorInvalidValue;
@@ -392,8 +515,23 @@ hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int
         } else if (op.ens == 1) {
             const int tgroups = (B + 7) / 8;
             const long mfma_wgs = (long)((op.m + 15) / 16) * ((B + 15) / 16) * nz;
-            if ((op.n & 3) == 0 && mfma_wgs >= 128) {
-                // enough 16 x 16 tiles to fill the chip (several operators per launch): matrix cores
+            const int tiles = (B + 15) / 16, rows_pad = ((op.m + 15) / 16) * 16, nchunks = (op.n + 127) / 128;
+            int splits = (SB_TARGET_WGS + nz * tiles - 1) / (nz * tiles);       // column ranges per token tile: fill the chip
+            splits = splits < 1 ? 1 : (splits > SB_MAX_SPLITS ? SB_MAX_SPLITS : splits);
+            if (splits > nchunks) splits = nchunks;
+            const size_t part_bytes = (size_t)nz * splits * tiles * rows_pad * 16 * sizeof(float);
+            if ((op.n & 3) == 0 && mfma_wgs >= 128 && op.m <= 512 && scratch && part_bytes <= scratch_bytes) {
+                // enough 16 x 16 tiles to fill the chip (several operators per launch): bf16 matrix cores on the
+                // three-way split of z, partial tiles per column range in the workspace, then their sum
+                float* part = static_cast<float*>(scratch);
+                const dim3 grid(splits, tiles, nz);
+                if (op.m <= 256) hipLaunchKernelGGL((sketch_rademacher_bf16_kernel<1>), grid, dim3(SB_WAVES * 64), 0, s, op, keys, zj, B, part);
+                else hipLaunchKernelGGL((sketch_rademacher_bf16_kernel<2>), grid, dim3(SB_WAVES * 64), 0, s, op, keys, zj, B, part);
+                const long total = (long)nz * B * op.m;
+                const int rgrid = (int)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+                hipLaunchKernelGGL(sketch_partials_kernel, dim3(rgrid), dim3(256), 0, s, part, nz, splits, tiles, op.m, B, op.scale, yj);
+            } else if ((op.n & 3) == 0 && mfma_wgs >= 128) {
+                // the same without a workspace (or more than 512 rows): fp32 matrix cores
                 hipLaunchKernelGGL(sketch_rademacher_mfma_kernel, dim3((op.m + 15) / 16, (B + 15) / 16, nz), dim3(SM_WAVES * 64), 0, s,
                                    op, keys, zj, B, yj);
             } else if ((long)((op.m + 3) / 4) * tgroups * nz >= 256) {
@@ -423,7 +561,7 @@ hipError_t launch_sketch_multi(const OpDesc* ops, int n_ops, const float* z, int
 }
 
 hipError_t launch_sketch(const OpDesc& op, const float* z, int B, float* y, hipStream_t s) {
-    return launch_sketch_multi(&op, 1, z, B, y, s);
+    return launch_sketch_multi(&op, 1, z, B, y, s, nullptr, 0);
 }
 
 }  // namespace csk

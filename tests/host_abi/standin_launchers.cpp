@@ -10,7 +10,7 @@ extern "C" { int standin_launches = 0; }
 namespace csk {
 static hipError_t ok() { ++standin_launches; return hipSuccess; }
 hipError_t launch_sketch(const OpDesc&, const float*, int, float*, hipStream_t) { return ok(); }
-hipError_t launch_sketch_multi(const OpDesc*, int, const float*, int, float*, hipStream_t) { return ok(); }
+hipError_t launch_sketch_multi(const OpDesc*, int, const float*, int, float*, hipStream_t, void*, size_t) { return ok(); }
 bool sketch_srht_supported(const OpDesc& op) { return op.nbits <= 15; }
 hipError_t launch_plan_build(const Plan&, const float*, hipStream_t) { return ok(); }
 size_t recover_spill_floats(const Plan& p, int k, int) { return p.N > 512 || k > 64 ? (size_t)k * p.rb * p.N : 0; }
