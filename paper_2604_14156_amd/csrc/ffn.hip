@@ -416,10 +416,11 @@ void ffn_gateup_gemv(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     if (lane == 0) hbuf[(size_t)g * 16 * b + c] = f32_to_bf16(sg / (1.0f + __expf(-sg)) * su);
 }
 
-// Down projection.  8 waves per workgroup, 6 blocks in flight per wave (other splits of the same number of
-// loads in flight, 16 x 3 or 4 x 12, are within a microsecond), at most 128 registers per lane.
-constexpr int DN_WAVES = 8;
-constexpr int DN_UB = 6;                              // blocks in flight per wave
+// Down projection.  16 waves per workgroup, each with one block in flight at a time: timed in alternation,
+// 16 x 1 beats 16 x 2 by half a microsecond per call and 8 waves x 6 blocks by two (more waves interleave
+// their load / exchange / multiply phases more finely than one wave's batches do).
+constexpr int DN_WAVES = 16;
+constexpr int DN_UB = 1;                              // blocks in flight per wave
 
 __global__ __launch_bounds__(DN_WAVES * 64)
 void ffn_down_mfma(const uint16_t* __restrict__ Wd, int d, int G, int b, const uint16_t* __restrict__ hbuf,
