@@ -37,8 +37,8 @@ constexpr int GW_WAVES = 8, GW_THREADS = GW_WAVES * 64;
 constexpr int GW_KC = 512;                            // columns of the token rows per staged chunk
 constexpr int GW_XROW = GW_KC + 8;                    // LDS row stride in elements: 16 bytes of padding
 constexpr int GW_TROW = 72;                           // row stride of a wave's turning tile in elements (128 + 16 bytes)
-constexpr int DW_WAVES = 8;
-constexpr int DW_UB = 3;                              // blocks in flight per wave
+constexpr int DW_WAVES = 16;
+constexpr int DW_UB = 1;                              // blocks in flight per wave (16 x 1 beats 8 x 3 by 2 us at 32 rows, equal at 64)
 
 __device__ __forceinline__ bf16x8_t ldfrag(const uint16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
 __device__ __forceinline__ bf16x8_t ldfrag_once(const uint16_t* p) {       // read once, whole lines per load
