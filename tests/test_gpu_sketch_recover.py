@@ -575,11 +575,13 @@ def test_group_of_layers_full_size_sketch_and_recovery(cs):
     assert exact >= 1
 
 
-@pytest.mark.parametrize("m,n,B,n_ops", [(40, 1004, 19, 30), (256, 4096, 16, 8), (32, 128, 33, 40)])
+@pytest.mark.parametrize("m,n,B,n_ops", [(40, 1004, 19, 30), (256, 4096, 16, 8), (32, 128, 33, 40),
+                                         (300, 2052, 20, 20), (512, 640, 5, 9), (520, 516, 16, 4)])
 def test_multi_operator_sketch_matrix_core_path(cs, m, n, B, n_ops):
     """Rademacher launches with at least 128 tiles of 16 rows x 16 tokens run on the matrix cores: ragged row,
-    token and column counts, more operators than one launch holds; every (operator, token) against the
-    single-operator kernel, sampled ones against the oracle."""
+    token and column counts, more operators than one launch holds, more than 256 rows (two row blocks per
+    wave), more than 512 (the fp32 matrix-core kernel); every (operator, token) against the single-operator
+    kernel, sampled ones against the oracle."""
     rng = wl.rng_for(91 + m + n_ops)
     z = rng.standard_normal((n_ops, B, n)).astype(np.float32)
     ops = [binding.make_op(wl.RADEMACHER, 700 + 3 * j, 2 * j, m, n) for j in range(n_ops)]
