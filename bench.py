@@ -524,11 +524,59 @@ def cpu_baseline(wl, layers_all=12, layers_one=3, B=16, seed=3000):
     with threadpool_limits(limits=1):
         t_one = layers(layers_one)
     rate = lambda t, n: B / (t / n * 32)
-    return {"value": rate(t_all, layers_all), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d of 32 layers of one decode step at batch %d (%.1f s), scaled to 32 layers"
-                      % (layers_all, B, t_all),
-            "single_thread": {"value": rate(t_one, layers_one), "unit": "tokens/s", "cores": 1,
-                              "sample": "%d of 32 layers (%.1f s), scaled to 32 layers" % (layers_one, t_one)}}
+
+    # the oracle's plain C twin (loops, -O2, OpenMP over independent tokens and rows) on the same layers:
+    # what the host does without an interpreter and without a tuned BLAS, on one core and on all of them
+    def twin_layers(n):
+        from oracle import c_twin
+        t_total = 0.0
+        for _ in range(n):
+            z, _ = wl.plant_usage(rng, pi, c.k, B, c.amp, c.bg)
+            u, _ = wl.plant_head_usage(rng, hs, B)
+            x = wl.make_tokens(rng, B, c.d, "bf16")
+            t0 = time.perf_counter()
+            yh = c_twin.sketch(hs.ens, seed, 1, hs.m, u)
+            c_twin.block_omp(Mh, yh, hs.H, hs.kh, False)
+            c_twin.head_attn(q64, K64, V64, compact)
+            y = c_twin.sketch(c.ens, seed, 0, c.m, z)
+            S = c_twin.block_omp(M, y, c.G, c.k, True)[0]
+            c_twin.block_ffn(Wg64, Wu64, Wd64, x, S)
+            t_total += time.perf_counter() - t0
+        return t_total
+
+    twin = None
+    try:
+        from oracle import c_twin
+        Wg64, Wu64, Wd64 = (np.ascontiguousarray(w, dtype=np.float64) for w in (Wg, Wu, Wd))
+        q64, K64, V64 = (np.ascontiguousarray(w, dtype=np.float64) for w in (q, K, V))
+        ncores = c_twin.set_threads(0)
+        t_tw_all = twin_layers(4)
+        c_twin.set_threads(1)
+        t_tw_one = twin_layers(1)
+        c_twin.set_threads(0)
+        twin = {"all_cores": {"value": rate(t_tw_all, 4), "unit": "tokens/s", "cores": ncores,
+                              "sample": "4 of 32 layers (%.1f s), scaled to 32 layers" % t_tw_all},
+                "single_thread": {"value": rate(t_tw_one, 1), "unit": "tokens/s", "cores": 1,
+                                  "sample": "1 of 32 layers (%.1f s), scaled to 32 layers" % t_tw_one},
+                "what": "oracle/c_twin: the same definitions as plain C loops in fp64 (gcc -O2, OpenMP over tokens and rows)"}
+    except Exception as exc:                              # no compiler on the box: the NumPy figures stand alone
+        twin = {"error": str(exc)[:200]}
+    numpy_leg = {"value": rate(t_all, layers_all), "unit": "tokens/s", "cores": int(threads),
+                 "sample": "%d of 32 layers of one decode step at batch %d (%.1f s), scaled to 32 layers"
+                           % (layers_all, B, t_all),
+                 "single_thread": {"value": rate(t_one, layers_one), "unit": "tokens/s", "cores": 1,
+                                   "sample": "%d of 32 layers (%.1f s), scaled to 32 layers" % (layers_one, t_one)},
+                 "what": "oracle/*.py: NumPy fp64, Python loops over tokens and rounds, the numerical libraries' thread pools as they come"}
+    if "all_cores" in twin:
+        # the headline of the baseline is the faster of the two forms of the oracle: the C twin on all cores
+        return {"value": twin["all_cores"]["value"], "unit": "tokens/s", "cores": twin["all_cores"]["cores"], "kind": "oracle",
+                "sample": "oracle/c_twin (plain C loops, fp64, gcc -O2, OpenMP over tokens and rows): "
+                          + twin["all_cores"]["sample"] + " of one decode step at batch %d" % B,
+                "single_thread": twin["single_thread"], "numpy_oracle": numpy_leg}
+    out = dict(numpy_leg)
+    out["kind"] = "oracle"
+    out["c_twin"] = twin
+    return out
 
 
 def time_loop(fn, iters, stream):

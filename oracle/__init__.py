@@ -42,6 +42,13 @@ Pin status of each function (what ties it to something other than itself):
 * joint_select_coupled -- pooled sketch = sketch of the pooled usage (linearity), k_tok = n
                         reduces to the mean over all tokens, planted prompts where the kept
                         tokens share one support and the dropped ones do not.
+* c_twin (plain C)   -- the decode-step functions (generator, operator entries, sketch, effective
+                        matrix with one atom per unit, block_omp, block_ffn, head_attn) written
+                        again as C loops for the CPU-baseline timing; pinned by the generator's
+                        known-answer vectors, exhaustive search over supports, the masked dense
+                        identity, full softmax attention, library least squares, and agreement
+                        with the NumPy functions above to rounding.  No parity test of the HIP
+                        path depends on it.
 """
 from .philox import philox4x32_10
 from .operator import phi_entries, phi_matrix, srht_rows, srht_order, GAUSS, RADEMACHER, SRHT
