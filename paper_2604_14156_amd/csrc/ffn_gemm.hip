@@ -35,7 +35,12 @@ struct GemmArgs {
     int T, d, G, nb_max;      // nb_max: row length of hid / 64
 };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return (row << 3) + (chunk ^ (row & 7)); }
+// LDS serves a 16-byte read per lane sixteen lanes at a time: lanes 0-7 with 24-31 and 8-15 with 16-23 of each half
+// of the wave, and the sixteen have to fall into different 16-byte columns of the 256-byte bank row (measured: a
+// fragment read takes 1.6 times as long otherwise).  A fragment read has lane = row % 32 + 32 * (chunk % 2), so the
+// swizzle takes bit 4 of the row along with the low bits.
+__device__ __forceinline__ int swz_of(int row) { return ((row >> 1) & 3) | (((row >> 4) & 1) << 2); }
+__device__ __forceinline__ int swz(int row, int chunk) { return (row << 3) + (chunk ^ swz_of(row)); }
 
 // rows of a [32 x 32] accumulator: register j of lane L is (row 8*(j/4) + 4*(L/32) + j%4, column L%32)
 __device__ __forceinline__ int acc_row(int j, int lane) { return 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3); }
@@ -207,7 +212,10 @@ constexpr int GW_MIN_WGS = CS_GW_MIN_WGS;              // fewer wide workgroups 
 constexpr int GW_STAGE = (GW_BM + GW_BN) * 4;          // 16-byte entries per stage
 constexpr int GW_MAX_BLOCKS = 4096;                    // longest gathered list the down product keeps in LDS
 
-__device__ __forceinline__ int swz4(int row, int chunk) { return (row << 2) + (chunk ^ ((row >> 1) & 3)); }
+// rows of 64 bytes: four rows fill a bank row, and of the rows read together (see swz) those that share row % 4
+// differ in bits 2 and 4
+__device__ __forceinline__ int swz4_of(int row) { return ((row >> 2) & 1) | (((row >> 4) & 1) << 1); }
+__device__ __forceinline__ int swz4(int row, int chunk) { return (row << 2) + (chunk ^ swz4_of(row)); }
 
 // One wave copies 1 KB from global memory into LDS without passing through registers: lane p
 // supplies the address of its 16 bytes, which land at lds_wave_base + 16 p.  The instruction takes
@@ -255,7 +263,7 @@ void ffn_gemm_wide_kernel(GemmArgs a) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int r = (u * 4 + wave) * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ ((r >> 1) & 3);
+        const int chunk = (lane & 3) ^ swz4_of(r);
         const int m = min(bm + r, T - 1);              // rows past T repeat the last row; never stored
         pa[u] = (MODE == 0 ? a.x + (size_t)m * d : a.hid + (size_t)m * ldh) + chunk * 8;
         if (MODE == 0) {

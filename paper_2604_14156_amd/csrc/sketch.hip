@@ -192,7 +192,7 @@ void sketch_rademacher_mfma_kernel(OpDesc op, OpKeys keys, const float* __restri
 // sketch_partials_kernel, which also applies the scale.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 sk_bf16x8;
 constexpr int SB_WAVES = 16;
-constexpr int SB_ROW = 136;                            // bf16 per token row of a plane: 128 + 8 (272 bytes: conflict-free 16-byte reads)
+constexpr int SB_ROW = 144;                            // bf16 per token row of a plane: 128 + 16 (288 bytes = 32 modulo 256: conflict-free 16-byte fragment reads, measured)
 constexpr int SB_PLANE = 16 * SB_ROW;
 constexpr int SB_MAX_SPLITS = 32;                      // column ranges per token tile
 #ifndef SB_TARGET_WGS
