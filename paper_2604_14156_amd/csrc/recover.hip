@@ -301,6 +301,7 @@ struct FastLayout {
 constexpr int RF_MAXK = 64;        // selected atoms handled by the single-wavefront solves
 constexpr int RF_MAXK_SELECT = 256; // selected atoms of the support-only variant (no solves)
 constexpr int RF_THREADS = 512;
+constexpr int RP_MIN_PROBLEMS = 256;   // launches with more sketches than this solve two per workgroup
 
 // fit = false (support and margin only): no refit work areas and no padding rows in the factor.
 static bool make_fast_layout(const Plan& p, int k, int lds_limit, int nthreads, bool fit, bool have_spill, FastLayout& L) {
@@ -758,6 +759,307 @@ void recover_fast_kernel(Plan p, RecoverArgs a, FastLayout L) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Two sketches per workgroup, for launches with more problems than the chip has compute units (the decode
+// loop's batched call: tokens x layers).  The rounds of recover_fast_kernel keep three waves of a
+// workgroup busy at the 7B FFN shape and a compute unit holds one such workgroup (the Gram matrix fills its
+// LDS), so 512 problems take two turns.  Here two tokens of the same operator share one copy of the Gram
+// matrix, stored as its lower triangle (it is symmetric entry by entry: both halves are the same sum of the
+// same products in the same order), each with a group of waves, a factor and a candidate area of its own;
+// the per-token arithmetic is that of recover_fast_kernel<true, *, false>, operation by operation, so the
+// supports and margins are the same bits.  M is read once for the two tokens.
+// ---------------------------------------------------------------------------
+struct PairLayout {
+    int group_floats;     // per token: off_y .. end of the factor
+    int off_y, off_cand, off_red, off_Dt;
+    int off_tri;          // the Gram triangle, after the two groups
+    int KS, total_floats;
+};
+
+static bool make_pair_layout(const Plan& p, int k, int lds_limit, PairLayout& L) {
+    const int N = p.N, m = p.op.m;
+    int ks = (k + 3) & ~3;
+    if (((ks >> 2) & 1) == 0) ks += 4;        // an odd number of 16-byte groups per row, as in the single-token layout
+    L.KS = ks;
+    int o = 0;
+    L.off_y = o; o += (m + 3) & ~3;
+    L.off_cand = o; o += 2 * 16 * 8;
+    L.off_red = o; o += 16;
+    int dt = N * ks;
+    if (dt < RF_THREADS * 4) dt = RF_THREADS * 4;          // doubles as the staging area of the first correlations
+    L.off_Dt = o; o += (dt + 3) & ~3;
+    L.group_floats = o;
+    L.off_tri = 2 * o;
+    const long total = 2L * o + (long)N * (N + 1) / 2;
+    L.total_floats = (int)total;
+    return total <= lds_limit / 4 - 16;
+}
+
+template <bool WANT_MARGIN>
+__global__ __launch_bounds__(RF_THREADS)
+void recover_pair_kernel(Plan p, RecoverArgs a, PairLayout L) {
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x;
+    constexpr int NT = RF_THREADS;
+    const int lane = tid & 63, wave = tid >> 6;
+    if (a.plans) p = a.plans[blockIdx.y];
+    const int N = p.N, m = p.op.m, k = a.k, KS = L.KS;
+    const int round_waves = (N + 63) >> 6;     // waves per token in the rounds; the host checks 2 * round_waves <= NT / 64
+    const int grp = wave / round_waves;        // the token this wave serves in the rounds (2 and above: none)
+    const int lw = wave - grp * round_waves;   // the wave's place in its group
+    const int c = tid - grp * round_waves * 64;   // atom of this thread in the rounds
+    const bool in_group = grp < 2;
+    const bool active = in_group && c < N;
+    const int t0 = 2 * blockIdx.x;
+    const int ntok = min(2, a.B - t0);         // a lone last token is solved twice and stored once
+    const int prob0 = blockIdx.y * a.B + t0, prob1 = prob0 + (ntok == 2 ? 1 : 0);
+
+    float* base0 = lds, * base1 = lds + L.group_floats;
+    float* mine = in_group && grp == 1 ? base1 : base0;
+    float* yv0 = base0 + L.off_y, * yv1 = base1 + L.off_y;
+    float* cand = mine + L.off_cand;           // [2][16][8]
+    float* red = mine + L.off_red;
+    float* Dt = mine + L.off_Dt;               // [N][KS], row c = factor entries of atom c
+    float* tri = lds + L.off_tri;              // G[i][j], j <= i, at i (i + 1) / 2 + j
+
+    // ---- every independent global load is issued before the first wait
+    const float* y0 = a.y + (size_t)prob0 * m, * y1 = a.y + (size_t)prob1 * m;
+    const float yreg0 = (tid < m) ? y0[tid] : 0.f, yreg1 = (tid < m) ? y1[tid] : 0.f;
+    const float w = (active && p.weighted) ? p.W[c] : 1.f;
+    const float gd = active ? p.gram[(size_t)c * N + c] : 1.f;
+    constexpr int GU = 8;
+    const int n4 = (N * N) >> 2;               // N is a multiple of 4: a group of four never straddles rows
+    const float4* gsrc = reinterpret_cast<const float4*>(p.gram);
+    float4 greg[GU];
+    int grow_[GU], gcol_[GU];
+    auto row_col = [&](int idx, int& row, int& col) {
+        // (4 idx) / N without the integer division: exact, 4 idx < 2^18 and N <= 256 keep (4 idx + 0.5) / N
+        // further than 2^-10 from the next integer
+        row = (int)__fdividef((float)(4 * idx) + 0.5f, (float)N);
+        col = 4 * idx - row * N;
+    };
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+        const int idx = u * NT + tid;
+        row_col(idx, grow_[u], gcol_[u]);
+        const bool need = idx < n4 && gcol_[u] <= grow_[u];
+        greg[u] = need ? gsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!need) grow_[u] = -1;
+    }
+    auto to_tri = [&](const float4& v, int row, int col) {
+        float* dst = tri + (row * (row + 1)) / 2 + col;
+        dst[0] = v.x;
+        if (col + 1 <= row) dst[1] = v.y;
+        if (col + 2 <= row) dst[2] = v.z;
+        if (col + 3 <= row) dst[3] = v.w;
+    };
+    // slices of M^T y: a thread takes four adjacent atoms and a contiguous range of rows, for both tokens
+    const int ncg = N >> 2;
+    const int parts = NT / ncg;
+    const int cg = tid % ncg, part = tid / ncg;
+    const int rows_per = (m + parts - 1) / parts;
+    const int i0 = part * rows_per, i1 = part < parts ? min(m, i0 + rows_per) : i0;
+    constexpr int MU = 8;
+    float4 mreg[MU];
+    const float4* mr = reinterpret_cast<const float4*>(p.Mr) + cg;
+#pragma unroll
+    for (int u = 0; u < MU; ++u)
+        mreg[u] = (i0 + u < i1) ? mr[(size_t)(i0 + u) * ncg] : make_float4(0.f, 0.f, 0.f, 0.f);
+    int bad0 = !isfinite(yreg0), bad1 = !isfinite(yreg1);
+    if (tid < m) { yv0[tid] = yreg0; yv1[tid] = yreg1; }
+    for (int i = tid + NT; i < m; i += NT) {          // only when m exceeds the workgroup size
+        const float v0 = y0[i], v1 = y1[i];
+        yv0[i] = v0; yv1[i] = v1;
+        if (!isfinite(v0)) bad0 = 1;
+        if (!isfinite(v1)) bad1 = 1;
+    }
+#pragma unroll
+    for (int u = 0; u < GU; ++u) if (grow_[u] >= 0) to_tri(greg[u], grow_[u], gcol_[u]);
+    for (int base = GU * NT; base < n4; base += NT) {
+        const int idx = base + tid;
+        int row, col;
+        row_col(idx, row, col);
+        if (idx < n4 && col <= row) to_tri(gsrc[idx], row, col);
+    }
+    bad0 = __syncthreads_or(bad0);
+    bad1 = __syncthreads_or(bad1);
+
+    float corr = 0.f;
+    {
+        float* stage0 = base0 + L.off_Dt, * stage1 = base1 + L.off_Dt;     // [parts][N] each
+        float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+        for (int ib = i0; ib < i1; ib += MU) {
+            if (ib != i0) {
+#pragma unroll
+                for (int u = 0; u < MU; ++u)
+                    mreg[u] = (ib + u < i1) ? mr[(size_t)(ib + u) * ncg] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < MU; ++u)
+                if (ib + u < i1) {
+                    const float ya = yv0[ib + u], yb = yv1[ib + u];
+                    acc0.x += mreg[u].x * ya; acc0.y += mreg[u].y * ya; acc0.z += mreg[u].z * ya; acc0.w += mreg[u].w * ya;
+                    acc1.x += mreg[u].x * yb; acc1.y += mreg[u].y * yb; acc1.z += mreg[u].z * yb; acc1.w += mreg[u].w * yb;
+                }
+        }
+        if (part < parts) {
+            reinterpret_cast<float4*>(stage0)[part * ncg + cg] = acc0;
+            reinterpret_cast<float4*>(stage1)[part * ncg + cg] = acc1;
+        }
+        __syncthreads();
+        if (active) for (int q = 0; q < parts; ++q) corr += Dt[q * N + c];
+        __syncthreads();                                // the staging areas become the factors
+    }
+    bool selected = false;
+    float margin = 1.f;
+    float sq = 0.f;                                     // squared norm of the thread's factor row so far
+    float* myrow = Dt + (size_t)(active ? c : 0) * KS;
+    // rows are zero beyond their last written entry, so that a round may read whole groups of four
+    for (int i = tid; i < (N * KS) >> 2; i += NT) {
+        reinterpret_cast<float4*>(base0 + L.off_Dt)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        reinterpret_cast<float4*>(base1 + L.off_Dt)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    int badr = 0;
+    for (int J = 0; J < k; ++J) {
+        if (in_group) {
+            // key: 0 for lanes without a candidate, else 1 + the bit pattern of the (non-negative) score
+            uint32_t key = 0u;
+            if (active && !selected) {
+                const float t = w * corr;
+                float score = t * t;
+                if (!(score >= 0.f)) score = 0.f;        // NaN scores tie at zero
+                key = __float_as_uint(score) + 1u;
+            }
+            const uint32_t m1 = wave_max_u32(key);
+            const unsigned long long hit = __ballot(key == m1);
+            const int l1 = __ffsll((long long)hit) - 1;
+            const float c1 = readlane_f32(corr, l1);
+            const float nrm2 = gd - sq;
+            float rs = 0.f;
+            if (nrm2 > 1e-10f * gd && nrm2 > 0.f) rs = __builtin_amdgcn_rsqf(nrm2);
+            const float i1v = readlane_f32(rs, l1);
+            uint32_t m2 = 0u;
+            if (WANT_MARGIN) m2 = wave_max_u32(lane == l1 ? 0u : key);
+            if (lane == 0) {
+                float4 cv;
+                cv.x = __uint_as_float(m1); cv.y = __int_as_float(lw * 64 + l1); cv.z = __uint_as_float(m2); cv.w = c1;
+                float* cw = cand + ((J & 1) * 16 + lw) * 8;
+                *reinterpret_cast<float4*>(cw) = cv;
+                cw[4] = i1v;
+            }
+        }
+        __syncthreads();
+        if (in_group) {
+            const float* cb = cand + (J & 1) * 16 * 8;
+            uint32_t k1 = 0u, k2 = 0u;
+            int gstar = 0;
+            float ccol = 0.f, inv = 0.f;
+            for (int w0 = 0; w0 < round_waves; w0 += 4) {
+                float4 cw[4];
+                float ci[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (w0 + q < round_waves) {
+                        const float* e = cb + (w0 + q) * 8;
+                        cw[q] = *reinterpret_cast<const float4*>(e);
+                        ci[q] = e[4];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (w0 + q >= round_waves) break;
+                    const uint32_t o1 = __float_as_uint(cw[q].x);
+                    const uint32_t o2 = __float_as_uint(cw[q].z);
+                    const bool up = o1 > k1 || w0 + q == 0;   // ties keep the lower wave = lower index
+                    k2 = up ? max(max(k2, k1), o2) : max(k2, o1);
+                    gstar = up ? __float_as_int(cw[q].y) : gstar;
+                    ccol = up ? cw[q].w : ccol;
+                    inv = up ? ci[q] : inv;
+                    k1 = up ? o1 : k1;
+                }
+            }
+            if (WANT_MARGIN) {
+                const float s1 = __uint_as_float(k1 - 1u);
+                const float s2 = k2 ? __uint_as_float(k2 - 1u) : 0.f;
+                margin = fminf(margin, s1 > 0.f ? (s1 - s2) * __builtin_amdgcn_rcpf(s1) : 0.f);
+            }
+            if (c == gstar) selected = true;
+            const int hi = max(gstar, c), lo = min(gstar, c);
+            const float gmine = active ? tri[(hi * (hi + 1)) / 2 + lo] : 0.f;
+            const float* prow = Dt + (size_t)gstar * KS;
+            float dot = 0.f;
+            const int JU = (J + 3) & ~3;               // whole groups of four: the rows end in zeros
+            int j = 0;
+            for (; j + 16 <= JU; j += 16) {
+                float4 u[4], v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    u[q] = *reinterpret_cast<const float4*>(myrow + j + 4 * q);
+                    v[q] = *reinterpret_cast<const float4*>(prow + j + 4 * q);
+                }
+                float d2 = 0.f;
+#pragma unroll
+                for (int q = 0; q < 4; q += 2) {
+                    dot += u[q].x * v[q].x + u[q].y * v[q].y + u[q].z * v[q].z + u[q].w * v[q].w;
+                    d2 += u[q + 1].x * v[q + 1].x + u[q + 1].y * v[q + 1].y + u[q + 1].z * v[q + 1].z + u[q + 1].w * v[q + 1].w;
+                }
+                dot += d2;
+            }
+            if (j < JU) {
+                const float4 u0 = *reinterpret_cast<const float4*>(myrow + j);
+                const float4 v0 = *reinterpret_cast<const float4*>(prow + j);
+                if (j + 4 < JU) {
+                    const float4 u1 = *reinterpret_cast<const float4*>(myrow + j + 4);
+                    const float4 v1 = *reinterpret_cast<const float4*>(prow + j + 4);
+                    if (j + 8 < JU) {
+                        const float4 u2 = *reinterpret_cast<const float4*>(myrow + j + 8);
+                        const float4 v2 = *reinterpret_cast<const float4*>(prow + j + 8);
+                        dot += u2.x * v2.x + u2.y * v2.y + u2.z * v2.z + u2.w * v2.w;
+                    }
+                    dot += u1.x * v1.x + u1.y * v1.y + u1.z * v1.z + u1.w * v1.w;
+                }
+                dot += u0.x * v0.x + u0.y * v0.y + u0.z * v0.z + u0.w * v0.w;
+            }
+            if (inv == 0.f) badr = 1;
+            const float dv = (gmine - dot) * inv;
+            const float bt = ccol * inv;
+            corr -= bt * dv;
+            sq += dv * dv;
+            if (active) myrow[J] = dv;
+        }
+    }
+    bad0 = __syncthreads_or(bad0 | (grp == 0 ? badr : 0));
+    bad1 = __syncthreads_or(bad1 | (grp == 1 ? badr : 0));
+
+    // ascending support straight from the selection flags: the rank of a selected atom is the number of
+    // selected atoms below it
+    const unsigned long long sb = __ballot(selected);
+    if (in_group && lane == 0) red[lw] = __int_as_float(__popcll(sb));
+    __syncthreads();
+    const bool stores = in_group && grp < ntok;
+    const int prob = grp == 1 ? prob1 : prob0;
+    if (stores && selected) {
+        int rank = __popcll(sb & ((1ull << lane) - 1ull));
+        for (int wv = 0; wv < lw; ++wv) rank += __float_as_int(red[wv]);
+        a.support[(size_t)prob * k + rank] = c;
+    }
+    if (WANT_MARGIN && stores && lw == 0 && lane == 0) a.margin[prob] = (grp == 1 ? bad1 : bad0) ? 0.f : margin;
+}
+
+template <bool WANT_MARGIN>
+static hipError_t launch_pair(const Plan& p, const RecoverArgs& a, const PairLayout& PL, hipStream_t s) {
+    const size_t bytes = (size_t)PL.total_floats * 4;
+    static size_t allowed = 0;
+    if (bytes > allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(recover_pair_kernel<WANT_MARGIN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        allowed = bytes;
+    }
+    hipLaunchKernelGGL((recover_pair_kernel<WANT_MARGIN>), dim3((a.B + 1) / 2, a.nplans), dim3(RF_THREADS), bytes, s, p, a, PL);
+    return hipGetLastError();
+}
+
 template <bool GRAM_LDS, bool WANT_MARGIN, bool WANT_FIT>
 static hipError_t launch_fast(const Plan& p, const RecoverArgs& a, const FastLayout& FL, int nthreads, hipStream_t s) {
     const size_t bytes = (size_t)FL.total_floats * 4;
@@ -779,6 +1081,11 @@ hipError_t launch_recover(const Plan& p, const RecoverArgs& a, int lds_limit, hi
         // one wavefront for small problems, otherwise a full workgroup so that the bulk loads
         // (Gram matrix, M) have many requests in flight
         const int nthreads = (p.N <= 64 && p.op.m <= 64) ? 64 : RF_THREADS;
+        // more problems than compute units, supports only: two tokens of an operator per workgroup
+        PairLayout PL;
+        if (!fit && nthreads == RF_THREADS && a.B >= 2 && (long)a.B * a.nplans > RP_MIN_PROBLEMS && (p.N & 3) == 0 &&
+            2 * ((p.N + 63) / 64) <= RF_THREADS / 64 && make_pair_layout(p, a.k, lds_limit, PL))
+            return a.margin ? launch_pair<true>(p, a, PL, s) : launch_pair<false>(p, a, PL, s);
         FastLayout FL;
         if (make_fast_layout(p, a.k, lds_limit, nthreads, fit, a.spill != nullptr && a.spill_stride >= (size_t)a.k * p.N, FL)) {
             const bool gl = FL.off_gram >= 0, mg = a.margin != nullptr;

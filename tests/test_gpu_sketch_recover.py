@@ -575,6 +575,49 @@ def test_group_of_layers_full_size_sketch_and_recovery(cs):
     assert exact >= 1
 
 
+@pytest.mark.parametrize("G,b,m,k,B,n_ops", [(172, 64, 256, 43, 16, 17), (100, 4, 72, 9, 5, 53), (256, 2, 80, 10, 3, 90),
+                                             (64, 8, 96, 12, 2, 130), (128, 4, 96, 59, 7, 40)])
+def test_more_sketches_than_compute_units_two_per_workgroup(cs, G, b, m, k, B, n_ops):
+    """Launches with more than 256 sketches and no refit outputs solve two tokens of an operator per
+    workgroup (Gram triangle shared in LDS); supports and margins are the bits of one call per operator
+    (one token per workgroup), odd batch sizes leave a lone last token, and sampled (operator, token)
+    pairs agree with the oracle's block-OMP."""
+    seed = 8400 + G
+    rng = wl.rng_for(seed)
+    n = G * b
+    ops, dcts, psis, zs = [], [], [], []
+    for j in range(n_ops):
+        pi, psi = wl.make_profiles(rng, G, b)
+        z, _ = wl.plant_usage(rng, pi, min(k, G // 3), B, "laplace", 0.05)
+        psi_dev = dev_f32(psi)
+        psis.append(psi_dev)
+        zs.append(z)
+        ops.append(binding.make_op(wl.RADEMACHER, seed, j, m, n))
+        dcts.append(binding.make_dict(psi_dev, G, b, 1))
+        cs.cs_plan(ops[j], dcts[j], psi_dev)
+    Y = cs.cs_sketch_multi(ops, dev_f32(np.stack(zs)))
+    sup, _, _, margin = cs.cs_recover_support_multi(ops, dcts, k, Y, want_coef=False, want_resid=False)
+    assert sup.shape == (n_ops, B, k)
+    for j in sorted({0, 1, n_ops // 2, n_ops - 1}):
+        s1, _, _, m1 = cs.cs_recover_support(ops[j], dcts[j], k, Y[j].clone(), want_coef=False, want_resid=False)
+        assert torch.equal(sup[j], s1) and torch.equal(margin[j], m1)
+    hs_ = host(sup)
+    for j, t in ((0, 0), (n_ops - 1, B - 1), (n_ops // 2, B // 2)):
+        assert np.all(np.diff(hs_[j, t]) > 0) and hs_[j, t].min() >= 0 and hs_[j, t].max() < G
+        y = host(Y[j, t]).astype(np.float64)
+        M = oracle.effective_matrix(wl.RADEMACHER, seed, j, m, n, G, b, 1, host(psis[j]).reshape(G, b, 1))
+        rec = oracle.block_omp(M, y, G, 1, k, True)
+        assert_greedy_support(M, y, G, 1, k, True, hs_[j, t], rec)
+    # a non-finite sketch poisons its own token only
+    Yb = Y.clone()
+    Yb[1, 0, 3] = float("nan")
+    supb, _, _, marb = cs.cs_recover_support_multi(ops, dcts, k, Yb, want_coef=False, want_resid=False)
+    assert float(marb[1, 0]) == 0.0
+    if B > 1:
+        assert torch.equal(supb[1, 1], sup[1, 1]) and torch.equal(marb[1, 1], margin[1, 1])
+    assert torch.equal(supb[0], sup[0]) and torch.equal(supb[2:], sup[2:])
+
+
 @pytest.mark.parametrize("m,n,B,n_ops", [(40, 1004, 19, 30), (256, 4096, 16, 8), (32, 128, 33, 40),
                                          (300, 2052, 20, 20), (512, 640, 5, 9), (520, 516, 16, 4)])
 def test_multi_operator_sketch_matrix_core_path(cs, m, n, B, n_ops):
