@@ -8,7 +8,7 @@
 // register file of a compute unit).  So here
 //   gate/up : the channels of all listed blocks form one range cut into gridDim.x equal pieces, so every
 //             workgroup streams the same number of bytes, and a workgroup's piece is cut once more
-//             among its waves.  A wave owns a tile of 8 channels (8 gate rows + 8 up rows) over the
+//             among its waves, in whole tiles.  A wave owns a tile of 8 channels (8 gate rows + 8 up rows) over the
 //             whole reduction index: its accumulators (one per tile of 16 tokens) are final, nothing
 //             is summed across waves.  Weights go global -> registers -> matrix core; the registers
 //             of a k-step are refilled with the next chunk's weights right after use, so every load
@@ -178,7 +178,10 @@ void ffn_gateup_wide(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     auto set_range = [&](int nb) {
         const long F = (long)nb * b;
         const int f_lo = (int)((long)blockIdx.x * F / gridDim.x), f_hi = (int)((long)(blockIdx.x + 1) * F / gridDim.x);
-        const int cpw = (f_hi - f_lo + GW_WAVES - 1) / GW_WAVES;
+        // whole tiles of 8 channels per wave: a wave with 6 of its 8 rows in use issues the same loads and
+        // multiplies as a full one (43 channels per workgroup: five full waves and one with three rows
+        // instead of seven waves with six rows; the waves left without rows still stage the token rows)
+        const int cpw = ((f_hi - f_lo + GW_WAVES - 1) / GW_WAVES + 7) & ~7;
         w_lo = min(f_hi, f_lo + wave * cpw);
         w_hi = min(f_hi, w_lo + cpw);
         npass = (cpw + 7) >> 3;                        // the same for every wave of the workgroup
