@@ -539,12 +539,13 @@ def test_multi_operator_sketch_errors(cs):
 
 
 def test_group_of_layers_full_size_sketch_and_recovery(cs):
-    """The launch configuration of the decode benchmark: 16 layers x 16 tokens per launch at the FFN shape.
-    Sketches and supports equal those of one call per layer; oracle on sampled (layer, token) pairs."""
+    """The launch configuration of the decode benchmark: 32 layers x 16 tokens per launch at the FFN shape
+    (matrix-core sketch kernel, two sketches per recovery workgroup).  Sketches and supports equal those of
+    one call per layer; oracle on sampled (layer, token) pairs."""
     c = wl.CFG2
     seed = 8300
     rng = wl.rng_for(seed)
-    n_ops, B = 16, 16
+    n_ops, B = 32, 16
     ops, dcts, psis, zs = [], [], [], []
     for j in range(n_ops):
         pi, psi = wl.make_profiles(rng, c.G, c.b)
@@ -558,7 +559,7 @@ def test_group_of_layers_full_size_sketch_and_recovery(cs):
     Z = dev_f32(np.stack(zs))
     Y = cs.cs_sketch_multi(ops, Z)
     sup, _, _, margin = cs.cs_recover_support_multi(ops, dcts, c.k, Y, want_coef=False, want_resid=False)
-    for j in (0, 7, 15):
+    for j in (0, 7, 15, 31):
         # this many tiles take the matrix-core sketch kernel: same products, another order of the additions
         yj = cs.cs_sketch(ops[j], Z[j])
         for t in range(B):
@@ -566,7 +567,7 @@ def test_group_of_layers_full_size_sketch_and_recovery(cs):
         s1 = cs.cs_recover_support(ops[j], dcts[j], c.k, Y[j].clone(), want_coef=False, want_resid=False)[0]
         assert torch.equal(sup[j], s1)
     hs_, exact = host(sup), 0
-    for j, t in ((0, 0), (7, 5), (15, 15)):
+    for j, t in ((0, 0), (7, 5), (15, 15), (31, 14), (24, 9)):
         want_y = oracle.sketch(c.ens, seed, 2 * j, c.m, zs[j][t:t + 1])[0]
         assert rel_err(host(Y[j, t]), want_y) <= 1e-5
         M = oracle.effective_matrix(c.ens, seed, 2 * j, c.m, c.n, c.G, c.b, 1, host(psis[j]).reshape(c.G, c.b, 1))
