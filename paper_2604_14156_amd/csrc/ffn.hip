@@ -215,7 +215,7 @@ void ffn_gateup_mfma(const uint16_t* __restrict__ Wg, const uint16_t* __restrict
     __shared__ int wcount[FD_WAVES];
     __shared__ float red[2][FD_WAVES][256];
     __shared__ int n_direct;                          // listed blocks that are handled as direct items
-    // per wave: two tiles of 16 rows (8 gate, 8 up) x 128 bytes, rows padded to 144 bytes (fragment reads without
+    // per wave: two tiles of 16 rows (8 gate, 8 up) x 128 bytes, pieces swizzled (turn_at: fragment reads without
     // bank conflicts); two pairs of k-steps are exchanged at a time, which halves the waits for LDS (1.4 us per
     // call at 16 rows)
     __shared__ __attribute__((aligned(16))) uint16_t turn[FD_WAVES][2][16 * FD_TROW];
