@@ -9,6 +9,9 @@ iteration is the classical normalised hard-thresholding scheme:
     g      = M^T (y - M alpha)                    gradient of the data term
     mu     = ||g_S||^2 / ||M g_S||^2              exact line search on the current support S
                                                   (first step: S = the k units with most gradient energy)
+                                                  stop when ||g_S|| <= 1e-3 of its value in the first step:
+                                                  alpha is then the least-squares fit on S and the line
+                                                  search would divide rounding noise by rounding noise
     p      = alpha + mu g
     S      = the k units with the largest energy of p   (ties -> smaller index)
     alpha  = p restricted to S
@@ -19,6 +22,9 @@ dictionary the unit's entries are scaled by their atoms' norms (rb = 1: (p_g ||m
 with the identity dictionary the raw sum of squares.
 """
 import numpy as np
+
+
+STOP_REL = 1e-3      # the iteration stops once the gradient on the support is this small against its first value
 
 
 def _unit_energy(v, G, rb, weights):
@@ -60,6 +66,7 @@ def block_iht(M, y, G, rb, k, iters, normalised, prefer=None, slack=0.0):
     support = None
     margin = 1.0
     min_margin = 1.0
+    num0 = None
     for _ in range(iters):
         g = M.T @ (y - M @ alpha)
         if support is None:
@@ -70,8 +77,13 @@ def block_iht(M, y, G, rb, k, iters, normalised, prefer=None, slack=0.0):
         cols = np.concatenate([np.arange(u * rb, (u + 1) * rb) for u in support])
         gs = np.zeros(N)
         gs[cols] = g[cols]
+        num = float(gs @ gs)
+        if num0 is None:
+            num0 = num
+        elif num <= STOP_REL ** 2 * num0:
+            break                                  # converged on this support: support, alpha and margin stand
         den = float(np.sum((M @ gs) ** 2))
-        mu = float(gs @ gs) / den if den > 0.0 else 0.0
+        mu = num / den if den > 0.0 else 0.0
         p = alpha + mu * g
         energy = _unit_energy(p, G, rb, weights)
         support, order = _top_units(energy, k, boost)

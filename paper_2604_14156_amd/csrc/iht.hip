@@ -112,6 +112,7 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
     };
 
     float pmine = 0.f;
+    float num0 = 0.f;                               // ||g_S||^2 of the first iteration (wave 0)
     for (int it = 0; it < iters; ++it) {
         // gradient g = c0 - G alpha (alpha has at most k non-zeros, listed in S after the first pass).
         // Each wave keeps the list and the listed coefficients in the registers of its first k lanes and
@@ -162,9 +163,17 @@ void recover_iht_kernel(Plan p, RecoverArgs a, int iters, IhtLayout L) {
                 for (int q = 0; q < 4; ++q) t += gv4[q] * gi4[q];
             }
             const float num = wave_sum(greg * greg), den = wave_sum(greg * t);
-            if (lane == 0) misc[0] = den > 0.f ? num / den : 0.f;
+            if (it == 0) num0 = num;
+            // Once the gradient on the support has dropped to 1e-3 of its first value, alpha is the least-squares fit
+            // on that support to three digits (the refit after the loop makes it exact) and further steps only
+            // shrink a vector whose direction fp32 resolves less and less: the step length, and with it the
+            // energies of the units outside the support and the margin, would come to depend on rounding.  The
+            // iteration stops there (support, alpha and margin stand).
+            const bool converged = it > 0 && num <= 1e-6f * num0;
+            if (lane == 0) { misc[0] = den > 0.f ? num / den : 0.f; misc[3] = converged ? 1.f : 0.f; }
         }
         __syncthreads();
+        if (misc[3] != 0.f) break;                      // uniform: every thread reads the same word
         const float mu = misc[0];
         pmine = active ? alpha[tid] + mu * g : 0.f;
         float e = w * pmine; e = e * e;

@@ -43,6 +43,8 @@ def _check(cs, op, dct, M, Y, G, k, prev, swaps, normalised, prev_coef=None, gam
             assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm
             assert abs(margin[t] - rec["margin"]) <= 1e-3
             exact += 1
+        elif list(s) == list(rec["support"]):
+            assert abs(resid[t] - rec["resid_norm"]) <= RES_TOL * ynorm      # a near tie resolved as the plain rule does
         else:
             rep = oracle.incremental_block_omp(M, y, G, 1, k, prev[t], swaps, normalised,
                                                prev_coef=None if prev_coef is None else prev_coef[t].astype(np.float64),

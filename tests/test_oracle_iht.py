@@ -121,3 +121,25 @@ def test_decode_shape_quality_is_close_to_greedy_pursuit():
         ov_iht += len(set(a["support"]) & set(S[t]))
         ov_omp += len(set(b["support"]) & set(S[t]))
     assert ov_iht >= 0.9 * ov_omp
+
+
+def test_the_iteration_stops_once_the_fit_on_the_support_is_reached():
+    """Past convergence the line search is a quotient of two rounding errors; the iteration ends when the
+    gradient on the support has dropped to 1e-3 of its first value, so more iterations change nothing: same
+    support, and the margin is that of the last projection that was made (a well-defined number, the same
+    for every iteration count past convergence)."""
+    rng = np.random.default_rng(12)
+    G, m, k = 12, 72, 2
+    M = rng.standard_normal((m, G)) / np.sqrt(m)
+    S = np.array([3, 8])
+    y = M[:, S] @ np.array([1.5, -1.0]) + 0.05 * rng.standard_normal(m)
+    recs = [oracle.block_iht(M, y, G, 1, k, iters, True) for iters in (20, 21, 50, 400)]
+    for r in recs[1:]:
+        assert list(r["support"]) == list(recs[0]["support"]) == list(S)
+        assert r["margin"] == recs[0]["margin"]
+    # the margin that stands is a projection's gap, strictly inside (0, 1): off-support units have energy there
+    assert 0.0 < recs[0]["margin"] < 1.0
+    # an orthonormal dictionary converges in one step: the second iteration already stops
+    Q, _ = np.linalg.qr(rng.standard_normal((m, G)))
+    one, many = oracle.block_iht(Q, y, G, 1, k, 1, True), oracle.block_iht(Q, y, G, 1, k, 9, True)
+    assert list(one["support"]) == list(many["support"]) and one["margin"] == many["margin"]
