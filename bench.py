@@ -935,7 +935,8 @@ def main():
         # union of the supports of one call stands for all (same distribution)
         # share of the step's recoveries whose selection margin clears the exact-comparison filter (all
         # layers x tokens of the last batched recovery)
-        margin_pass = float((st.margin_all > 1e-3).float().mean())
+        # (same-step mode recovers layer by layer: the margins of the last layer's batch stand for the step)
+        margin_pass = float(((st.margin_all if args.recovery == "next-step" else st.margin) > 1e-3).float().mean())
         ffn_bytes = union_mean * 3 * c.b * c.d * 2
         # what a plain streaming read reaches on this device in this run (the K caches of the layers in turn)
         chk = torch.zeros((1,), dtype=torch.int32, device="cuda:0")
