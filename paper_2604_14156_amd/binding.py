@@ -169,7 +169,7 @@ class Context:
         return y
 
     def cs_recover_support(self, op, dct, k, y, support=None, coef=None, resid=None, margin=None,
-                           want_coef=True, want_resid=True):
+                           want_coef=True, want_resid=True, want_margin=True):
         B = y.shape[0]
         dev = y.device
         self._retain(dct)
@@ -179,14 +179,14 @@ class Context:
             coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
             resid = self._alloc((B,), torch.float32, dev)
-        if margin is None:
+        if margin is None and want_margin:
             margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                 _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 
     def cs_recover_support_multi(self, ops, dcts, k, y, support=None, coef=None, resid=None, margin=None,
-                                 want_coef=True, want_resid=True):
+                                 want_coef=True, want_resid=True, want_margin=True):
         """ops, dcts: sequences of n_ops operators / dictionaries (or ctypes arrays); y: [n_ops, B, m]."""
         n_ops, B = y.shape[0], y.shape[1]
         dev = y.device
@@ -203,14 +203,14 @@ class Context:
             coef = self._alloc((n_ops, B, k * rb), torch.float32, dev)
         if resid is None and want_resid:
             resid = self._alloc((n_ops, B), torch.float32, dev)
-        if margin is None:
+        if margin is None and want_margin:
             margin = self._alloc((n_ops, B), torch.float32, dev)
         self._check(self.lib.cs_recover_support_multi(self._h, n_ops, ops, dcts, k, _ptr(y), B,
                                                       _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 
     def cs_recover_support_iht(self, op, dct, k, iters, y, support=None, coef=None, resid=None, margin=None,
-                               want_coef=True, want_resid=True):
+                               want_coef=True, want_resid=True, want_margin=True):
         B = y.shape[0]
         dev = y.device
         self._retain(dct)
@@ -220,14 +220,14 @@ class Context:
             coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
             resid = self._alloc((B,), torch.float32, dev)
-        if margin is None:
+        if margin is None and want_margin:
             margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support_iht(self._h, ctypes.byref(op), ctypes.byref(dct), k, iters, _ptr(y), B,
                                                     _ptr(support), _ptr(coef), _ptr(resid), _ptr(margin)))
         return support, coef, resid, margin
 
     def cs_recover_support_inc(self, op, dct, k, y, prev_support, swaps, prev_coef=None, gamma=0.0,
-                               support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True):
+                               support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True, want_margin=True):
         B = y.shape[0]
         dev = y.device
         self._retain(dct)
@@ -237,7 +237,7 @@ class Context:
             coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
             resid = self._alloc((B,), torch.float32, dev)
-        if margin is None:
+        if margin is None and want_margin:
             margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support_inc(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                     _ptr(prev_support), _ptr(prev_coef), float(gamma), swaps,
@@ -250,7 +250,7 @@ class Context:
         return torch.zeros((B, words), dtype=torch.int32, device=device)
 
     def cs_recover_support_inc_carry(self, op, dct, k, y, prev_support, swaps, state,
-                                     support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True):
+                                     support=None, coef=None, resid=None, margin=None, want_coef=True, want_resid=True, want_margin=True):
         B = y.shape[0]
         dev = y.device
         self._retain(dct)
@@ -260,7 +260,7 @@ class Context:
             coef = self._alloc((B, k * dct.rb), torch.float32, dev)
         if resid is None and want_resid:
             resid = self._alloc((B,), torch.float32, dev)
-        if margin is None:
+        if margin is None and want_margin:
             margin = self._alloc((B,), torch.float32, dev)
         self._check(self.lib.cs_recover_support_inc_carry(self._h, ctypes.byref(op), ctypes.byref(dct), k, _ptr(y), B,
                                                           _ptr(prev_support), swaps, _ptr(state),

@@ -646,6 +646,48 @@ def test_more_sketches_than_compute_units_two_per_workgroup(cs, G, b, m, k, B, n
     assert torch.equal(supb[0], sup[0]) and torch.equal(supb[2:], sup[2:])
 
 
+def test_outputs_left_out_change_no_support(cs):
+    """coef, resid_norm and margin may each be NULL (Sec. 12: the dispatch needs the support alone): every
+    solver and every launch shape returns the same support whatever else is asked for."""
+    G, b, m, k, B = 100, 4, 72, 9, 6
+    seed = 8600
+    rng = wl.rng_for(seed)
+    n_ops = 50                                         # 300 sketches: two per workgroup in the batched call
+    ops, dcts, zs = [], [], []
+    for j in range(n_ops):
+        pi, psi = wl.make_profiles(rng, G, b)
+        z, S = wl.plant_usage(rng, pi, k, B, "laplace", 0.05)
+        pd = dev_f32(psi)
+        zs.append(z)
+        ops.append(binding.make_op(wl.RADEMACHER, seed, j, m, G * b))
+        dcts.append(binding.make_dict(pd, G, b, 1))
+        cs.cs_plan(ops[j], dcts[j], pd)
+    Y = cs.cs_sketch_multi(ops, dev_f32(np.stack(zs)))
+    full = cs.cs_recover_support_multi(ops, dcts, k, Y)
+    assert full[1] is not None and full[2] is not None and full[3] is not None
+    for wc, wr, wm in ((False, False, True), (False, False, False), (True, False, False), (False, True, False)):
+        got = cs.cs_recover_support_multi(ops, dcts, k, Y, want_coef=wc, want_resid=wr, want_margin=wm)
+        assert torch.equal(got[0], full[0])
+        assert (got[1] is None) == (not wc) and (got[2] is None) == (not wr) and (got[3] is None) == (not wm)
+        if wm:
+            assert torch.equal(got[3], full[3])
+    y0 = Y[0].clone()
+    one = cs.cs_recover_support(ops[0], dcts[0], k, y0)
+    assert torch.equal(one[0], full[0][0])
+    assert torch.equal(cs.cs_recover_support(ops[0], dcts[0], k, y0, want_coef=False, want_resid=False, want_margin=False)[0], one[0])
+    iht = cs.cs_recover_support_iht(ops[0], dcts[0], k, 6, y0)
+    assert torch.equal(cs.cs_recover_support_iht(ops[0], dcts[0], k, 6, y0, want_coef=False, want_resid=False, want_margin=False)[0], iht[0])
+    prev = one[0].clone()
+    inc = cs.cs_recover_support_inc(ops[0], dcts[0], k, y0, prev, 2)
+    assert torch.equal(cs.cs_recover_support_inc(ops[0], dcts[0], k, y0, prev, 2, want_coef=False, want_resid=False, want_margin=False)[0], inc[0])
+    st1, st2 = cs.cs_inc_state(B, k, "cuda:0"), cs.cs_inc_state(B, k, "cuda:0")
+    car = cs.cs_recover_support_inc_carry(ops[0], dcts[0], k, y0, prev, 2, st1)
+    assert torch.equal(cs.cs_recover_support_inc_carry(ops[0], dcts[0], k, y0, prev, 2, st2, want_coef=False, want_resid=False,
+                                                       want_margin=False)[0], car[0])
+    for j in range(n_ops):
+        cs.cs_plan_drop(ops[j], dcts[j])
+
+
 @pytest.mark.parametrize("m,n,B,n_ops", [(40, 1004, 19, 30), (256, 4096, 16, 8), (32, 128, 33, 40),
                                          (300, 2052, 20, 20), (512, 640, 5, 9), (520, 516, 16, 4)])
 def test_multi_operator_sketch_matrix_core_path(cs, m, n, B, n_ops):
